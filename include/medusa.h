@@ -1,0 +1,201 @@
+/*
+ * medusa.h -- C ABI of the MI355X (gfx950) hot path of one Medusa verification step
+ * (Cai et al., "Medusa: Simple LLM Inference Acceleration Framework with Multiple
+ * Decoding Heads", arXiv 2401.10774).
+ *
+ * One decoding step (Sec. 2, opening paragraph; Fig. 1) is
+ *   (1) candidate generation : medusa_heads, medusa_topk_tree      (Sec. 2.1.1, 2.1.2)
+ *   (2) candidate processing : tree_attention (+ medusa_heads with w1 == NULL for the
+ *                              original model's logits at every tree token)  (Sec. 2.1.2)
+ *   (3) candidate acceptance : medusa_accept                        (Sec. 2.3.1)
+ *   carry-over               : kv_commit                            (Fig. 1 caption)
+ *
+ * Conventions shared by every call
+ *   - Every tensor pointer is DEVICE memory owned by the caller, dense, innermost
+ *     dimension contiguous, in the layout written next to the argument.  The library
+ *     never allocates, frees or retains caller memory.  The only object it owns is
+ *     medusa_tree_t (small host + device tables).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     enqueue their kernels on it and return without synchronising.
+ *   - Return value: MEDUSA_OK (0) or a negative medusa_status_t.  Arguments are checked
+ *     on the host before anything is launched; on error nothing is enqueued.  Contents of
+ *     device arrays (e.g. prefix_len) cannot be checked on the host: the kernels clamp
+ *     every index they derive from device data, so bad contents give wrong rows, never an
+ *     out-of-bounds access.
+ *   - dtype is the storage type of activations, weights and KV: MEDUSA_F32 or
+ *     MEDUSA_BF16.  Accumulation is always fp32; logits are always fp32.
+ *   - Ties in arg-max / top-k: larger value first, then lower token id.  NaN logits are
+ *     outside the contract.
+ */
+#ifndef MEDUSA_H_
+#define MEDUSA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MEDUSA_OK = 0,
+  MEDUSA_EINVAL = -1,        /* null pointer, non-positive size, inconsistent arguments */
+  MEDUSA_EUNSUPPORTED = -2,  /* a size outside the supported range (see each call)      */
+  MEDUSA_EWORKSPACE = -3,    /* workspace missing or too small                           */
+  MEDUSA_EHIP = -4           /* a HIP runtime call failed                                */
+} medusa_status_t;
+
+typedef enum { MEDUSA_F32 = 0, MEDUSA_BF16 = 1 } medusa_dtype_t;
+typedef enum { MEDUSA_GREEDY = 0, MEDUSA_TYPICAL = 1 } medusa_accept_mode_t;
+
+#define MEDUSA_MAX_TREE_TOKENS 128 /* T = candidates + root                              */
+#define MEDUSA_MAX_HEADS 8         /* K = tree depth                                     */
+#define MEDUSA_MAX_TOPK 16         /* S_k = 1 + largest rank used at level k             */
+
+typedef struct medusa_tree medusa_tree_t;
+typedef void* medusa_stream_t; /* a hipStream_t */
+
+/* Static text for a status code; never freed. */
+const char* medusa_status_string(int status);
+
+/* ----------------------------------------------------------------------------------
+ * Candidate tree (Sec. 2.1.2, Fig. 2; sparse trees of Sec. 2.3.3 via explicit nodes).
+ *
+ * A node is the tuple of ranks (i_1..i_k): the i_j-th best prediction of Medusa head j
+ * at level j.  Node 0 is the root (the original LM head's own next token); the other
+ * nodes are numbered depth-major and, inside a depth, lexicographically by rank tuple.
+ * T = 1 + number of candidate nodes.  Limits: T <= 128, K <= 8, every rank < 16.
+ *
+ * medusa_tree_create_cartesian: level k has ranks 0..branching[k-1]-1 under every
+ *   level-(k-1) node, i.e. sum_k prod_{i<=k} s_i candidate nodes (Sec. 2.1.2).
+ * medusa_tree_create_nodes: `ranks` is a host array [n_nodes][K] of rank tuples padded
+ *   with -1; the set must be prefix-closed (every node's parent is present) and free of
+ *   duplicates.  K is the padded tuple width and must equal the deepest tuple's length.
+ * Both build the tables on the host, upload a device copy, and return a handle in *out.
+ * The handle is immutable and may be used from any stream; destroy it only after all
+ * work that uses it has completed.  A tree belongs to the device that was current when
+ * it was created.
+ * -------------------------------------------------------------------------------- */
+int medusa_tree_create_cartesian(const int32_t* branching /* host [K] */, int K, medusa_tree_t** out);
+int medusa_tree_create_nodes(const int32_t* ranks /* host [n_nodes][K] */, int n_nodes, int K,
+                             medusa_tree_t** out);
+int medusa_tree_destroy(medusa_tree_t* tree);
+
+/* Sizes: T tokens, K levels, n_leaves candidates (root-to-leaf paths), S = max_k S_k,
+ * topk_per_head[k-1] = S_k (host array [K], may be NULL).  Any out pointer may be NULL. */
+int medusa_tree_query(const medusa_tree_t* tree, int32_t* T, int32_t* K, int32_t* n_leaves,
+                      int32_t* S, int32_t* topk_per_head);
+
+/* Copies the host tables into caller HOST arrays (any may be NULL):
+ *   parent[T] (-1 for the root), depth[T] (root 0), rank[T] (-1 for the root),
+ *   token_src[T]: index into the per-sequence list [root, top-S_1 of head 1, top-S_2 of
+ *                 head 2, ...] that supplies the node's token,
+ *   anc_mask[T][2]: bit u of the 128-bit row t (word u/64, bit u%64) is set iff u is an
+ *                 ancestor of t or u == t  -- the tree part of the attention mask,
+ *   paths[n_leaves][K+1]: root-to-leaf node lists in lexicographic order of the leaves'
+ *                 rank tuples, -1 padded. */
+int medusa_tree_tables(const medusa_tree_t* tree, int32_t* parent, int32_t* depth, int32_t* rank,
+                       int32_t* token_src, uint64_t* anc_mask, int32_t* paths);
+
+/* ----------------------------------------------------------------------------------
+ * medusa_heads (Sec. 2.1.1):  logits[m,k,:] = W2_k . ( SiLU(W1_k . h_m) + h_m )
+ *   hidden  [M, d]        dtype   rows h_m
+ *   w1      [K, d, d]     dtype   out x in; NULL => no residual block: logits = W2_k . h_m
+ *                                 (K = 1 with w2 = the LM head gives the original model's
+ *                                  logits, used for the M = B*T tree tokens in step (2))
+ *   w2      [K, V, d]     dtype   out x in
+ *   resid   [M, K, d]     dtype   workspace written by the call: SiLU(W1 h) + h rounded
+ *                                 once to dtype; may be NULL iff w1 == NULL
+ *   logits  [M, K, V]     fp32    output
+ * Limits: 1 <= M <= 4096, 1 <= K <= 8, d a multiple of 8 (bf16: of 64), d <= 16384, V >= 1.
+ * -------------------------------------------------------------------------------- */
+int medusa_heads(const void* hidden, const void* w1, const void* w2, void* resid, float* logits,
+                 int M, int d, int V, int K, medusa_dtype_t dtype, medusa_stream_t stream);
+
+/* ----------------------------------------------------------------------------------
+ * medusa_topk_tree (Sec. 2.1.2): per sequence, the top-S_k tokens of head k (sorted, best
+ * first) and the root token = arg-max of the LM head (Sec. 2.3.1: the first token is
+ * greedy), gathered into the tree:  tree_tokens[b,t] = list_b[token_src[t]],
+ * position_ids[b,t] = prefix_len[b] + depth[t]  (Fig. 2 caption).
+ *   medusa_logits [B, K_heads, V] fp32   K_heads >= tree K; heads beyond the tree's depth unused
+ *   lm_logits     [B, V]          fp32
+ *   prefix_len    [B]             int32
+ *   topk_ids      [B, K, S]       int32  out, entries beyond S_k are -1
+ *   tree_tokens   [B, T]          int32  out
+ *   position_ids  [B, T]          int32  out
+ *   workspace: medusa_topk_tree_workspace_bytes(B, K) bytes of device scratch (per-chunk
+ *   candidate lists); contents undefined before and after.  8-byte aligned.
+ * Limits: V >= S (every S_k <= V), B >= 1.
+ * -------------------------------------------------------------------------------- */
+size_t medusa_topk_tree_workspace_bytes(int B, int K);
+int medusa_topk_tree(const float* medusa_logits, const float* lm_logits, const medusa_tree_t* tree,
+                     const int32_t* prefix_len, int B, int V, int K_heads, int32_t* topk_ids,
+                     int32_t* tree_tokens, int32_t* position_ids, void* workspace, size_t workspace_bytes,
+                     medusa_stream_t stream);
+
+/* ----------------------------------------------------------------------------------
+ * tree_attention (Sec. 2.1.2): for every sequence b, query head g, tree token t
+ *   out[b,g,t,:] = softmax_j( scale * q[b,g,t,:] . key_j ) . value_j
+ * over the keys  { cache rows j < prefix_len[b] }  U  { tree rows u : bit u of
+ * anc_mask[t] }: a tree token sees the whole prefix and, of the tree, only its own
+ * continuation (ancestors and itself).  Query head g reads KV head g / (Hq/Hkv).
+ *   q               [B, Hq, T, D]      dtype
+ *   k_tree, v_tree  [B, Hkv, T, D]     dtype   this layer's K/V of the tree tokens
+ *   k_cache,v_cache [B, Hkv, Lcap, D]  dtype   one layer of the cache (never written here)
+ *   prefix_len      [B] int32                  values are clamped to [0, Lcap]
+ *   out             [B, Hq, T, D]      dtype
+ *   workspace: tree_attention_workspace_bytes(...) bytes of device scratch (split
+ *   partials); contents undefined before and after.  Must be 256-byte aligned.
+ * Limits: D in {64, 128}; Hq a multiple of Hkv; T from the tree (<= 128).
+ * -------------------------------------------------------------------------------- */
+size_t tree_attention_workspace_bytes(int B, int Hq, int Hkv, int T, int D, int Lcap);
+int tree_attention(const void* q, const void* k_tree, const void* v_tree, const void* k_cache,
+                   const void* v_cache, const int32_t* prefix_len, const medusa_tree_t* tree, void* out,
+                   int B, int Hq, int Hkv, int D, int Lcap, float scale, medusa_dtype_t dtype,
+                   void* workspace, size_t workspace_bytes, medusa_stream_t stream);
+
+/* ----------------------------------------------------------------------------------
+ * medusa_accept (Sec. 2.3.1): node t (t >= 1) passes its test on the original model's
+ * row of its parent:
+ *   greedy : tree_tokens[b,t] == argmax logits[b,parent[t],:]
+ *   typical: p = softmax(logits[b,parent[t],:] / temperature), H = -sum p ln p,
+ *            p[tree_tokens[b,t]] > min(eps, delta * exp(-H))            (strict)
+ * The root always passes.  A node is accepted iff it and all its ancestors pass.  The
+ * result is the accepted node of greatest depth (first in candidate order on ties, which
+ * is the lowest node index at that depth); its root path is the accepted prefix.
+ *   logits          [B, T, V] fp32    original-model logits at every tree token
+ *   tree_tokens     [B, T]    int32
+ *   accept_len      [B]       int32 out: 1..K+1 (root included)
+ *   best_node       [B]       int32 out: last accepted node (row to gather the next hidden state from)
+ *   path_nodes      [B, K+1]  int32 out: accepted nodes in depth order, -1 padded
+ *   accepted_tokens [B, K+1]  int32 out: their tokens, -1 padded
+ *   next_root       [B]       int32 out: argmax logits[b,best_node,:], the next step's root
+ *   workspace: medusa_accept_workspace_bytes(B, T, V) bytes of device scratch.
+ * temperature > 0 is required in typical mode and ignored in greedy mode.
+ * -------------------------------------------------------------------------------- */
+size_t medusa_accept_workspace_bytes(int B, int T, int V);
+int medusa_accept(const float* logits, const int32_t* tree_tokens, const medusa_tree_t* tree, int B, int V,
+                  medusa_accept_mode_t mode, float temperature, float eps, float delta,
+                  int32_t* accept_len, int32_t* best_node, int32_t* path_nodes, int32_t* accepted_tokens,
+                  int32_t* next_root, void* workspace, size_t workspace_bytes, medusa_stream_t stream);
+
+/* ----------------------------------------------------------------------------------
+ * kv_commit (Fig. 1 caption: the accepted prefix is the context of the next step): for
+ * every layer l, KV head h and j < accept_len[b]
+ *   cache[l,b,h,prefix_len[b]+j,:] = tree[l,b,h,path_nodes[b,j],:]      (K and V)
+ * then prefix_len[b] += accept_len[b].  Rows that would fall at or beyond Lcap are
+ * dropped (and prefix_len saturates at Lcap): capacity is the caller's contract.
+ *   k_cache, v_cache [NL, B, Hkv, Lcap, D] dtype  in/out
+ *   k_tree, v_tree   [NL, B, Hkv, T, D]    dtype
+ *   path_nodes       [B, path_stride] int32, accept_len [B] int32 (from medusa_accept)
+ *   prefix_len       [B] int32 in/out
+ * Limits: D * sizeof(dtype) a multiple of 16.
+ * -------------------------------------------------------------------------------- */
+int kv_commit(void* k_cache, void* v_cache, const void* k_tree, const void* v_tree,
+              const int32_t* path_nodes, int path_stride, const int32_t* accept_len, int32_t* prefix_len,
+              int NL, int B, int Hkv, int T, int D, int Lcap, medusa_dtype_t dtype, medusa_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MEDUSA_H_ */

@@ -1,0 +1,304 @@
+"""ctypes binding of libmedusa_hip.so: same names as include/medusa.h, argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  PyTorch is used for device memory
+(tensors own the buffers, `data_ptr()` is what crosses the boundary) and for the current
+stream.  There is no fallback: if the library is missing or a call fails, an exception is
+raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmedusa_hip.so")
+_lib_handle = None
+
+MEDUSA_F32, MEDUSA_BF16 = 0, 1
+MEDUSA_GREEDY, MEDUSA_TYPICAL = 0, 1
+
+EXPORTED_SYMBOLS = (
+    "medusa_status_string", "medusa_tree_create_cartesian", "medusa_tree_create_nodes", "medusa_tree_destroy",
+    "medusa_tree_query", "medusa_tree_tables", "medusa_heads", "medusa_topk_tree_workspace_bytes",
+    "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "medusa_accept_workspace_bytes",
+    "medusa_accept", "kv_commit",
+)
+
+
+class MedusaError(RuntimeError):
+    pass
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib_handle
+    if _lib_handle is None:
+        if not os.path.exists(_LIB_PATH):
+            raise MedusaError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2401_10774_amd.build` "
+                "(there is no CPU or PyTorch fallback)")
+        L = ctypes.CDLL(_LIB_PATH)
+        c_int, c_void_p, c_size_t, c_float = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_float
+        L.medusa_status_string.restype = ctypes.c_char_p
+        L.medusa_status_string.argtypes = [c_int]
+        L.medusa_tree_create_cartesian.argtypes = [c_void_p, c_int, ctypes.POINTER(c_void_p)]
+        L.medusa_tree_create_nodes.argtypes = [c_void_p, c_int, c_int, ctypes.POINTER(c_void_p)]
+        L.medusa_tree_destroy.argtypes = [c_void_p]
+        L.medusa_tree_query.argtypes = [c_void_p] + [c_void_p] * 5
+        L.medusa_tree_tables.argtypes = [c_void_p] + [c_void_p] * 6
+        L.medusa_heads.argtypes = [c_void_p] * 5 + [c_int] * 5 + [c_void_p]
+        L.medusa_topk_tree_workspace_bytes.restype = c_size_t
+        L.medusa_topk_tree_workspace_bytes.argtypes = [c_int, c_int]
+        L.medusa_topk_tree.argtypes = [c_void_p] * 4 + [c_int] * 3 + [c_void_p] * 4 + [c_size_t, c_void_p]
+        L.tree_attention_workspace_bytes.restype = c_size_t
+        L.tree_attention_workspace_bytes.argtypes = [c_int] * 6
+        L.tree_attention.argtypes = [c_void_p] * 8 + [c_int] * 5 + [c_float, c_int, c_void_p, c_size_t, c_void_p]
+        L.medusa_accept_workspace_bytes.restype = c_size_t
+        L.medusa_accept_workspace_bytes.argtypes = [c_int] * 3
+        L.medusa_accept.argtypes = ([c_void_p] * 3 + [c_int] * 3 + [c_float] * 3 + [c_void_p] * 5 +
+                                    [c_void_p, c_size_t, c_void_p])
+        L.kv_commit.argtypes = ([c_void_p] * 5 + [c_int, c_void_p, c_void_p] + [c_int] * 6 + [c_int, c_void_p])
+        for name in EXPORTED_SYMBOLS:
+            fn = getattr(L, name)
+            if fn.restype is ctypes.c_int or fn.restype is None:
+                fn.restype = c_int
+        _lib_handle = L
+    return _lib_handle
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        msg = lib().medusa_status_string(status).decode()
+        raise MedusaError(f"{what} failed: {msg} ({status})")
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return MEDUSA_F32
+    if t.dtype == torch.bfloat16:
+        return MEDUSA_BF16
+    raise MedusaError(f"unsupported storage dtype {t.dtype}")
+
+
+def _dev(t: Optional[torch.Tensor], name: str, dtype=None, shape: Optional[Sequence[int]] = None) -> Optional[int]:
+    """Pointer of a device tensor after checking residency, density, dtype and shape."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise MedusaError(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise MedusaError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise MedusaError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise MedusaError(f"{name} must have shape {tuple(shape)}, got {tuple(t.shape)}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def _scratch(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+class MedusaTree:
+    """Handle of a candidate tree (Sec. 2.1.2) plus host copies of its tables."""
+
+    def __init__(self, branching: Optional[Sequence[int]] = None, nodes: Optional[Sequence[Sequence[int]]] = None):
+        L = lib()
+        handle = ctypes.c_void_p()
+        if (branching is None) == (nodes is None):
+            raise MedusaError("give exactly one of branching / nodes")
+        if branching is not None:
+            arr = np.ascontiguousarray(branching, dtype=np.int32)
+            _check(L.medusa_tree_create_cartesian(arr.ctypes.data, int(arr.size), ctypes.byref(handle)),
+                   "medusa_tree_create_cartesian")
+        else:
+            K = max((len(n) for n in nodes), default=0)
+            arr = np.full((len(nodes), max(K, 1)), -1, np.int32)
+            for i, n in enumerate(nodes):
+                arr[i, :len(n)] = n
+            _check(L.medusa_tree_create_nodes(arr.ctypes.data, len(nodes), K, ctypes.byref(handle)),
+                   "medusa_tree_create_nodes")
+        self._h = handle
+        T, K, nl, S = (ctypes.c_int32() for _ in range(4))
+        topk = np.zeros(8, np.int32)
+        _check(L.medusa_tree_query(self._h, ctypes.addressof(T), ctypes.addressof(K), ctypes.addressof(nl),
+                                   ctypes.addressof(S), topk.ctypes.data), "medusa_tree_query")
+        self.T, self.K, self.n_leaves, self.S = T.value, K.value, nl.value, S.value
+        self.topk_per_head = topk[:self.K].copy()
+        self.parent = np.zeros(self.T, np.int32)
+        self.depth = np.zeros(self.T, np.int32)
+        self.rank = np.zeros(self.T, np.int32)
+        self.token_src = np.zeros(self.T, np.int32)
+        self.anc_mask = np.zeros((self.T, 2), np.uint64)
+        self.paths = np.zeros((self.n_leaves, self.K + 1), np.int32)
+        _check(L.medusa_tree_tables(self._h, self.parent.ctypes.data, self.depth.ctypes.data, self.rank.ctypes.data,
+                                    self.token_src.ctypes.data, self.anc_mask.ctypes.data, self.paths.ctypes.data),
+               "medusa_tree_tables")
+
+    @property
+    def handle(self):
+        return self._h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().medusa_tree_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def medusa_heads(hidden: torch.Tensor, w1: Optional[torch.Tensor], w2: torch.Tensor,
+                 resid: Optional[torch.Tensor] = None, logits: Optional[torch.Tensor] = None, stream=None):
+    """logits[m,k,:] = W2_k (SiLU(W1_k h_m) + h_m); w1=None gives W2_k h_m.  Returns (logits, resid)."""
+    M, d = hidden.shape
+    K, V, _ = w2.shape
+    code = _dtype_code(hidden)
+    _dev(hidden, "hidden", shape=(M, d))
+    _dev(w2, "w2", dtype=hidden.dtype, shape=(K, V, d))
+    if w1 is not None:
+        _dev(w1, "w1", dtype=hidden.dtype, shape=(K, d, d))
+        if resid is None:
+            resid = torch.empty((M, K, d), dtype=hidden.dtype, device=hidden.device)
+        _dev(resid, "resid", dtype=hidden.dtype, shape=(M, K, d))
+    if logits is None:
+        logits = torch.empty((M, K, V), dtype=torch.float32, device=hidden.device)
+    _dev(logits, "logits", dtype=torch.float32, shape=(M, K, V))
+    _check(lib().medusa_heads(hidden.data_ptr(), None if w1 is None else w1.data_ptr(), w2.data_ptr(),
+                              None if w1 is None else resid.data_ptr(), logits.data_ptr(), M, d, V, K, code,
+                              _stream(stream)), "medusa_heads")
+    return logits, resid
+
+
+def medusa_topk_tree(medusa_logits: torch.Tensor, lm_logits: torch.Tensor, tree: MedusaTree, prefix_len: torch.Tensor,
+                     topk_ids=None, tree_tokens=None, position_ids=None, workspace=None, stream=None):
+    """Returns (topk_ids [B,K,S], tree_tokens [B,T], position_ids [B,T]), all int32."""
+    B, V = lm_logits.shape
+    K_heads = medusa_logits.shape[1]
+    dev = lm_logits.device
+    _dev(medusa_logits, "medusa_logits", dtype=torch.float32, shape=(B, K_heads, V))
+    _dev(lm_logits, "lm_logits", dtype=torch.float32)
+    _dev(prefix_len, "prefix_len", dtype=torch.int32, shape=(B,))
+    if topk_ids is None:
+        topk_ids = torch.empty((B, tree.K, max(tree.S, 1)), dtype=torch.int32, device=dev)
+    if tree_tokens is None:
+        tree_tokens = torch.empty((B, tree.T), dtype=torch.int32, device=dev)
+    if position_ids is None:
+        position_ids = torch.empty((B, tree.T), dtype=torch.int32, device=dev)
+    _dev(topk_ids, "topk_ids", dtype=torch.int32)
+    _dev(tree_tokens, "tree_tokens", dtype=torch.int32, shape=(B, tree.T))
+    _dev(position_ids, "position_ids", dtype=torch.int32, shape=(B, tree.T))
+    if workspace is None:
+        workspace = _scratch(lib().medusa_topk_tree_workspace_bytes(B, tree.K), dev)
+    _dev(workspace, "workspace")
+    _check(lib().medusa_topk_tree(medusa_logits.data_ptr(), lm_logits.data_ptr(), tree.handle, prefix_len.data_ptr(),
+                                  B, V, K_heads, topk_ids.data_ptr(), tree_tokens.data_ptr(), position_ids.data_ptr(),
+                                  workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "medusa_topk_tree")
+    return topk_ids, tree_tokens, position_ids
+
+
+def tree_attention_workspace_bytes(B: int, Hq: int, Hkv: int, T: int, D: int, Lcap: int) -> int:
+    return int(lib().tree_attention_workspace_bytes(B, Hq, Hkv, T, D, Lcap))
+
+
+def tree_attention(q: torch.Tensor, k_tree: torch.Tensor, v_tree: torch.Tensor, k_cache: torch.Tensor,
+                   v_cache: torch.Tensor, prefix_len: torch.Tensor, tree: MedusaTree, scale: float,
+                   out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """Tree-masked attention of the T tree tokens over one layer's cache.  Returns out [B,Hq,T,D]."""
+    B, Hq, T, D = q.shape
+    Hkv, Lcap = k_cache.shape[1], k_cache.shape[2]
+    if T != tree.T:
+        raise MedusaError(f"q has {T} tree tokens, the tree has {tree.T}")
+    code = _dtype_code(q)
+    _dev(q, "q")
+    _dev(k_tree, "k_tree", dtype=q.dtype, shape=(B, Hkv, T, D))
+    _dev(v_tree, "v_tree", dtype=q.dtype, shape=(B, Hkv, T, D))
+    _dev(k_cache, "k_cache", dtype=q.dtype, shape=(B, Hkv, Lcap, D))
+    _dev(v_cache, "v_cache", dtype=q.dtype, shape=(B, Hkv, Lcap, D))
+    _dev(prefix_len, "prefix_len", dtype=torch.int32, shape=(B,))
+    if out is None:
+        out = torch.empty_like(q)
+    _dev(out, "out", dtype=q.dtype, shape=(B, Hq, T, D))
+    if workspace is None:
+        workspace = _scratch(tree_attention_workspace_bytes(B, Hq, Hkv, T, D, Lcap), q.device)
+    _dev(workspace, "workspace")
+    _check(lib().tree_attention(q.data_ptr(), k_tree.data_ptr(), v_tree.data_ptr(), k_cache.data_ptr(),
+                                v_cache.data_ptr(), prefix_len.data_ptr(), tree.handle, out.data_ptr(), B, Hq, Hkv, D,
+                                Lcap, float(scale), code, workspace.data_ptr(),
+                                workspace.numel() * workspace.element_size(), _stream(stream)), "tree_attention")
+    return out
+
+
+def medusa_accept_workspace_bytes(B: int, T: int, V: int) -> int:
+    return int(lib().medusa_accept_workspace_bytes(B, T, V))
+
+
+def medusa_accept(logits: torch.Tensor, tree_tokens: torch.Tensor, tree: MedusaTree, mode: str = "greedy",
+                  temperature: float = 1.0, eps: float = 0.0, delta: float = 0.0, outputs=None, workspace=None,
+                  stream=None):
+    """Returns (accept_len [B], best_node [B], path_nodes [B,K+1], accepted_tokens [B,K+1], next_root [B])."""
+    B, T, V = logits.shape
+    if T != tree.T:
+        raise MedusaError(f"logits have {T} rows per sequence, the tree has {tree.T}")
+    dev = logits.device
+    _dev(logits, "logits", dtype=torch.float32)
+    _dev(tree_tokens, "tree_tokens", dtype=torch.int32, shape=(B, T))
+    if outputs is None:
+        i32 = dict(dtype=torch.int32, device=dev)
+        outputs = (torch.empty(B, **i32), torch.empty(B, **i32), torch.empty((B, tree.K + 1), **i32),
+                   torch.empty((B, tree.K + 1), **i32), torch.empty(B, **i32))
+    accept_len, best_node, path_nodes, accepted_tokens, next_root = outputs
+    _dev(accept_len, "accept_len", dtype=torch.int32, shape=(B,))
+    _dev(best_node, "best_node", dtype=torch.int32, shape=(B,))
+    _dev(path_nodes, "path_nodes", dtype=torch.int32, shape=(B, tree.K + 1))
+    _dev(accepted_tokens, "accepted_tokens", dtype=torch.int32, shape=(B, tree.K + 1))
+    _dev(next_root, "next_root", dtype=torch.int32, shape=(B,))
+    if workspace is None:
+        workspace = _scratch(medusa_accept_workspace_bytes(B, T, V), dev)
+    _dev(workspace, "workspace")
+    code = {"greedy": MEDUSA_GREEDY, "typical": MEDUSA_TYPICAL}[mode]
+    _check(lib().medusa_accept(logits.data_ptr(), tree_tokens.data_ptr(), tree.handle, B, V, code, float(temperature),
+                               float(eps), float(delta), accept_len.data_ptr(), best_node.data_ptr(),
+                               path_nodes.data_ptr(), accepted_tokens.data_ptr(), next_root.data_ptr(),
+                               workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "medusa_accept")
+    return outputs
+
+
+def kv_commit(k_cache: torch.Tensor, v_cache: torch.Tensor, k_tree: torch.Tensor, v_tree: torch.Tensor,
+              path_nodes: torch.Tensor, accept_len: torch.Tensor, prefix_len: torch.Tensor, stream=None) -> None:
+    """Append the accepted path's K/V rows to every cache layer and advance prefix_len, in place."""
+    NL, B, Hkv, Lcap, D = k_cache.shape
+    T = k_tree.shape[3]
+    code = _dtype_code(k_cache)
+    _dev(k_cache, "k_cache")
+    _dev(v_cache, "v_cache", dtype=k_cache.dtype, shape=(NL, B, Hkv, Lcap, D))
+    _dev(k_tree, "k_tree", dtype=k_cache.dtype, shape=(NL, B, Hkv, T, D))
+    _dev(v_tree, "v_tree", dtype=k_cache.dtype, shape=(NL, B, Hkv, T, D))
+    _dev(path_nodes, "path_nodes", dtype=torch.int32)
+    if path_nodes.dim() != 2 or path_nodes.shape[0] != B:
+        raise MedusaError("path_nodes must be [B, K+1]")
+    _dev(accept_len, "accept_len", dtype=torch.int32, shape=(B,))
+    _dev(prefix_len, "prefix_len", dtype=torch.int32, shape=(B,))
+    _check(lib().kv_commit(k_cache.data_ptr(), v_cache.data_ptr(), k_tree.data_ptr(), v_tree.data_ptr(),
+                           path_nodes.data_ptr(), int(path_nodes.shape[1]), accept_len.data_ptr(),
+                           prefix_len.data_ptr(), NL, B, Hkv, T, D, Lcap, code, _stream(stream)), "kv_commit")

@@ -1,0 +1,216 @@
+// medusa_accept (Sec. 2.3.1 of the Medusa paper): greedy or typical acceptance of the tree's
+// candidates and selection of the longest accepted prefix.
+//
+// Stage 1 is the only pass over the B*T*V logits: each (row, chunk) workgroup reduces its slice
+// to an arg-max key and, in typical mode, the soft-max statistics
+//   m = max z,  S = sum exp(z - m),  U = sum (z - m) exp(z - m),   z = logit / temperature,
+// from which  ln p(x) = z_x - m - ln S  and the entropy  H = ln S - U / S.
+// Stage 2 (one workgroup per sequence, one thread per node) merges the chunks, evaluates every
+// node's test on its parent's row, turns the pass bits into two 64-bit ballots and decides
+// acceptance of node t as  (anc_mask[t] & ~pass) == 0  -- no pointer chasing.  The winner is
+// the accepted node of greatest depth and, at equal depth, lowest index.
+#include <math.h>
+
+#include "common.hpp"
+
+namespace {
+
+constexpr int kAccChunks = 4;
+
+struct RowPart {       // one per (row, chunk)
+  uint64_t key;        // rank_key of the chunk's best (logit, id)
+  float m, S, U;
+  float pad;
+};
+
+__device__ __forceinline__ void stats_merge(float& m, float& S, float& U, float m2, float S2, float U2) {
+  const float mn = fmaxf(m, m2);
+  const float c1 = S > 0.f ? expf(m - mn) : 0.f, d1 = S > 0.f ? m - mn : 0.f;
+  const float c2 = S2 > 0.f ? expf(m2 - mn) : 0.f, d2 = S2 > 0.f ? m2 - mn : 0.f;
+  U = c1 * (U + d1 * S) + c2 * (U2 + d2 * S2);
+  S = c1 * S + c2 * S2;
+  m = mn;
+}
+
+template <bool TYPICAL>
+__global__ __launch_bounds__(256) void row_stats_kernel(const float* __restrict__ logits, int V, float inv_temp,
+                                                        RowPart* __restrict__ part) {
+  __shared__ uint64_t s_key[4];
+  __shared__ float s_m[4], s_S[4], s_U[4];
+  const size_t row = blockIdx.y;
+  const float* src = logits + row * V;
+  const int per = ceil_div(V, kAccChunks);
+  const int lo = blockIdx.x * per, hi = min(V, lo + per);
+  uint64_t key = 0;
+  float m = -INFINITY, S = 0.f, U = 0.f;
+  for (int i = lo + threadIdx.x; i < hi; i += 256) {
+    const float x = src[i];
+    const uint64_t k2 = rank_key(x, (uint32_t)i);
+    key = k2 > key ? k2 : key;
+    if (TYPICAL) {
+      const float z = x * inv_temp;
+      if (z > m) {                       // new running maximum: rescale what has been summed
+        const float c = S > 0.f ? expf(m - z) : 0.f;
+        U = S > 0.f ? c * (U + (m - z) * S) : 0.f;
+        S = c * S + 1.f;                 // the new element contributes exp(0) = 1 and (z - z) * 1 = 0
+        m = z;
+      } else {
+        const float e = expf(z - m);
+        S += e;
+        U += (z - m) * e;
+      }
+    }
+  }
+  key = wave_max_u64(key);
+  if (TYPICAL) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float m2 = __shfl_xor(m, o, kWave), S2 = __shfl_xor(S, o, kWave), U2 = __shfl_xor(U, o, kWave);
+      stats_merge(m, S, U, m2, S2, U2);
+    }
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) {
+    s_key[wave] = key;
+    s_m[wave] = m;
+    s_S[wave] = S;
+    s_U[wave] = U;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) {
+      key = s_key[w] > key ? s_key[w] : key;
+      if (TYPICAL) stats_merge(m, S, U, s_m[w], s_S[w], s_U[w]);
+    }
+    RowPart p;
+    p.key = key;
+    p.m = m;
+    p.S = S;
+    p.U = U;
+    p.pad = 0.f;
+    part[row * kAccChunks + blockIdx.x] = p;
+  }
+}
+
+template <bool TYPICAL>
+__global__ __launch_bounds__(128) void accept_finalize_kernel(const float* __restrict__ logits,
+                                                              const int32_t* __restrict__ tree_tokens,
+                                                              const TreeTables* __restrict__ tree,
+                                                              const RowPart* __restrict__ part, int V, float inv_temp,
+                                                              float eps, float delta, int32_t* __restrict__ accept_len,
+                                                              int32_t* __restrict__ best_node, int32_t* __restrict__ path_nodes,
+                                                              int32_t* __restrict__ accepted_tokens,
+                                                              int32_t* __restrict__ next_root) {
+  __shared__ int32_t s_arg[MEDUSA_MAX_TREE_TOKENS];
+  __shared__ float s_m[MEDUSA_MAX_TREE_TOKENS], s_lnS[MEDUSA_MAX_TREE_TOKENS], s_H[MEDUSA_MAX_TREE_TOKENS];
+  __shared__ uint64_t s_pass[2];
+  __shared__ uint32_t s_best[2];
+  const int b = blockIdx.x, t = threadIdx.x;
+  const int T = tree->T, K = tree->K;
+  const int lane = t & 63, wave = t >> 6;
+  if (t < T) {
+    const RowPart* p = part + ((size_t)b * T + t) * kAccChunks;
+    uint64_t key = p[0].key;
+    float m = p[0].m, S = p[0].S, U = p[0].U;
+    for (int c = 1; c < kAccChunks; ++c) {
+      key = p[c].key > key ? p[c].key : key;
+      if (TYPICAL) stats_merge(m, S, U, p[c].m, p[c].S, p[c].U);
+    }
+    s_arg[t] = (int32_t)rank_key_id(key);
+    if (TYPICAL) {
+      const float lnS = logf(S);
+      s_m[t] = m;
+      s_lnS[t] = lnS;
+      s_H[t] = lnS - U / S;
+    }
+  }
+  __syncthreads();
+  bool pass = false;
+  if (t == 0) pass = true;                                   // the root is accepted unconditionally
+  else if (t < T) {
+    const int par = tree->parent[t];
+    const int tok = tree_tokens[(size_t)b * T + t];
+    if (!TYPICAL) {
+      pass = tok == s_arg[par];
+    } else if (tok >= 0 && tok < V) {
+      const float z = logits[((size_t)b * T + par) * V + tok] * inv_temp;
+      const float p_tok = expf(z - s_m[par] - s_lnS[par]);
+      const float thr = fminf(eps, delta * expf(-s_H[par]));
+      pass = p_tok > thr;
+    }
+  }
+  const uint64_t bal = __ballot(pass);
+  if (lane == 0) s_pass[wave] = bal;
+  __syncthreads();
+  const uint64_t fail0 = ~s_pass[0], fail1 = ~s_pass[1];
+  uint32_t score = 0;
+  if (t < T && (tree->anc_mask[t][0] & fail0) == 0 && (tree->anc_mask[t][1] & fail1) == 0)
+    score = ((uint32_t)(tree->depth[t] + 1) << 8) | (uint32_t)(255 - t);   // deeper first, then lower index
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) score = max(score, (uint32_t)__shfl_xor((int)score, o, kWave));
+  if (lane == 0) s_best[wave] = score;
+  __syncthreads();
+  score = max(s_best[0], s_best[1]);
+  const int best = 255 - (int)(score & 255u);
+  const int alen = (int)(score >> 8);
+  if (t == 0) {
+    accept_len[b] = alen;
+    best_node[b] = best;
+    next_root[b] = s_arg[best];
+  }
+  if (t <= K) {
+    // ancestors have smaller indices than descendants, so the j-th set bit of the winner's
+    // ancestor mask is its ancestor at depth j
+    int node = -1;
+    if (t < alen) {
+      int seen = 0;
+      for (int u = 0; u < T; ++u) {
+        if ((tree->anc_mask[best][u >> 6] >> (u & 63)) & 1ull) {
+          if (seen == t) { node = u; break; }
+          ++seen;
+        }
+      }
+    }
+    path_nodes[(size_t)b * (K + 1) + t] = node;
+    accepted_tokens[(size_t)b * (K + 1) + t] = node >= 0 ? tree_tokens[(size_t)b * T + node] : -1;
+  }
+}
+
+}  // namespace
+
+extern "C" size_t medusa_accept_workspace_bytes(int B, int T, int V) {
+  (void)V;
+  if (B < 1 || T < 1) return 0;
+  return (size_t)B * T * kAccChunks * sizeof(RowPart);
+}
+
+extern "C" int medusa_accept(const float* logits, const int32_t* tree_tokens, const medusa_tree_t* tree, int B, int V,
+                             medusa_accept_mode_t mode, float temperature, float eps, float delta, int32_t* accept_len,
+                             int32_t* best_node, int32_t* path_nodes, int32_t* accepted_tokens, int32_t* next_root,
+                             void* workspace, size_t workspace_bytes, medusa_stream_t stream_) {
+  if (!logits || !tree_tokens || !tree || !accept_len || !best_node || !path_nodes || !accepted_tokens || !next_root)
+    return MEDUSA_EINVAL;
+  if (B < 1 || V < 1) return MEDUSA_EINVAL;
+  if (mode != MEDUSA_GREEDY && mode != MEDUSA_TYPICAL) return MEDUSA_EINVAL;
+  if (mode == MEDUSA_TYPICAL && !(temperature > 0.f)) return MEDUSA_EINVAL;
+  if (!tree->dev) return MEDUSA_EHIP;
+  const int T = tree->host.T;
+  if (!workspace || workspace_bytes < medusa_accept_workspace_bytes(B, T, V)) return MEDUSA_EWORKSPACE;
+  hipStream_t stream = (hipStream_t)stream_;
+  RowPart* part = (RowPart*)workspace;
+  const dim3 grid(kAccChunks, B * T);
+  const float inv_temp = mode == MEDUSA_TYPICAL ? 1.0f / temperature : 1.0f;
+  if (mode == MEDUSA_TYPICAL) {
+    hipLaunchKernelGGL(row_stats_kernel<true>, grid, dim3(256), 0, stream, logits, V, inv_temp, part);
+    MEDUSA_LAUNCH_CHECK();
+    hipLaunchKernelGGL(accept_finalize_kernel<true>, dim3(B), dim3(128), 0, stream, logits, tree_tokens, tree->dev, part,
+                       V, inv_temp, eps, delta, accept_len, best_node, path_nodes, accepted_tokens, next_root);
+  } else {
+    hipLaunchKernelGGL(row_stats_kernel<false>, grid, dim3(256), 0, stream, logits, V, inv_temp, part);
+    MEDUSA_LAUNCH_CHECK();
+    hipLaunchKernelGGL(accept_finalize_kernel<false>, dim3(B), dim3(128), 0, stream, logits, tree_tokens, tree->dev, part,
+                       V, inv_temp, eps, delta, accept_len, best_node, path_nodes, accepted_tokens, next_root);
+  }
+  MEDUSA_LAUNCH_CHECK();
+  return MEDUSA_OK;
+}

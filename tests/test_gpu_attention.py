@@ -1,0 +1,88 @@
+"""GPU parity: tree_attention (HIP, through the C ABI) against the CPU oracle, element by element."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2401_10774_amd as M
+from oracle import medusa_oracle as O
+from workloads import draw_normal
+from _harness import TOL, poison_tail, row_rel_err, to_dev, to_host_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(dtype, branching, B, Hq, Hkv, D, Lcap, prefix, seed, nodes=None):
+    gt = M.MedusaTree(branching=branching) if nodes is None else M.MedusaTree(nodes=nodes)
+    ot = O.tree_cartesian(branching) if nodes is None else O.tree_from_nodes(nodes)
+    T = ot.T
+    q = draw_normal(seed, 5, (B, Hq, T, D), 1.0, dtype)
+    kt = draw_normal(seed, 6, (B, Hkv, T, D), 1.0, dtype)
+    vt = draw_normal(seed, 7, (B, Hkv, T, D), 1.0, dtype)
+    kc = draw_normal(seed, 8, (B, Hkv, Lcap, D), 1.0, dtype)
+    vc = draw_normal(seed, 9, (B, Hkv, Lcap, D), 1.0, dtype)
+    pl = np.asarray(prefix, np.int32)
+    scale = 1.0 / math.sqrt(D)
+    # rows at and beyond the prefix hold NaN on the device: they must never influence the result
+    out = M.tree_attention(to_dev(q), to_dev(kt), to_dev(vt), to_dev(poison_tail(kc, pl)), to_dev(poison_tail(vc, pl)),
+                           to_dev(pl), gt, scale)
+    torch.cuda.synchronize()
+    ref = O.tree_attention_ref(q, kt, vt, kc, vc, pl, ot, scale)
+    got = to_host_f64(out)
+    assert np.isfinite(got).all()
+    err = row_rel_err(got, ref)
+    assert err <= TOL[dtype], f"attention rel err {err}"
+    return got, ref, ot
+
+
+def test_config1_fp32():
+    run_case("f32", (3, 2), 1, 4, 4, 64, 160, [128], 100)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Lcap,prefix", [
+    (1, 4, 4, 1152, [1024]),                 # 7B-like tree over a 1024 prefix: several splits
+    (2, 4, 4, 700, [641, 33]),               # ragged, partial last key block
+    (3, 8, 2, 300, [0, 1, 300]),             # GQA 4:1; empty prefix, one key, full capacity
+    (1, 2, 1, 2100, [2047]),                 # MQA, long prefix
+])
+def test_bf16_tree_64_nodes(B, Hq, Hkv, Lcap, prefix):
+    run_case("bf16", (4, 3, 2, 1), B, Hq, Hkv, 128, Lcap, prefix, 101)
+
+
+def test_bf16_tree_88_nodes_crosses_the_64_bit_mask_word():
+    run_case("bf16", (4, 3, 2, 1, 1), 2, 5, 5, 128, 600, [512, 77], 102)
+
+
+def test_bf16_small_trees_and_head_dim_64():
+    run_case("bf16", (3, 2), 2, 4, 2, 64, 200, [128, 5], 103)
+    run_case("bf16", (1,), 1, 2, 2, 128, 64, [40], 104)
+    run_case("bf16", None, 1, 2, 2, 128, 64, [40], 105, nodes=[])            # root only: plain decode attention
+    run_case("bf16", None, 2, 8, 2, 128, 500, [400, 17], 106,
+             nodes=[(0,), (1,), (3,), (0, 0), (0, 2), (1, 0), (0, 0, 0)])      # sparse tree
+
+
+def test_f32_other_shapes():
+    run_case("f32", (4, 3, 2, 1), 2, 4, 2, 128, 2300, [2200, 0], 107)          # > one 2048-key pass
+
+
+def test_path_equivalence_on_gpu_output():
+    """Sec. 2.1.2: every root-to-leaf path, run as its own causal sequence, reproduces the tree output."""
+    got, ref, ot = run_case("bf16", (3, 2, 2), 1, 2, 2, 128, 96, [64], 108)
+    # the oracle satisfies the invariant exactly (tests/test_oracle_attention.py); the GPU inherits it
+    # within tolerance, checked here per path rather than per tensor
+    for path in ot.paths:
+        nodes = [int(n) for n in path if n >= 0]
+        assert row_rel_err(got[:, :, nodes], ref[:, :, nodes]) <= TOL["bf16"]
+
+
+def test_run_twice_is_bit_identical():
+    gt = M.MedusaTree(branching=(4, 3, 2, 1))
+    B, Hq, Hkv, D, Lcap = 2, 8, 4, 128, 1200
+    q = to_dev(draw_normal(109, 5, (B, Hq, gt.T, D), 1.0, "bf16"))
+    kt = to_dev(draw_normal(109, 6, (B, Hkv, gt.T, D), 1.0, "bf16"))
+    kc = to_dev(draw_normal(109, 8, (B, Hkv, Lcap, D), 1.0, "bf16"))
+    pl = to_dev(np.array([1100, 300], np.int32))
+    a = M.tree_attention(q, kt, kt, kc, kc, pl, gt, 0.088)
+    b = M.tree_attention(q, kt, kt, kc, kc, pl, gt, 0.088)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))

@@ -1,0 +1,83 @@
+"""GPU parity: medusa_heads (HIP, through the C ABI) against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2401_10774_amd as M
+from oracle import medusa_oracle as O
+from workloads import draw_normal, get_config, make_step_inputs
+from _harness import TOL, row_rel_err, to_dev, to_host_bits, to_host_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(dtype, M_rows, d, V, K, with_w1, seed):
+    h = draw_normal(seed, 0, (M_rows, d), 1.0, dtype)
+    w1 = draw_normal(seed, 2, (K, d, d), 0.02, dtype) if with_w1 else None
+    w2 = draw_normal(seed, 3, (K, V, d), 0.02, dtype)
+    logits, resid = M.medusa_heads(to_dev(h), None if w1 is None else to_dev(w1), to_dev(w2))
+    torch.cuda.synchronize()
+    ref_logits, ref_resid = O.medusa_heads_ref(h, w1, w2, dtype)
+    err = row_rel_err(to_host_f64(logits), ref_logits)
+    assert err <= TOL[dtype], f"logits rel err {err}"
+    if with_w1:
+        rerr = row_rel_err(to_host_f64(resid), ref_resid)
+        assert rerr <= TOL[dtype], f"residual rel err {rerr}"
+    return err
+
+
+# M spans the wave-per-row path (<= 4) and the MFMA path (> 4) with ragged row tiles; V = 1000 / 333
+# leaves ragged 64-row workgroup tails; d spans several reduction steps.
+@pytest.mark.parametrize("M_rows", [1, 2, 3, 4, 5, 16, 17, 65, 81, 100])
+@pytest.mark.parametrize("with_w1", [True, False])
+def test_bf16_shapes(M_rows, with_w1):
+    run_case("bf16", M_rows, 512, 1000, 2, with_w1, 50 + M_rows)
+
+
+@pytest.mark.parametrize("d,V,K", [(64, 7, 1), (192, 333, 3), (4096, 130, 1), (5120, 70, 2)])
+def test_bf16_odd_sizes(d, V, K):
+    for M_rows in (1, 4, 10):
+        run_case("bf16", M_rows, d, V, K, True, 60)
+
+
+@pytest.mark.parametrize("M_rows", [1, 3, 4, 10])
+def test_f32_shapes(M_rows):
+    err = run_case("f32", M_rows, 256, 1000, 2, True, 70 + M_rows)
+    assert err < 1e-5
+    run_case("f32", M_rows, 8, 5, 1, False, 71)
+
+
+def test_config1_exact_shapes():
+    cfg = get_config("C1")
+    x = make_step_inputs(cfg, ["h_last", "hidden_tree", "w1", "w2", "w_lm"])
+    logits, _ = M.medusa_heads(to_dev(x["h_last"]), to_dev(x["w1"]), to_dev(x["w2"]))
+    ref, _ = O.medusa_heads_ref(x["h_last"], x["w1"], x["w2"], "f32")
+    assert row_rel_err(to_host_f64(logits), ref) <= 1e-5
+    hid = x["hidden_tree"].reshape(cfg.B * cfg.T, cfg.d)
+    ver, _ = M.medusa_heads(to_dev(hid), None, to_dev(x["w_lm"][None]))
+    ref, _ = O.medusa_heads_ref(hid, None, x["w_lm"][None], "f32")
+    assert row_rel_err(to_host_f64(ver), ref) <= 1e-5
+
+
+def test_zero_w1_head_reproduces_the_lm_head_bitwise():
+    """Sec. 2.1.1 initialisation: W1 = 0, W2 = LM head.  SiLU(0) + h = h exactly, so both paths
+    must feed identical operands to the same projection kernel."""
+    d, V, K = 256, 500, 2
+    for dtype in ("bf16", "f32"):
+        h = to_dev(draw_normal(80, 0, (3, d), 1.0, dtype))
+        w_lm = to_dev(draw_normal(80, 4, (V, d), 0.02, dtype))
+        w1 = torch.zeros((K, d, d), dtype=h.dtype, device="cuda")
+        w2 = torch.stack([w_lm] * K).contiguous()
+        heads, resid = M.medusa_heads(h, w1, w2)
+        lm, _ = M.medusa_heads(h, None, w_lm[None].contiguous())
+        assert np.array_equal(to_host_bits(resid[:, 0]), to_host_bits(h))
+        for k in range(K):
+            assert torch.equal(heads[:, k], lm[:, 0])
+
+
+def test_run_twice_is_bit_identical():
+    h = to_dev(draw_normal(81, 0, (65, 512), 1.0, "bf16"))
+    w2 = to_dev(draw_normal(81, 3, (1, 2000, 512), 0.02, "bf16"))
+    a, _ = M.medusa_heads(h, None, w2)
+    b, _ = M.medusa_heads(h, None, w2)
+    assert torch.equal(a, b)
