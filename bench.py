@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the Medusa verification step on one MI355X.
+
+A step is one pass of the whole hot path (heads, top-k/tree, tree attention on one cache layer,
+LM-head logits of the tree tokens, acceptance, KV commit of all layers) over one batch of seeded
+synthetic inputs that are already resident in HBM.  Prints ONE JSON line with the step rate, the
+roofline of the dominant kernel (the W2 vocabulary projection of medusa_heads, timed live with
+HIP events inside the timed region) and the CPU oracle timed on the host cores as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="C2", help="workload name (C1..C5); the headline metric is quoted on C2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="also time every library call on its own (stderr)")
+    return ap.parse_args()
+
+
+class HipEvents:
+    """Raw hipEvent_t handles for the library's profiling hook (timed on whatever stream the hook records on)."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0 and self.hip.hipEventCreate(ctypes.byref(b)) == 0
+            self.pairs.append((a, b))
+
+    def elapsed_ms(self, i):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.pairs[i][0], self.pairs[i][1])
+        assert rc == 0, f"hipEventElapsedTime failed ({rc})"
+        return ms.value
+
+    def close(self):
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2401_10774_amd as M
+    from paper_2401_10774_amd.step import VerificationStep
+    from workloads import get_config, make_step_inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    cfg = get_config(args.config)
+    torch.cuda.set_device(0)
+
+    t0 = time.time()
+    x = make_step_inputs(cfg)
+
+    def dev(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+        return torch.from_numpy(a).cuda()
+
+    tensors = {k: dev(v) for k, v in x.items()}
+    tree = M.MedusaTree(branching=cfg.branching)
+    step = VerificationStep(tensors, tree, cfg.accept, cfg.temperature, cfg.eps, cfg.delta)
+    step.prepare()
+    torch.cuda.synchronize()
+    print(f"[bench] {cfg.name}: inputs drawn and uploaded in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+
+    L = M.lib()
+    K, W = args.steps, args.warmup
+    for i in range(W):
+        step.reset_prefix()
+        step.run(i % cfg.NL)
+    torch.cuda.synchronize()
+
+    events = HipEvents(K)
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for i in range(K):
+        L.medusa_profile_set_events(events.pairs[i][0], events.pairs[i][1])
+        step.reset_prefix()
+        step.run((W + i) % cfg.NL)
+    stop.record()
+    torch.cuda.synchronize()
+    L.medusa_profile_set_events(None, None)
+    ms_per_step = start.elapsed_time(stop) / K
+    kern_ms = sum(events.elapsed_ms(i) for i in range(K)) / K
+    events.close()
+    accept_len = step.accept_out[0].cpu().numpy()
+
+    e = 2 if cfg.dtype == "bf16" else 4
+    mean_prefix = float(np.mean(x["prefix_len"]))
+    parts = step.algorithmic_bytes(mean_prefix, float(accept_len.mean()))
+    steps_per_s = 1e3 / ms_per_step
+    step_gbs = parts["total"] / (ms_per_step * 1e-3) / 1e9
+    # dominant kernel: the W2 stream of medusa_heads (M = B rows): weights once + activations + fp32 logits
+    dom_bytes = parts["heads_w2"]
+    dom_gbs = dom_bytes / (kern_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "verification steps/sec + achieved HBM GB/s vs peak, 7B shapes, 64-node tree",
+        "value": round(steps_per_s, 2),
+        "unit": "steps/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": f"{cfg.name}: B={cfg.B} d={cfg.d} heads={cfg.Hq}/{cfg.Hkv}x{cfg.D} V={cfg.V} K={cfg.K} "
+                        f"tree={cfg.branching} T={cfg.T} prefix=[{cfg.L_min},{cfg.L_max}] NL={cfg.NL} "
+                        f"accept={cfg.accept}",
+            "seed": cfg.seed,
+            "launch": "eager, one stream, attended cache layer rotates every step",
+        },
+        "step_hbm": {"algorithmic_bytes": int(parts["total"]), "achieved_GBps": round(step_gbs, 1),
+                     "frac_of_peak": round(step_gbs / HBM_PEAK_GBS, 4)},
+        "roofline": {
+            "kernel": "gemv_bf16_kernel<1, EPI_LOGITS> (medusa_heads W2 projection, M=B)" if cfg.dtype == "bf16" and cfg.B <= 4
+                      else "medusa_heads W2 projection",
+            "bound": "hbm",
+            "achieved": round(dom_gbs, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
+            "bytes_per_launch": int(dom_bytes),
+            "avg_launch_us": round(kern_ms * 1e3, 2),
+            "traffic": None,
+        },
+        "mean_accept_len": round(float(accept_len.mean()), 3),
+    }
+
+    if args.breakdown:
+        breakdown(step, cfg, parts)
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, x)
+    print(json.dumps(out), flush=True)
+
+
+def breakdown(step, cfg, parts):
+    """Per-call timings (each call 50x back to back, attended layer rotating); informational, stderr only."""
+    import torch
+    pre, post = step._calls(0)
+    names = ["heads (W1+W2)", "topk_tree", "attention", "verify GEMM", "accept", "commit"]
+    keys = [("heads_w1", "heads_w2"), ("topk",), ("attention",), ("verify",), ("accept",), ("commit",)]
+    stream = torch.cuda.current_stream().cuda_stream
+    n = 50
+    for idx, name in enumerate(names):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for i in range(n):
+            calls = step._calls(i % cfg.NL)
+            _, fn, fargs = (calls[0] + calls[1])[idx]
+            fn(*fargs, stream)
+            if name == "commit":
+                step.reset_prefix()
+        b.record()
+        torch.cuda.synchronize()
+        us = a.elapsed_time(b) / n * 1e3
+        nbytes = sum(parts[k] for k in keys[idx])
+        print(f"[bench]   {name:14s} {us:9.1f} us  {nbytes / 1e6:9.1f} MB  {nbytes / us / 1e3:8.1f} GB/s", file=sys.stderr)
+
+
+def cpu_baseline(cfg, x):
+    """The CPU oracle, as it stands, on one full step of the same inputs (host cores of this machine)."""
+    from oracle import medusa_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    otree = O.tree_cartesian(cfg.branching)
+    pl0 = x["prefix_len"].copy()
+    n, t0 = 0, time.time()
+    while True:                                  # whole steps until about 10 s of CPU work are on the clock
+        x["prefix_len"][:] = pl0
+        O.verification_step_ref(x, otree, cfg.dtype, 1.0 / math.sqrt(cfg.D), cfg.accept, cfg.temperature, cfg.eps,
+                                cfg.delta)
+        n += 1
+        dt = time.time() - t0
+        if dt >= 10.0 or n >= 50:
+            break
+    return {"value": round(n / dt, 4), "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{n} full step(s) of {cfg.name} (all heads, all tree rows, all {cfg.NL} committed layers), "
+                      f"{dt:.1f} s wall, numpy float64"}
+
+
+if __name__ == "__main__":
+    main()

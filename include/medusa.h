@@ -195,6 +195,15 @@ int kv_commit(void* k_cache, void* v_cache, const void* k_tree, const void* v_tr
               const int32_t* path_nodes, int path_stride, const int32_t* accept_len, int32_t* prefix_len,
               int NL, int B, int Hkv, int T, int D, int Lcap, medusa_dtype_t dtype, medusa_stream_t stream);
 
+/* ----------------------------------------------------------------------------------
+ * Benchmark hook (no counterpart in the paper): while a pair of hipEvent_t handles is set,
+ * every medusa_heads call with w1 != NULL records `start` right before and `stop` right after
+ * its vocabulary-projection kernel (the W2 stream, the largest single read of the step) on the
+ * call's stream, so a caller can time that kernel inside a running step.  Pass NULL, NULL to
+ * switch it off (the default).  Process-wide, not thread-safe; the events stay caller-owned.
+ * -------------------------------------------------------------------------------- */
+int medusa_profile_set_events(void* start, void* stop);
+
 #ifdef __cplusplus
 }
 #endif

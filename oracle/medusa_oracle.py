@@ -346,3 +346,44 @@ def kv_commit_ref(k_cache, v_cache, k_tree, v_tree, path_nodes, accept_len, pref
             k_cache[:, b, :, L + j, :] = k_tree[:, b, :, node, :]
             v_cache[:, b, :, L + j, :] = v_tree[:, b, :, node, :]
         prefix_len[b] = L + a
+
+
+# --------------------------------------------------------------------------
+# the whole step, chained (Sec. 2, opening paragraph: the three substeps of a decoding step)
+# --------------------------------------------------------------------------
+
+@dataclass
+class StepResult:
+    medusa_logits: np.ndarray     # [B, K, V]
+    lm_logits_last: np.ndarray    # [B, V]
+    topk_ids: np.ndarray
+    tree_tokens: np.ndarray
+    position_ids: np.ndarray
+    attn_out: np.ndarray          # [B, Hq, T, D]
+    verify_logits: np.ndarray     # [B, T, V]
+    accept: AcceptResult
+    prefix_len: np.ndarray        # after the commit
+
+
+def verification_step_ref(x: dict, tree: Tree, dtype: str, scale: float, mode: str, temperature: float,
+                          eps: float, delta: float, attn_layer: int = 0, plant=None) -> StepResult:
+    """One verification iteration on the arrays of ``x`` (names as in workloads.TENSOR_IDS):
+    heads on h_last, top-k and tree assembly, tree attention on one cache layer, the original
+    model's logits at every tree token (LM head on hidden_tree), acceptance, commit.
+    Caches and prefix_len in ``x`` are updated in place.  ``plant`` may adjust the verification
+    logits before acceptance (test harness only)."""
+    B, T = x["hidden_tree"].shape[0], x["hidden_tree"].shape[1]
+    d = x["h_last"].shape[1]
+    medusa_logits, _ = medusa_heads_ref(x["h_last"], x["w1"], x["w2"], dtype)
+    lm_last, _ = medusa_heads_ref(x["h_last"], None, x["w_lm"][None], dtype)
+    lm_last = lm_last[:, 0]
+    topk, tokens, pos = medusa_topk_tree_ref(medusa_logits, lm_last, tree, x["prefix_len"])
+    attn = tree_attention_ref(x["q"], x["k_tree"][attn_layer], x["v_tree"][attn_layer], x["k_cache"][attn_layer],
+                              x["v_cache"][attn_layer], x["prefix_len"], tree, scale)
+    ver, _ = medusa_heads_ref(x["hidden_tree"].reshape(B * T, d), None, x["w_lm"][None], dtype)
+    ver = ver[:, 0].reshape(B, T, -1)
+    if plant is not None:
+        ver = plant(ver, tokens)
+    acc = medusa_accept_ref(ver, tokens, tree, mode, temperature, eps, delta)
+    kv_commit_ref(x["k_cache"], x["v_cache"], x["k_tree"], x["v_tree"], acc.path_nodes, acc.accept_len, x["prefix_len"])
+    return StepResult(medusa_logits, lm_last, topk, tokens, pos, attn, ver, acc, x["prefix_len"])

@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = (
     "medusa_status_string", "medusa_tree_create_cartesian", "medusa_tree_create_nodes", "medusa_tree_destroy",
     "medusa_tree_query", "medusa_tree_tables", "medusa_heads", "medusa_topk_tree_workspace_bytes",
     "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "medusa_accept_workspace_bytes",
-    "medusa_accept", "kv_commit",
+    "medusa_accept", "kv_commit", "medusa_profile_set_events",
 )
 
 
@@ -65,6 +65,7 @@ def lib() -> ctypes.CDLL:
         L.medusa_accept.argtypes = ([c_void_p] * 3 + [c_int] * 3 + [c_float] * 3 + [c_void_p] * 5 +
                                     [c_void_p, c_size_t, c_void_p])
         L.kv_commit.argtypes = ([c_void_p] * 5 + [c_int, c_void_p, c_void_p] + [c_int] * 6 + [c_int, c_void_p])
+        L.medusa_profile_set_events.argtypes = [c_void_p, c_void_p]
         for name in EXPORTED_SYMBOLS:
             fn = getattr(L, name)
             if fn.restype is ctypes.c_int or fn.restype is None:

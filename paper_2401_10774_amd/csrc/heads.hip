@@ -231,6 +231,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_bf16_kernel(GemmArgs a) {
   }
 }
 
+// Optional event pair recorded around the vocabulary-projection launch (benchmark hook).
+hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
+
 template <int EPI>
 int launch_gemm(const GemmArgs& a, medusa_dtype_t dtype, hipStream_t stream) {
   const dim3 block(256);
@@ -301,5 +304,16 @@ extern "C" int medusa_heads(const void* hidden, const void* w1, const void* w2, 
   a.W = w2;
   a.out = logits;
   a.N = V;
-  return launch_gemm<EPI_LOGITS>(a, dtype, stream);
+  const bool prof = w1 && g_prof_start && g_prof_stop;
+  if (prof) MEDUSA_HIP_TRY(hipEventRecord(g_prof_start, stream));
+  const int rc = launch_gemm<EPI_LOGITS>(a, dtype, stream);
+  if (prof && rc == MEDUSA_OK) MEDUSA_HIP_TRY(hipEventRecord(g_prof_stop, stream));
+  return rc;
+}
+
+extern "C" int medusa_profile_set_events(void* start, void* stop) {
+  if ((start == nullptr) != (stop == nullptr)) return MEDUSA_EINVAL;
+  g_prof_start = (hipEvent_t)start;
+  g_prof_stop = (hipEvent_t)stop;
+  return MEDUSA_OK;
 }

@@ -19,10 +19,20 @@ def to_host_f64(t: torch.Tensor) -> np.ndarray:
 
 
 def to_host_bits(t: torch.Tensor) -> np.ndarray:
-    """Raw storage back on the host: uint16 patterns for bfloat16, else the array itself."""
+    """Raw storage back on the host as unsigned integers (uint16 for bfloat16, uint32 for float32),
+    so that comparisons are bitwise (NaN poison included)."""
     if t.dtype == torch.bfloat16:
         return t.detach().view(torch.int16).cpu().numpy().view(np.uint16)
+    if t.dtype == torch.float32:
+        return t.detach().view(torch.int32).cpu().numpy().view(np.uint32)
     return t.detach().cpu().numpy()
+
+
+def bits(a: np.ndarray) -> np.ndarray:
+    """Host array as unsigned integers of the same width (bitwise comparison)."""
+    if a.dtype == np.float32:
+        return a.view(np.uint32)
+    return a
 
 
 def row_rel_err(got: np.ndarray, ref: np.ndarray) -> float:

@@ -6,7 +6,7 @@ import torch
 import paper_2401_10774_amd as M
 from oracle import medusa_oracle as O
 from workloads import draw_normal, get_config, make_step_inputs
-from _harness import TOL, row_rel_err, to_dev, to_host_bits, to_host_f64
+from _harness import TOL, bits, row_rel_err, to_dev, to_host_bits, to_host_f64
 
 pytestmark = pytest.mark.gpu
 

@@ -7,7 +7,7 @@ import torch
 import paper_2401_10774_amd as M
 from oracle import medusa_oracle as O
 from workloads import draw_normal
-from _harness import to_dev, to_host_bits
+from _harness import bits, to_dev, to_host_bits
 
 pytestmark = pytest.mark.gpu
 
@@ -170,7 +170,7 @@ def test_kv_commit_bitwise(dtype, NL, B, Hkv, T, D, Lcap):
     M.kv_commit(d_kc, d_vc, to_dev(kt), to_dev(vt), to_dev(path), to_dev(alen), d_pl)
     torch.cuda.synchronize()
     O.kv_commit_ref(kc, vc, kt, vt, path, alen, pl)
-    assert np.array_equal(to_host_bits(d_kc), kc) and np.array_equal(to_host_bits(d_vc), vc)
+    assert np.array_equal(to_host_bits(d_kc), bits(kc)) and np.array_equal(to_host_bits(d_vc), bits(vc))
     assert np.array_equal(d_pl.cpu().numpy(), pl)
 
 
