@@ -22,6 +22,10 @@
  *     device arrays (e.g. prefix_len) cannot be checked on the host: the kernels clamp
  *     every index they derive from device data, so bad contents give wrong rows, never an
  *     out-of-bounds access.
+ *   - medusa_topk_tree, medusa_accept and kv_commit each keep a few ticket counters in device
+ *     memory of the library (used to elect the last workgroup of a launch; they return to zero
+ *     when a launch completes).  Calls of the SAME entry point must therefore not overlap on one
+ *     GPU: issue them on one stream, or order the streams.  Batch size B <= 4096 for these calls.
  *   - dtype is the storage type of activations, weights and KV: MEDUSA_F32 or
  *     MEDUSA_BF16.  Accumulation is always fp32; logits are always fp32.
  *   - Ties in arg-max / top-k: larger value first, then lower token id.  NaN logits are

@@ -45,13 +45,14 @@ def _run(cmd):
 
 def build_library(verbose: bool = False) -> str:
     hipcc = _hipcc()
+    extra = os.environ.get("MEDUSA_HIPCC_EXTRA", "").split()      # tuning knobs, e.g. -DMEDUSA_GEMM_STAGES=3
     tmp = tempfile.mkdtemp(prefix="medusa_hip_build_")
     try:
         objs = [os.path.join(tmp, s.replace(".hip", ".o")) for s in SOURCES]
 
         def compile_one(pair):
             src, obj = pair
-            return _run([hipcc, *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj])
+            return _run([hipcc, *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj])
 
         with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
             logs = list(ex.map(compile_one, zip(SOURCES, objs)))

@@ -1,14 +1,15 @@
 // medusa_accept (Sec. 2.3.1 of the Medusa paper): greedy or typical acceptance of the tree's
 // candidates and selection of the longest accepted prefix.
 //
-// Stage 1 is the only pass over the B*T*V logits: each (row, chunk) workgroup reduces its slice
+// One launch.  The only pass over the B*T*V logits: each (row, chunk) workgroup reduces its slice
 // to an arg-max key and, in typical mode, the soft-max statistics
 //   m = max z,  S = sum exp(z - m),  U = sum (z - m) exp(z - m),   z = logit / temperature,
 // from which  ln p(x) = z_x - m - ln S  and the entropy  H = ln S - U / S.
-// Stage 2 (one workgroup per sequence, one thread per node) merges the chunks, evaluates every
-// node's test on its parent's row, turns the pass bits into two 64-bit ballots and decides
-// acceptance of node t as  (anc_mask[t] & ~pass) == 0  -- no pointer chasing.  The winner is
-// the accepted node of greatest depth and, at equal depth, lowest index.
+// The last workgroup of a sequence to finish (ticket counter) then merges the chunks with one
+// thread per node, evaluates every node's test on its parent's row, turns the pass bits into
+// two 64-bit ballots and decides acceptance of node t as  (anc_mask[t] & ~pass) == 0  -- no
+// pointer chasing.  The winner is the accepted node of greatest depth and, at equal depth,
+// lowest index.
 #include <math.h>
 
 #include "common.hpp"
@@ -16,6 +17,11 @@
 namespace {
 
 constexpr int kAccChunks = 4;
+constexpr int kMaxBatch = 4096;
+
+// Ticket counters of the "last workgroup of a sequence" election; zero between launches.
+// Shared by all calls on a GPU: calls that overlap on different streams would race.
+__device__ unsigned int g_accept_ticket[kMaxBatch];
 
 struct RowPart {       // one per (row, chunk)
   uint64_t key;        // rank_key of the chunk's best (logit, id)
@@ -33,18 +39,15 @@ __device__ __forceinline__ void stats_merge(float& m, float& S, float& U, float 
 }
 
 template <bool TYPICAL>
-__global__ __launch_bounds__(256) void row_stats_kernel(const float* __restrict__ logits, int V, float inv_temp,
-                                                        RowPart* __restrict__ part) {
+__device__ __forceinline__ void row_stats(const float* __restrict__ logits, int V, float inv_temp,
+                                          RowPart* __restrict__ part) {
   __shared__ uint64_t s_key[4];
   __shared__ float s_m[4], s_S[4], s_U[4];
   const size_t row = blockIdx.y;
   const float* src = logits + row * V;
-  const int per = ceil_div(V, kAccChunks);
-  const int lo = blockIdx.x * per, hi = min(V, lo + per);
   uint64_t key = 0;
   float m = -INFINITY, S = 0.f, U = 0.f;
-  for (int i = lo + threadIdx.x; i < hi; i += 256) {
-    const float x = src[i];
+  auto visit = [&](float x, int i) {
     const uint64_t k2 = rank_key(x, (uint32_t)i);
     key = k2 > key ? k2 : key;
     if (TYPICAL) {
@@ -60,12 +63,27 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const float* __restrict_
         U += (z - m) * e;
       }
     }
+  };
+  if ((V & 3) == 0) {                    // rows are 16-byte aligned: four logits per load
+    const int per = ceil_div(V >> 2, kAccChunks);
+    const int lo = blockIdx.x * per, hi = min(V >> 2, lo + per);
+    const floatx4_t* src4 = (const floatx4_t*)src;
+#pragma unroll 4
+    for (int i = lo + threadIdx.x; i < hi; i += 256) {
+      const floatx4_t v = src4[i];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) visit(v[e], 4 * i + e);
+    }
+  } else {
+    const int per = ceil_div(V, kAccChunks);
+    const int lo = blockIdx.x * per, hi = min(V, lo + per);
+    for (int i = lo + threadIdx.x; i < hi; i += 256) visit(src[i], i);
   }
   key = wave_max_u64(key);
   if (TYPICAL) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
-      const float m2 = __shfl_xor(m, o, kWave), S2 = __shfl_xor(S, o, kWave), U2 = __shfl_xor(U, o, kWave);
+      const float m2 = __shfl_xor(m, o, kWave), S2 = __shfl_xor(S, o, kWave), U2 = __shfl_xor(U, o, kWave);   // 6 steps, once per workgroup
       stats_merge(m, S, U, m2, S2, U2);
     }
   }
@@ -82,39 +100,38 @@ __global__ __launch_bounds__(256) void row_stats_kernel(const float* __restrict_
       key = s_key[w] > key ? s_key[w] : key;
       if (TYPICAL) stats_merge(m, S, U, s_m[w], s_S[w], s_U[w]);
     }
-    RowPart p;
-    p.key = key;
-    p.m = m;
-    p.S = S;
-    p.U = U;
-    p.pad = 0.f;
-    part[row * kAccChunks + blockIdx.x] = p;
+    RowPart* p = part + row * kAccChunks + blockIdx.x;
+    store_agent(&p->key, key);
+    store_agent(&p->m, m);
+    store_agent(&p->S, S);
+    store_agent(&p->U, U);
   }
 }
 
+// Runs in the 256 threads of one workgroup; threads >= 128 only take part in the barriers.
 template <bool TYPICAL>
-__global__ __launch_bounds__(128) void accept_finalize_kernel(const float* __restrict__ logits,
-                                                              const int32_t* __restrict__ tree_tokens,
-                                                              const TreeTables* __restrict__ tree,
-                                                              const RowPart* __restrict__ part, int V, float inv_temp,
-                                                              float eps, float delta, int32_t* __restrict__ accept_len,
-                                                              int32_t* __restrict__ best_node, int32_t* __restrict__ path_nodes,
-                                                              int32_t* __restrict__ accepted_tokens,
-                                                              int32_t* __restrict__ next_root) {
+__device__ __forceinline__ void accept_finalize(int b, const float* __restrict__ logits,
+                                                const int32_t* __restrict__ tree_tokens,
+                                                const TreeTables* __restrict__ tree, const RowPart* __restrict__ part,
+                                                int V, float inv_temp, float eps, float delta,
+                                                int32_t* __restrict__ accept_len, int32_t* __restrict__ best_node,
+                                                int32_t* __restrict__ path_nodes, int32_t* __restrict__ accepted_tokens,
+                                                int32_t* __restrict__ next_root) {
   __shared__ int32_t s_arg[MEDUSA_MAX_TREE_TOKENS];
   __shared__ float s_m[MEDUSA_MAX_TREE_TOKENS], s_lnS[MEDUSA_MAX_TREE_TOKENS], s_H[MEDUSA_MAX_TREE_TOKENS];
   __shared__ uint64_t s_pass[2];
   __shared__ uint32_t s_best[2];
-  const int b = blockIdx.x, t = threadIdx.x;
+  const int t = threadIdx.x;
   const int T = tree->T, K = tree->K;
   const int lane = t & 63, wave = t >> 6;
   if (t < T) {
     const RowPart* p = part + ((size_t)b * T + t) * kAccChunks;
-    uint64_t key = p[0].key;
-    float m = p[0].m, S = p[0].S, U = p[0].U;
+    uint64_t key = load_agent(&p[0].key);
+    float m = load_agent(&p[0].m), S = load_agent(&p[0].S), U = load_agent(&p[0].U);
     for (int c = 1; c < kAccChunks; ++c) {
-      key = p[c].key > key ? p[c].key : key;
-      if (TYPICAL) stats_merge(m, S, U, p[c].m, p[c].S, p[c].U);
+      const uint64_t k2 = load_agent(&p[c].key);
+      key = k2 > key ? k2 : key;
+      if (TYPICAL) stats_merge(m, S, U, load_agent(&p[c].m), load_agent(&p[c].S), load_agent(&p[c].U));
     }
     s_arg[t] = (int32_t)rank_key_id(key);
     if (TYPICAL) {
@@ -140,7 +157,7 @@ __global__ __launch_bounds__(128) void accept_finalize_kernel(const float* __res
     }
   }
   const uint64_t bal = __ballot(pass);
-  if (lane == 0) s_pass[wave] = bal;
+  if (lane == 0 && wave < 2) s_pass[wave] = bal;
   __syncthreads();
   const uint64_t fail0 = ~s_pass[0], fail1 = ~s_pass[1];
   uint32_t score = 0;
@@ -148,7 +165,7 @@ __global__ __launch_bounds__(128) void accept_finalize_kernel(const float* __res
     score = ((uint32_t)(tree->depth[t] + 1) << 8) | (uint32_t)(255 - t);   // deeper first, then lower index
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) score = max(score, (uint32_t)__shfl_xor((int)score, o, kWave));
-  if (lane == 0) s_best[wave] = score;
+  if (lane == 0 && wave < 2) s_best[wave] = score;
   __syncthreads();
   score = max(s_best[0], s_best[1]);
   const int best = 255 - (int)(score & 255u);
@@ -176,6 +193,21 @@ __global__ __launch_bounds__(128) void accept_finalize_kernel(const float* __res
   }
 }
 
+// grid (kAccChunks, B*T), 256 threads.
+template <bool TYPICAL>
+__global__ __launch_bounds__(256) void accept_kernel(const float* __restrict__ logits, const int32_t* __restrict__ tree_tokens,
+                                                     const TreeTables* __restrict__ tree, RowPart* __restrict__ part, int V,
+                                                     float inv_temp, float eps, float delta, int32_t* __restrict__ accept_len,
+                                                     int32_t* __restrict__ best_node, int32_t* __restrict__ path_nodes,
+                                                     int32_t* __restrict__ accepted_tokens, int32_t* __restrict__ next_root) {
+  row_stats<TYPICAL>(logits, V, inv_temp, part);
+  const int T = tree->T;
+  const int b = blockIdx.y / T;
+  if (!last_workgroup_of(&g_accept_ticket[b], (unsigned)(kAccChunks * T))) return;
+  accept_finalize<TYPICAL>(b, logits, tree_tokens, tree, part, V, inv_temp, eps, delta, accept_len, best_node, path_nodes,
+                           accepted_tokens, next_root);
+}
+
 }  // namespace
 
 extern "C" size_t medusa_accept_workspace_bytes(int B, int T, int V) {
@@ -193,24 +225,21 @@ extern "C" int medusa_accept(const float* logits, const int32_t* tree_tokens, co
   if (B < 1 || V < 1) return MEDUSA_EINVAL;
   if (mode != MEDUSA_GREEDY && mode != MEDUSA_TYPICAL) return MEDUSA_EINVAL;
   if (mode == MEDUSA_TYPICAL && !(temperature > 0.f)) return MEDUSA_EINVAL;
+  if (B > kMaxBatch) return MEDUSA_EUNSUPPORTED;
   if (!tree->dev) return MEDUSA_EHIP;
   const int T = tree->host.T;
-  if (!workspace || workspace_bytes < medusa_accept_workspace_bytes(B, T, V)) return MEDUSA_EWORKSPACE;
+  if (!workspace || workspace_bytes < medusa_accept_workspace_bytes(B, T, V) || ((uintptr_t)workspace & 7) != 0)
+    return MEDUSA_EWORKSPACE;
   hipStream_t stream = (hipStream_t)stream_;
   RowPart* part = (RowPart*)workspace;
   const dim3 grid(kAccChunks, B * T);
   const float inv_temp = mode == MEDUSA_TYPICAL ? 1.0f / temperature : 1.0f;
-  if (mode == MEDUSA_TYPICAL) {
-    hipLaunchKernelGGL(row_stats_kernel<true>, grid, dim3(256), 0, stream, logits, V, inv_temp, part);
-    MEDUSA_LAUNCH_CHECK();
-    hipLaunchKernelGGL(accept_finalize_kernel<true>, dim3(B), dim3(128), 0, stream, logits, tree_tokens, tree->dev, part,
-                       V, inv_temp, eps, delta, accept_len, best_node, path_nodes, accepted_tokens, next_root);
-  } else {
-    hipLaunchKernelGGL(row_stats_kernel<false>, grid, dim3(256), 0, stream, logits, V, inv_temp, part);
-    MEDUSA_LAUNCH_CHECK();
-    hipLaunchKernelGGL(accept_finalize_kernel<false>, dim3(B), dim3(128), 0, stream, logits, tree_tokens, tree->dev, part,
-                       V, inv_temp, eps, delta, accept_len, best_node, path_nodes, accepted_tokens, next_root);
-  }
+  if (mode == MEDUSA_TYPICAL)
+    hipLaunchKernelGGL(accept_kernel<true>, grid, dim3(256), 0, stream, logits, tree_tokens, tree->dev, part, V, inv_temp,
+                       eps, delta, accept_len, best_node, path_nodes, accepted_tokens, next_root);
+  else
+    hipLaunchKernelGGL(accept_kernel<false>, grid, dim3(256), 0, stream, logits, tree_tokens, tree->dev, part, V, inv_temp,
+                       eps, delta, accept_len, best_node, path_nodes, accepted_tokens, next_root);
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;
 }

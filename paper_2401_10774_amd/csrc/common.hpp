@@ -69,30 +69,93 @@ template <typename T> __device__ __forceinline__ void store_from_float(T* p, flo
 template <> __device__ __forceinline__ void store_from_float<float>(float* p, float v) { *p = v; }
 template <> __device__ __forceinline__ void store_from_float<uint16_t>(uint16_t* p, float v) { *p = (uint16_t)float_to_bf16_bits(v); }
 
-// Butterfly reductions over the 64 lanes of a wavefront; every lane ends with the result.
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+// Wavefront reductions; every lane ends with the result.  Inside a 16-lane row the exchange uses
+// DPP (quad permutes, then half-row and row mirrors: no LDS crossbar); the four row results are
+// combined through scalar registers.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) { return __uint_as_float(dpp_u32<CTRL>(__float_as_uint(v))); }
+constexpr int kDppQuadSwap1 = 0xB1;   // quad_perm [1,0,3,2]
+constexpr int kDppQuadSwap2 = 0x4E;   // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141; // row_half_mirror
+constexpr int kDppMirror = 0x140;     // row_mirror
+
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_f32<kDppQuadSwap1>(v);
+  v += dpp_f32<kDppQuadSwap2>(v);
+  v += dpp_f32<kDppHalfMirror>(v);
+  v += dpp_f32<kDppMirror>(v);
   return v;
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_f32<kDppQuadSwap1>(v));
+  v = fmaxf(v, dpp_f32<kDppQuadSwap2>(v));
+  v = fmaxf(v, dpp_f32<kDppHalfMirror>(v));
+  v = fmaxf(v, dpp_f32<kDppMirror>(v));
+  return v;
+}
+__device__ __forceinline__ float readlane_f32(float v, int lane) {
+  return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(v), lane));
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  v = row16_sum(v);
+  return (readlane_f32(v, 0) + readlane_f32(v, 16)) + (readlane_f32(v, 32) + readlane_f32(v, 48));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
-  return v;
+  v = row16_max(v);
+  return fmaxf(fmaxf(readlane_f32(v, 0), readlane_f32(v, 16)), fmaxf(readlane_f32(v, 32), readlane_f32(v, 48)));
 }
-__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int o) {
-  uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
-  lo = __shfl_xor(lo, o, kWave);
-  hi = __shfl_xor(hi, o, kWave);
+template <int CTRL>
+__device__ __forceinline__ uint64_t dpp_max_u64(uint64_t v) {
+  const uint32_t lo = dpp_u32<CTRL>((uint32_t)v), hi = dpp_u32<CTRL>((uint32_t)(v >> 32));
+  const uint64_t w = ((uint64_t)hi << 32) | lo;
+  return w > v ? w : v;
+}
+__device__ __forceinline__ uint64_t readlane_u64(uint64_t v, int lane) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, lane);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), lane);
   return ((uint64_t)hi << 32) | lo;
 }
 __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    uint64_t w = shfl_xor_u64(v, o);
-    v = w > v ? w : v;
+  v = dpp_max_u64<kDppQuadSwap1>(v);
+  v = dpp_max_u64<kDppQuadSwap2>(v);
+  v = dpp_max_u64<kDppHalfMirror>(v);
+  v = dpp_max_u64<kDppMirror>(v);
+  const uint64_t a = readlane_u64(v, 0), b = readlane_u64(v, 16), c = readlane_u64(v, 32), d = readlane_u64(v, 48);
+  const uint64_t ab = a > b ? a : b, cd = c > d ? c : d;
+  return ab > cd ? ab : cd;
+}
+
+// "Last workgroup of a group" election for single-launch two-phase kernels.  Every workgroup
+// calls it once after it has written its partial results with store_agent(); exactly one call per
+// group of `total` workgroups returns true, and that workgroup may then read all partials of
+// the group with load_agent().  On this multi-die GPU a device-wide fence costs a write-back of
+// the die's L2, so no fence is used: partials are written through to the device-coherent level
+// (agent-scope stores), each wavefront waits until its own stores are acknowledged, and only
+// then is the ticket taken; readers bypass the non-coherent caches the same way.  The counter
+// returns to zero, so it needs no initialisation between launches.
+template <typename T>
+__device__ __forceinline__ T load_agent(const T* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ void store_agent(T* p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool last_workgroup_of(unsigned int* counter, unsigned int total) {
+  __shared__ unsigned int s_ticket;
+  __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wavefront's loads and stores are complete
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned int t = atomicAdd(counter, 1u);
+    if (t == total - 1) atomicExch(counter, 0u);
+    s_ticket = t;
   }
-  return v;
+  __syncthreads();
+  return s_ticket == total - 1;
 }
 
 // Order-preserving key for (logit, token id): a larger key means a larger logit, or an equal

@@ -6,16 +6,19 @@
 //   * M <= 4  (bf16): one wavefront per weight row, 16-byte non-temporal loads that cover
 //                     1 KB of the row per instruction, packed bf16 dot products on the
 //                     vector ALUs, activations resident in LDS.
-//   * M  > 4  (bf16): 16x16x32 bf16 MFMA tiles; a workgroup owns 64 weight rows x up to 80
-//                     activation rows, its four wavefronts interleave over the reduction
-//                     dimension and are summed through LDS in a fixed order.
+//   * M  > 4  (bf16): 16x16x32 bf16 MFMA tiles fed from a double-buffered LDS tile that is
+//                     filled with full-line loads several reduction steps ahead; up to 80
+//                     activation rows x 128 weight rows per workgroup (128 x 128 for M > 80).
 //   * fp32          : plain FMA version of the first scheme (small configurations only).
 // The residual block's epilogue applies SiLU, adds h and rounds once to the storage type.
+#include <stdlib.h>
+
 #include "common.hpp"
 
 namespace {
 
 enum { EPI_LOGITS = 0, EPI_RESID = 1 };
+
 
 // acc[m][n] = sum_j W[k][n][j] * X[m*xs_m + k*xs_k + j]
 struct GemmArgs {
@@ -25,6 +28,7 @@ struct GemmArgs {
   void* out;           // EPI_LOGITS: float [M][K][N];  EPI_RESID: dtype [M][K][N]
   int M, N, d, K;
   long xs_m, xs_k;     // element strides of X between rows m and between heads k
+  int rows_per_wg;     // GEMV kernels: weight rows per workgroup (multiple of 8)
 };
 
 typedef __bf16 dot2_t __attribute__((__vector_size__(2 * sizeof(__bf16))));
@@ -50,7 +54,6 @@ __device__ __forceinline__ void epilogue_store(const GemmArgs& a, int m, int k, 
 // bf16, M <= 4 per block of rows: wave-per-row streaming GEMV.
 // grid (row blocks, K, m blocks), 256 threads.  LDS: MB x d bf16.
 // ---------------------------------------------------------------------------------------
-constexpr int kGemvRowsPerWg = 64;
 
 template <int MB, int EPI>
 __global__ __launch_bounds__(256) void gemv_bf16_kernel(GemmArgs a) {
@@ -69,9 +72,9 @@ __global__ __launch_bounds__(256) void gemv_bf16_kernel(GemmArgs a) {
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint16_t* W = (const uint16_t*)a.W + (size_t)k * a.N * a.d;
-  const int n_begin = blockIdx.x * kGemvRowsPerWg;
+  const int n_begin = blockIdx.x * a.rows_per_wg;
   constexpr int R = 2, U = 4;
-  for (int nb = n_begin + wave * R; nb < n_begin + kGemvRowsPerWg && nb < a.N; nb += 4 * R) {
+  for (int nb = n_begin + wave * R; nb < n_begin + a.rows_per_wg && nb < a.N; nb += 4 * R) {
     float acc[R][MB];
 #pragma unroll
     for (int r = 0; r < R; ++r)
@@ -136,8 +139,8 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(GemmArgs a) {
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const float* W = (const float*)a.W + (size_t)k * a.N * a.d;
-  const int n_begin = blockIdx.x * kGemvRowsPerWg;
-  for (int n = n_begin + wave; n < n_begin + kGemvRowsPerWg && n < a.N; n += 4) {
+  const int n_begin = blockIdx.x * a.rows_per_wg;
+  for (int n = n_begin + wave; n < n_begin + a.rows_per_wg && n < a.N; n += 4) {
     float acc[MB];
 #pragma unroll
     for (int mm = 0; mm < MB; ++mm) acc[mm] = 0.f;
@@ -159,83 +162,140 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(GemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// bf16, M > 4: MFMA 16x16x32.  Workgroup tile = (16*MT activation rows) x (64 weight rows);
-// the four wavefronts take reduction steps w, w+4, w+8, ... (32 elements each) and are summed
-// through LDS in wave order.  Operand layout of v_mfma_f32_16x16x32_bf16: lane l supplies
-// row/column (l % 16) and the eight reduction elements 8*(l/16) .. 8*(l/16)+7; it receives
-// output column (l % 16), rows 4*(l/16) .. 4*(l/16)+3.  A = activations, B = weights.
-// grid (ceil(N/64), K, ceil(M/(16*MT))), 256 threads, LDS 8*MT KB.
+// bf16, M > 4: LDS-staged MFMA GEMM (v_mfma_f32_16x16x32_bf16).
+//
+// Workgroup tile BM x BN = (WM*16*MT activation rows) x (WN*16*NT weight rows), four wavefronts
+// arranged WM x WN, reduction in steps of BK = 64 elements = one 128-byte line per row.  Both
+// operands are fetched with 16-byte loads in which 8 consecutive lanes cover one full 128-byte
+// line of a row (half as many L2 requests per byte as loading MFMA operand layout directly, which
+// measured request-bound at ~3.5 TB/s), held in registers PD reduction steps ahead of their use,
+// then written to a double-buffered, padded LDS tile from which the wavefronts read their MFMA
+// operands (lane l: row l%16, elements 8*(l/16)..+7 of a 32-element step).  One barrier per step.
+// Output layout of the MFMA: lane l holds column l%16 (weight row), rows 4*(l/16)..+3
+// (activation rows).  grid (ceil(N/BN), K, ceil(M/BM)), 256 threads.
 // ---------------------------------------------------------------------------------------
-template <int MT, int EPI>
-__global__ __launch_bounds__(256) void gemm_mfma_bf16_kernel(GemmArgs a) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  floatx4_t* red = (floatx4_t*)smem;            // [4 waves][MT*2 tiles][64 lanes]
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int i16 = lane & 15, q = lane >> 4;
+template <int WM, int WN, int MT, int NT, int PD, int EPI>
+__global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
+  constexpr int BM = WM * 16 * MT, BN = WN * 16 * NT, BK = 64;
+  constexpr int PITCH = BK * 2 + 16;                  // bytes per LDS row: 128 data + 16 pad
+  constexpr int CHUNKS = (BM + BN) * 8;               // 16-byte chunks per reduction step
+  constexpr int LPT = (CHUNKS + 255) / 256;           // chunks per thread per step
+  constexpr int STAGE_BYTES = (BM + BN) * PITCH;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i16 = lane & 15, q4 = lane >> 4;
+  const int wm = wave / WN, wn = wave - wm * WN;
   const int k = blockIdx.y;
-  const int n0 = blockIdx.x * 64, m0 = blockIdx.z * (16 * MT);
+  const int n0 = blockIdx.x * BN, m0 = blockIdx.z * BM;
   const uint16_t* W = (const uint16_t*)a.W + (size_t)k * a.N * a.d;
   const uint16_t* X = (const uint16_t*)a.X + (size_t)k * a.xs_k;
 
-  const uint16_t* wp[4];
+  // Per-thread source pointers and LDS offsets of its LPT chunks (rows clamped into range; the
+  // surplus chunk ids of the last slot repeat the final chunk, which is harmless).
+  const uint16_t* src[LPT];
+  int dst[LPT];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) wp[j] = W + (size_t)min(n0 + 16 * j + i16, a.N - 1) * a.d + q * 8;
-  const uint16_t* xp[MT];
-#pragma unroll
-  for (int t = 0; t < MT; ++t) xp[t] = X + (size_t)min(m0 + 16 * t + i16, a.M - 1) * a.xs_m + q * 8;
+  for (int it = 0; it < LPT; ++it) {
+    const int id = min(it * 256 + tid, CHUNKS - 1);
+    const int row = id >> 3, c = id & 7;
+    src[it] = row < BM ? X + (size_t)min(m0 + row, a.M - 1) * a.xs_m + c * 8
+                       : W + (size_t)min(n0 + row - BM, a.N - 1) * a.d + c * 8;
+    dst[it] = row * PITCH + c * 16;
+  }
 
-  floatx4_t acc[MT][4];
+  floatx4_t acc[MT][NT];
 #pragma unroll
   for (int t = 0; t < MT; ++t)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[t][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < NT; ++j) acc[t][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
-  const int steps = a.d >> 5;
-
-  for (int s = wave; s < steps; s += 4) {
-    bf16x8_t wf[4], xf[MT];
+  const int nk = a.d / BK;
+  u32x4_t regs[PD][LPT];
+  auto gload = [&](int step, u32x4_t (&r)[LPT]) {
+    const int off = min(step, nk - 1) * BK;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) wf[j] = *(const bf16x8_t*)(wp[j] + (size_t)s * 32);
+    for (int it = 0; it < LPT; ++it) r[it] = *(const u32x4_t*)(src[it] + off);
+  };
+  auto lstore = [&](int buf, const u32x4_t (&r)[LPT]) {
 #pragma unroll
-    for (int t = 0; t < MT; ++t) xf[t] = *(const bf16x8_t*)(xp[t] + (size_t)s * 32);
+    for (int it = 0; it < LPT; ++it) *(u32x4_t*)(lds + buf * STAGE_BYTES + dst[it]) = r[it];
+  };
+  const int x_off = ((wm * MT) * 16 + i16) * PITCH + q4 * 16;
+  const int w_off = (BM + (wn * NT) * 16 + i16) * PITCH + q4 * 16;
+  auto compute = [&](int buf, uint32_t keep) {
+    const unsigned char* base = lds + buf * STAGE_BYTES;
 #pragma unroll
-    for (int t = 0; t < MT; ++t)
+    for (int kk = 0; kk < 2; ++kk) {
+      bf16x8_t xf[MT], wf[NT];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) acc[t][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[t], wf[j], acc[t][j], 0, 0, 0);
-  }
-
-  // Sum the four wavefronts' partial tiles through LDS, two of the four column tiles at a
-  // time (keeps the buffer at 8*MT KB), always in wave order 0,1,2,3.
-#pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    if (half) __syncthreads();
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-#pragma unroll
-      for (int jj = 0; jj < 2; ++jj) red[(wave * MT * 2 + t * 2 + jj) * 64 + lane] = acc[t][half * 2 + jj];
-    __syncthreads();
-    for (int tile = wave; tile < MT * 2; tile += 4) {
-      floatx4_t s = red[tile * 64 + lane];
-#pragma unroll
-      for (int w = 1; w < 4; ++w) s += red[(w * MT * 2 + tile) * 64 + lane];
-      const int t = tile >> 1, j = half * 2 + (tile & 1);
-      const int n = n0 + 16 * j + i16;
-      const int mb = m0 + 16 * t + 4 * q;
-      if (n < a.N) {
-        if (mb + 0 < a.M) epilogue_store<EPI, uint16_t>(a, mb + 0, k, n, s[0]);
-        if (mb + 1 < a.M) epilogue_store<EPI, uint16_t>(a, mb + 1, k, n, s[1]);
-        if (mb + 2 < a.M) epilogue_store<EPI, uint16_t>(a, mb + 2, k, n, s[2]);
-        if (mb + 3 < a.M) epilogue_store<EPI, uint16_t>(a, mb + 3, k, n, s[3]);
+      for (int t = 0; t < MT; ++t) {
+        u32x4_t bits = *(const u32x4_t*)(base + x_off + t * 16 * PITCH + kk * 64);
+        bits &= keep;
+        xf[t] = __builtin_bit_cast(bf16x8_t, bits);
       }
+#pragma unroll
+      for (int j = 0; j < NT; ++j) wf[j] = *(const bf16x8_t*)(base + w_off + j * 16 * PITCH + kk * 64);
+#pragma unroll
+      for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[t][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[t], wf[j], acc[t][j], 0, 0, 0);
+    }
+  };
+
+  // Prologue: steps 0..PD-1 in flight, step 0 into LDS, then step PD replaces it in the registers.
+#pragma unroll
+  for (int s = 0; s < PD; ++s) gload(s, regs[s]);
+  lstore(0, regs[0]);
+  gload(PD, regs[0]);
+  __syncthreads();
+  // Main loop, unrolled by PD so that register-stage indices are compile-time.  It is branch-free:
+  // steps past the end are clamped reloads whose activations are masked to zero.
+  for (int i0 = 0; i0 < nk; i0 += PD) {
+#pragma unroll
+    for (int j = 0; j < PD; ++j) {
+      const int i = i0 + j;
+      compute(i & 1, (uint32_t) - (int)(i < nk));
+      __builtin_amdgcn_sched_barrier(0);
+      lstore((i + 1) & 1, regs[(j + 1) % PD]);           // step i+1 (loaded PD steps ago)
+      __builtin_amdgcn_sched_barrier(0);
+      gload(i + 1 + PD, regs[(j + 1) % PD]);
+      __builtin_amdgcn_sched_barrier(0);
+      __syncthreads();
     }
   }
+
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int n = n0 + (wn * NT + j) * 16 + i16;
+      const int mb = m0 + (wm * MT + t) * 16 + 4 * q4;
+      if (n < a.N) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (mb + r < a.M) epilogue_store<EPI, uint16_t>(a, mb + r, k, n, acc[t][j][r]);
+      }
+    }
 }
 
 // Optional event pair recorded around the vocabulary-projection launch (benchmark hook).
 hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
 
+// Weight rows per GEMV workgroup: 16 measured best on MI355X at 7B shapes (8, 32 and 64 were
+// 1-10 % slower); fewer for small matrices so that the grid still covers the chip.
+int gemv_rows_per_wg(int N, int K) {
+  static const int forced = [] { const char* e = getenv("MEDUSA_GEMV_ROWS"); return e ? atoi(e) : 0; }();
+  if (forced >= 8 && forced % 8 == 0) return forced;
+  long rows = ((long)N * K / 1024) & ~7L;
+  return rows < 8 ? 8 : (rows > 16 ? 16 : (int)rows);
+}
+
 template <int EPI>
-int launch_gemm(const GemmArgs& a, medusa_dtype_t dtype, hipStream_t stream) {
+int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) {
+  GemmArgs a = a_in;
+  a.rows_per_wg = gemv_rows_per_wg(a.N, a.K);
+  const int kGemvRowsPerWg = a.rows_per_wg;
   const dim3 block(256);
   if (dtype == MEDUSA_F32) {
     // activations of one m-block live in LDS: keep it within 64 KB
@@ -252,17 +312,26 @@ int launch_gemm(const GemmArgs& a, medusa_dtype_t dtype, hipStream_t stream) {
     if (MB == 1) hipLaunchKernelGGL((gemv_bf16_kernel<1, EPI>), grid, block, lds, stream, a);
     else if (MB == 2) hipLaunchKernelGGL((gemv_bf16_kernel<2, EPI>), grid, block, lds, stream, a);
     else hipLaunchKernelGGL((gemv_bf16_kernel<4, EPI>), grid, block, lds, stream, a);
-  } else {
-    const int MT = a.M > 64 ? 5 : ceil_div(a.M, 16);
-    const dim3 grid(ceil_div(a.N, 64), a.K, ceil_div(a.M, 16 * MT));
-    const size_t lds = (size_t)4 * MT * 2 * 64 * sizeof(floatx4_t);
+  } else if (a.M <= 80) {
+    // skinny: every wavefront sees all activation rows; 128 weight rows per workgroup when that
+    // still yields a few hundred workgroups, else 64
+    const int MT = ceil_div(a.M, 16);
+    static const int force_wide = [] { const char* e = getenv("MEDUSA_GEMM_WIDE"); return e ? atoi(e) : -1; }();
+    const bool wide = force_wide >= 0 ? force_wide != 0 : (long)ceil_div(a.N, 128) * a.K >= 200;
+    const dim3 grid(ceil_div(a.N, wide ? 128 : 64), a.K, 1);
+#define MEDUSA_SKINNY(MT_)                                                                                        \
+  case MT_:                                                                                                       \
+    if (wide) hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 2, 4, EPI>), grid, block, 0, stream, a);        \
+    else hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 1, 4, EPI>), grid, block, 0, stream, a);             \
+    break;
     switch (MT) {
-      case 1: hipLaunchKernelGGL((gemm_mfma_bf16_kernel<1, EPI>), grid, block, lds, stream, a); break;
-      case 2: hipLaunchKernelGGL((gemm_mfma_bf16_kernel<2, EPI>), grid, block, lds, stream, a); break;
-      case 3: hipLaunchKernelGGL((gemm_mfma_bf16_kernel<3, EPI>), grid, block, lds, stream, a); break;
-      case 4: hipLaunchKernelGGL((gemm_mfma_bf16_kernel<4, EPI>), grid, block, lds, stream, a); break;
-      default: hipLaunchKernelGGL((gemm_mfma_bf16_kernel<5, EPI>), grid, block, lds, stream, a); break;
+      MEDUSA_SKINNY(1) MEDUSA_SKINNY(2) MEDUSA_SKINNY(3) MEDUSA_SKINNY(4) MEDUSA_SKINNY(5)
     }
+#undef MEDUSA_SKINNY
+  } else {
+    // 128 x 128 tile, wavefronts 2 x 2, each 64 x 64
+    const dim3 grid(ceil_div(a.N, 128), a.K, ceil_div(a.M, 128));
+    hipLaunchKernelGGL((gemm_lds_bf16_kernel<2, 2, 4, 4, 2, EPI>), grid, block, 0, stream, a);
   }
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;

@@ -1,17 +1,23 @@
 // medusa_topk_tree (Sec. 2.1.2 of the Medusa paper): per-head top-S_k token ids, the greedy
 // root token, and the gather of both into the fixed candidate tree.
 //
-// Two launches.  Stage 1 scans the logits once: every (row, chunk) workgroup keeps per-lane
-// sorted candidate lists in registers and merges them with wavefront max-reductions on a
-// 64-bit (value, inverted id) key, so ties resolve to the lower token id everywhere.
-// Stage 2 (one wavefront per sequence) merges the chunk winners, writes topk_ids and gathers
-// tree_tokens / position_ids from the node tables.
+// One launch.  Every (row, chunk) workgroup scans its slice of one logits row once: each lane
+// keeps a sorted candidate list in registers, lists are merged with wavefront max-reductions on
+// a 64-bit (value, inverted id) key, so ties resolve to the lower token id everywhere.  The last
+// workgroup of a sequence to finish (ticket counter) merges the chunk winners of that
+// sequence's K+1 rows, writes topk_ids and gathers tree_tokens / position_ids from the node
+// tables.
 #include "common.hpp"
 
 namespace {
 
-constexpr int kChunks = 8;          // workgroups per logits row in stage 1
+constexpr int kChunks = 16;         // workgroups per logits row
 constexpr int kMaxS = MEDUSA_MAX_TOPK;
+constexpr int kMaxBatch = 4096;
+
+// Ticket counters of the "last workgroup of a sequence" election; zero between launches.
+// Shared by all calls on a GPU: calls that overlap on different streams would race.
+__device__ unsigned int g_topk_ticket[kMaxBatch];
 
 // Insert key into a descending list of compile-time length S (registers only).
 template <int S>
@@ -42,24 +48,41 @@ __device__ __forceinline__ void wave_top(uint64_t (&list)[S], uint64_t (&out)[S]
   }
 }
 
-// rows: [B*(K+1)] logits rows of length V; row index b*(K+1)+0 is the LM head, +k head k.
-// part: [rows][kChunks][kMaxS] keys (0 = empty).
+// rows: [B*(K+1)] logits rows of length V; row index b*(K+1)+0 is the LM head, +h head h.
+// part: [rows][kChunks][S] keys (0 = empty).  grid (kChunks, B*(K+1)), 256 threads.
 template <int S>
-__global__ __launch_bounds__(256) void topk_stage1(const float* __restrict__ medusa_logits, const float* __restrict__ lm_logits,
-                                                   int V, int K_heads, int K, uint64_t* __restrict__ part) {
+__global__ __launch_bounds__(256) void topk_tree_kernel(const float* __restrict__ medusa_logits,
+                                                        const float* __restrict__ lm_logits, int V, int K_heads,
+                                                        uint64_t* __restrict__ part, const TreeTables* __restrict__ tree,
+                                                        const int32_t* __restrict__ prefix_len,
+                                                        int32_t* __restrict__ topk_ids, int32_t* __restrict__ tree_tokens,
+                                                        int32_t* __restrict__ position_ids) {
   __shared__ uint64_t cand[4][S];
+  __shared__ int32_t flat[1 + MEDUSA_MAX_HEADS * kMaxS];
+  const int K = tree->K;
   const int row = blockIdx.y;                       // b*(K+1) + h
   const int b = row / (K + 1), h = row - b * (K + 1);
   const float* src = h == 0 ? lm_logits + (size_t)b * V : medusa_logits + ((size_t)b * K_heads + (h - 1)) * V;
-  const int per = ceil_div(V, kChunks);
-  const int lo = blockIdx.x * per, hi = min(V, lo + per);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   uint64_t list[S];
 #pragma unroll
   for (int i = 0; i < S; ++i) list[i] = 0;
-  for (int i = lo + threadIdx.x; i < hi; i += 256) list_insert<S>(list, rank_key(src[i], (uint32_t)i));
+  if ((V & 3) == 0) {                               // rows are 16-byte aligned: four logits per load
+    const int per = ceil_div(V >> 2, kChunks);
+    const int lo = blockIdx.x * per, hi = min(V >> 2, lo + per);
+    const floatx4_t* src4 = (const floatx4_t*)src;
+    for (int i = lo + threadIdx.x; i < hi; i += 256) {
+      const floatx4_t v = src4[i];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) list_insert<S>(list, rank_key(v[e], (uint32_t)(4 * i + e)));
+    }
+  } else {
+    const int per = ceil_div(V, kChunks);
+    const int lo = blockIdx.x * per, hi = min(V, lo + per);
+    for (int i = lo + threadIdx.x; i < hi; i += 256) list_insert<S>(list, rank_key(src[i], (uint32_t)i));
+  }
   uint64_t top[S];
   wave_top<S>(list, top);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (lane == 0) {
 #pragma unroll
     for (int i = 0; i < S; ++i) cand[wave][i] = top[i];
@@ -67,51 +90,53 @@ __global__ __launch_bounds__(256) void topk_stage1(const float* __restrict__ med
   __syncthreads();
   if (wave == 0) {
     // 4*S <= 64 candidates, one per lane; S rounds of wavefront max
-    uint64_t mine[1] = {lane < 4 * S ? cand[lane / S][lane % S] : 0};
-    uint64_t* dst = part + ((size_t)row * kChunks + blockIdx.x) * kMaxS;
+    uint64_t mine = lane < 4 * S ? cand[lane / S][lane % S] : 0;
+    uint64_t* dst = part + ((size_t)row * kChunks + blockIdx.x) * S;
 #pragma unroll
     for (int r = 0; r < S; ++r) {
-      const uint64_t best = wave_max_u64(mine[0]);
-      if (mine[0] == best) mine[0] = 0;
-      if (lane == 0) dst[r] = best;
+      const uint64_t best = wave_max_u64(mine);
+      if (mine == best) mine = 0;
+      if (lane == 0) store_agent(dst + r, best);
     }
-    if (lane == 0)
-      for (int r = S; r < kMaxS; ++r) dst[r] = 0;
   }
-}
 
-// One wavefront per sequence.
-__global__ __launch_bounds__(64) void topk_stage2(const uint64_t* __restrict__ part, const TreeTables* __restrict__ tree,
-                                                  const int32_t* __restrict__ prefix_len, int32_t* __restrict__ topk_ids,
-                                                  int32_t* __restrict__ tree_tokens, int32_t* __restrict__ position_ids) {
-  __shared__ int32_t flat[1 + MEDUSA_MAX_HEADS * kMaxS];
-  const int b = blockIdx.x, lane = threadIdx.x;
-  const int K = tree->K, S = tree->S, T = tree->T;
-  for (int h = 0; h <= K; ++h) {
-    const int want = h == 0 ? 1 : tree->topk_per_head[h - 1];
-    const uint64_t* src = part + ((size_t)b * (K + 1) + h) * kChunks * kMaxS;
-    // kChunks*kMaxS = 128 candidates: two per lane
-    uint64_t c0 = src[lane], c1 = src[lane + 64];
-    for (int r = 0; r < want; ++r) {
-      const uint64_t mx = c0 > c1 ? c0 : c1;
-      const uint64_t best = wave_max_u64(mx);
-      if (c0 == best) c0 = 0;
-      else if (c1 == best) c1 = 0;
-      if (lane == 0) {
-        const int32_t id = (int32_t)rank_key_id(best);
-        if (h == 0) flat[0] = id;
-        else {
-          flat[tree->head_base[h - 1] + r] = id;
-          topk_ids[((size_t)b * K + (h - 1)) * S + r] = id;
+  // ---- the sequence's last workgroup merges the chunk winners and fills the tree ------------
+  if (!last_workgroup_of(&g_topk_ticket[b], (unsigned)(kChunks * (K + 1)))) return;
+  const int Smax = tree->S, T = tree->T;
+  if (wave == 0) {
+    for (int hh = 0; hh <= K; ++hh) {
+      const int want = hh == 0 ? 1 : tree->topk_per_head[hh - 1];
+      const uint64_t* p = part + ((size_t)b * (K + 1) + hh) * kChunks * S;
+      constexpr int PER_LANE = (kChunks * S + 63) / 64;
+      uint64_t c[PER_LANE];
+#pragma unroll
+      for (int j = 0; j < PER_LANE; ++j) c[j] = j * 64 + lane < kChunks * S ? load_agent(p + j * 64 + lane) : 0;
+      for (int r = 0; r < want; ++r) {
+        uint64_t mx = c[0];
+#pragma unroll
+        for (int j = 1; j < PER_LANE; ++j) mx = c[j] > mx ? c[j] : mx;
+        const uint64_t best = wave_max_u64(mx);
+        bool done = false;                            // keys are unique: exactly one slot matches
+#pragma unroll
+        for (int j = 0; j < PER_LANE; ++j) {
+          if (!done && c[j] == best) { c[j] = 0; done = true; }
+        }
+        if (lane == 0) {
+          const int32_t id = (int32_t)rank_key_id(best);
+          if (hh == 0) flat[0] = id;
+          else {
+            flat[tree->head_base[hh - 1] + r] = id;
+            topk_ids[((size_t)b * K + (hh - 1)) * Smax + r] = id;
+          }
         }
       }
+      if (hh > 0 && lane == 0)
+        for (int r = want; r < Smax; ++r) topk_ids[((size_t)b * K + (hh - 1)) * Smax + r] = -1;
     }
-    if (h > 0 && lane == 0)
-      for (int r = want; r < S; ++r) topk_ids[((size_t)b * K + (h - 1)) * S + r] = -1;
   }
   __syncthreads();
   const int L = prefix_len[b];
-  for (int t = lane; t < T; t += 64) {
+  for (int t = threadIdx.x; t < T; t += 256) {
     tree_tokens[(size_t)b * T + t] = flat[tree->token_src[t]];
     position_ids[(size_t)b * T + t] = L + tree->depth[t];
   }
@@ -133,22 +158,25 @@ extern "C" int medusa_topk_tree(const float* medusa_logits, const float* lm_logi
   if (K > 0 && (!medusa_logits || !topk_ids)) return MEDUSA_EINVAL;
   if (B < 1 || V < 1 || K_heads < K) return MEDUSA_EINVAL;
   if (S > V) return MEDUSA_EINVAL;
+  if (B > kMaxBatch) return MEDUSA_EUNSUPPORTED;
   if (!tree->dev) return MEDUSA_EHIP;
-  if (!workspace || workspace_bytes < medusa_topk_tree_workspace_bytes(B, K)) return MEDUSA_EWORKSPACE;
+  if (!workspace || workspace_bytes < medusa_topk_tree_workspace_bytes(B, K) || ((uintptr_t)workspace & 7) != 0)
+    return MEDUSA_EWORKSPACE;
   hipStream_t stream = (hipStream_t)stream_;
   uint64_t* part = (uint64_t*)workspace;
-  const dim3 grid(kChunks, B * (K + 1));
+  const dim3 grid(kChunks, B * (K + 1)), block(256);
   const int Sc = S <= 1 ? 1 : (S <= 2 ? 2 : (S <= 4 ? 4 : (S <= 8 ? 8 : 16)));
+#define MEDUSA_TOPK(S_)                                                                                         \
+  hipLaunchKernelGGL(topk_tree_kernel<S_>, grid, block, 0, stream, medusa_logits, lm_logits, V, K_heads, part, \
+                     tree->dev, prefix_len, topk_ids, tree_tokens, position_ids)
   switch (Sc) {
-    case 1: hipLaunchKernelGGL(topk_stage1<1>, grid, dim3(256), 0, stream, medusa_logits, lm_logits, V, K_heads, K, part); break;
-    case 2: hipLaunchKernelGGL(topk_stage1<2>, grid, dim3(256), 0, stream, medusa_logits, lm_logits, V, K_heads, K, part); break;
-    case 4: hipLaunchKernelGGL(topk_stage1<4>, grid, dim3(256), 0, stream, medusa_logits, lm_logits, V, K_heads, K, part); break;
-    case 8: hipLaunchKernelGGL(topk_stage1<8>, grid, dim3(256), 0, stream, medusa_logits, lm_logits, V, K_heads, K, part); break;
-    default: hipLaunchKernelGGL(topk_stage1<16>, grid, dim3(256), 0, stream, medusa_logits, lm_logits, V, K_heads, K, part); break;
+    case 1: MEDUSA_TOPK(1); break;
+    case 2: MEDUSA_TOPK(2); break;
+    case 4: MEDUSA_TOPK(4); break;
+    case 8: MEDUSA_TOPK(8); break;
+    default: MEDUSA_TOPK(16); break;
   }
-  MEDUSA_LAUNCH_CHECK();
-  hipLaunchKernelGGL(topk_stage2, dim3(B), dim3(64), 0, stream, part, tree->dev, prefix_len, topk_ids, tree_tokens,
-                     position_ids);
+#undef MEDUSA_TOPK
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;
 }
