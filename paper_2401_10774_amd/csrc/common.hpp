@@ -51,15 +51,14 @@ __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) { return __
 __device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
 
-// fp32 -> bf16 bits, round to nearest even (finite inputs; NaN stays NaN).
-__device__ __forceinline__ uint32_t float_to_bf16_bits(float x) {
-  uint32_t u = __float_as_uint(x);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
+// fp32 -> bf16, round to nearest even, with the hardware converter (v_cvt_pk_bf16_f32).
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2v_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return float_to_bf16_bits(lo) | (float_to_bf16_bits(hi) << 16);
+  const f32x2_t f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2v_t));
 }
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float x) { return pack_bf16x2(x, 0.f) & 0xffffu; }
 
 template <typename T> __device__ __forceinline__ float load_as_float(const T* p);
 template <> __device__ __forceinline__ float load_as_float<float>(const float* p) { return *p; }

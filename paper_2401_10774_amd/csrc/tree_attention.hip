@@ -6,30 +6,43 @@
 //   * One workgroup = one (sequence, KV head, block of up to 80 query rows, split of the key
 //     range).  All G = Hq/Hkv query heads that share the KV head are handled together: their
 //     G*T rows are contiguous in q and out.
-//   * The key range of a sequence is the list of 32-key blocks [prefix blocks ..., tree blocks
-//     ...]; a split owns a contiguous run of blocks and its four wavefronts take blocks
-//     round-robin.  Each wavefront is an independent online-soft-max worker: K is read from
-//     HBM straight into MFMA operand layout, scores are formed transposed (S^T = K Q^T) so the
-//     probabilities are already in the operand layout of the second product O^T = V^T P^T,
-//     and only V passes through a private LDS tile to be read transposed.
-//   * The wavefronts' partial (max, sum, O) are merged through LDS in a fixed order; splits
-//     are merged by a second small kernel (skipped when there is a single split).
+//   * Keys are numbered prefix first, tree after (key L+u is tree node u), and processed in
+//     64-key blocks; a split owns a contiguous run of blocks, computed from prefix_len[b] on
+//     the device.  K and V tiles are fetched with full-line 16-byte loads one block ahead of
+//     their use (registers), then parked in padded LDS tiles; K of block i+1 and V of block i
+//     are written between the two barriers of block i, so single tiles suffice and two
+//     workgroups fit on a CU to cover each other's latencies.
+//   * Scores are formed transposed, S^T = K Q^T: wavefront w owns keys 16w..16w+15 of the block
+//     for all query rows, so each lane owns one query column per tile and the row maximum needs
+//     two cross-lane steps plus one exchange of 4 x rows floats through LDS.  The probabilities
+//     go to LDS as bf16 [query][key]; in the second product O^T = V^T P^T wavefront w owns a
+//     quarter of the head dimension for all query rows, so the output accumulators are never
+//     merged across wavefronts.  Two barriers per 64 keys.
+//   * The tree mask is the 128-bit ancestor word of the lane's query node shifted to the block's
+//     key range; keys past the valid range are redirected to a valid row and masked, so stale or
+//     poisoned cache rows are never used.
+//   * A split writes its partial as fp16 output normalised by its own soft-max sum plus the
+//     fp32 running maximum and sum; a second small kernel merges the splits in index order
+//     (skipped when there is a single split), so results are run-to-run bit-identical.  Merging
+//     inside the first kernel (last split elected by a ticket) was tried and measured slower:
+//     one workgroup pulling all partials of a head is a serial tail of several round trips.
 // fp32 path (and any D the MFMA path does not cover): one workgroup per query row, plain FMAs.
 #include <math.h>
+#include <stdlib.h>
 
 #include "common.hpp"
 
 namespace {
 
-constexpr int kBlkKeys = 32;
+constexpr int kBlkKeys = 64;
 
 struct AttnArgs {
   const void *q, *k_tree, *v_tree, *k_cache, *v_cache;
   const int32_t* prefix_len;
   const TreeTables* tree;
   void* out;
-  float* ws_o;       // [B*Hkv*n_splits][R][D] un-normalised partial outputs
-  float* ws_ml;      // [B*Hkv*n_splits][R][2] (running max in log2 units, sum)
+  uint64_t* ws_o;    // [B*Hkv*n_splits][R][D/4] partial outputs, normalised by their own sum, 4 x fp16
+  uint64_t* ws_ml;   // [B*Hkv*n_splits][R] (running max in log2 units, sum) as two floats
   int B, Hq, Hkv, T, Lcap, G, R, n_splits, row_blocks;
   float scale;
 };
@@ -123,31 +136,46 @@ __global__ __launch_bounds__(256) void tree_attn_plain_kernel(AttnArgs a) {
 // MFMA split-K kernel, bf16.  grid (n_splits, Hkv*row_blocks, B), 256 threads.
 // Operand layout of v_mfma_f32_16x16x32_bf16 (A: 16 x 32, B: 32 x 16, C: 16 x 16): lane l
 // holds row (A) / column (B) l%16 and reduction elements 8*(l/16)..+7; it receives column
-// l%16 and rows 4*(l/16)..+3 of C.  The reduction index may be permuted freely as long as A
-// and B agree, which is what lets P^T be consumed where S^T was produced.
+// l%16 and rows 4*(l/16)..+3 of C.
 // ---------------------------------------------------------------------------------------
-template <int D, int MT>
-__global__ __launch_bounds__(256) void tree_attn_mfma_kernel(AttnArgs a) {
-  constexpr int KS = D / 32;                  // reduction steps of K Q^T
-  constexpr int DT = D / 16;                  // 16-wide tiles of the head dimension
-  constexpr int VSTR = D + 8;                 // padded LDS row stride of the V tile (elements)
-  constexpr int V_BYTES = 4 * kBlkKeys * VSTR * 2;
-  constexpr int MERGE_BYTES = 2 * MT * DT * 64 * 16;
-  constexpr int POOL = V_BYTES > MERGE_BYTES ? V_BYTES : MERGE_BYTES;
-  __shared__ __attribute__((aligned(16))) unsigned char pool[POOL];
-  __shared__ float s_m[4][16 * MT];
-  __shared__ float s_l[2][16 * MT];
+typedef short short4_t __attribute__((ext_vector_type(4)));
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+// Four bf16 of a transposed tile: within each group of 16 lanes, lane j of the group receives
+// element (j % 4) of the 8-byte rows addressed by lanes j/4, j/4 + 4, j/4 + 8, j/4 + 12 of the
+// group (ds_read_b64_tr_b16).  With lane r addressing V[key0 + r/4][d0 + 4*(r%4) .. +3], lane j
+// receives V[key0 .. key0+3][d0 + j]: four consecutive keys of one head-dimension column.
+__device__ __forceinline__ short4_t lds_read_tr16(const unsigned char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4_t*)p);
+}
+
+template <int D, int MT>
+__global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
+  constexpr int KS = D / 32;                    // reduction steps of K Q^T
+  constexpr int DPW = D / 64;                   // 16-wide output tiles of the head dimension per wavefront
+  constexpr int PITCH = D * 2 + 16;             // LDS row pitch of the K and V tiles (bytes)
+  constexpr int TENSOR_BYTES = kBlkKeys * PITCH;
+  constexpr int PPITCH = kBlkKeys * 2 + 16;     // LDS row pitch of the probability tile (bytes)
+  constexpr int CPR = D / 8;                    // 16-byte chunks per K/V row
+  constexpr int LPT = kBlkKeys * CPR / 256;     // chunks per thread per block and tensor
+  __shared__ __attribute__((aligned(16))) unsigned char s_k[TENSOR_BYTES];
+  __shared__ __attribute__((aligned(16))) unsigned char s_v[TENSOR_BYTES];
+  __shared__ __attribute__((aligned(16))) unsigned char s_p[16 * MT * PPITCH];
+  __shared__ float s_max[4][16 * MT];
+  __shared__ float s_sum[4][16 * MT];
+  __shared__ uint64_t s_anc[16 * MT][2];        // ancestor mask of every query row of this workgroup
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, q4 = lane >> 4;
   const int split = blockIdx.x;
   const int kvh = blockIdx.y / a.row_blocks, rb = blockIdx.y - kvh * a.row_blocks;
   const int b = blockIdx.z;
   const int T = a.T, R = a.R;
   const int L = min(max(a.prefix_len[b], 0), a.Lcap);
-  const int nblk_p = ceil_div(L, kBlkKeys), nblk = nblk_p + ceil_div(T, kBlkKeys);
+  const int n_keys = L + T;
+  const int nblk = ceil_div(n_keys, kBlkKeys);
   const int bps = ceil_div(nblk, a.n_splits);
-  const int blk_lo = split * bps, blk_hi = min(nblk, blk_lo + bps);
+  const int blk_lo = min(split * bps, nblk), blk_hi = min(nblk, blk_lo + bps);
+  const int n_iter = blk_hi - blk_lo;
   const int row0 = rb * 16 * MT;
 
   const uint16_t* qg = (const uint16_t*)a.q + ((size_t)b * a.Hq + (size_t)kvh * a.G) * T * D;
@@ -156,237 +184,238 @@ __global__ __launch_bounds__(256) void tree_attn_mfma_kernel(AttnArgs a) {
   const uint16_t* kt = (const uint16_t*)a.k_tree + ((size_t)b * a.Hkv + kvh) * T * D;
   const uint16_t* vt = (const uint16_t*)a.v_tree + ((size_t)b * a.Hkv + kvh) * T * D;
 
-  // Q^T fragments (B operand): column = query row, reduction = head dimension.
+  if (tid < 16 * MT) {
+    const int tq = min(row0 + tid, R - 1) % T;
+    s_anc[tid][0] = a.tree->anc_mask[tq][0];
+    s_anc[tid][1] = a.tree->anc_mask[tq][1];
+  }
+  // Q^T fragments (B operand of K Q^T): column = query row, reduction = head dimension.
   bf16x8_t qf[MT][KS];
-  int tq[MT];                                  // tree node of this lane's query column
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int r = min(row0 + 16 * mt + i16, R - 1);
-    tq[mt] = r % T;
 #pragma unroll
     for (int c = 0; c < KS; ++c) qf[mt][c] = *(const bf16x8_t*)(qg + (size_t)r * D + 32 * c + 8 * q4);
   }
 
-  floatx4_t o[MT][DT];
+  // This thread's chunks of a K (or V) block: row in the block, element offset, LDS offset.
+  int ch_row[LPT], ch_off[LPT], ch_dst[LPT];
+#pragma unroll
+  for (int it = 0; it < LPT; ++it) {
+    const int id = it * 256 + tid;
+    ch_row[it] = id / CPR;
+    const int col = (id - ch_row[it] * CPR) * 8;
+    ch_off[it] = ch_row[it] * D + col;
+    ch_dst[it] = ch_row[it] * PITCH + col * 2;
+  }
+  // One tensor's rows of block `iter` of this split (index clamped into the split's range;
+  // the redundant reloads past the end are never used).
+  auto gload = [&](int iter, const uint16_t* cache, const uint16_t* tree_rows, u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
+    const int key0 = (blk_lo + min(iter, n_iter - 1)) * kBlkKeys;
+    if (key0 + kBlkKeys <= L) {                  // the common case: the whole block lies in the prefix
+      const uint16_t* base = cache + (size_t)key0 * D;
+#pragma unroll
+      for (int it = 0; it < LPT; ++it) r[it] = *(const u32x4_t*)(base + ch_off[it]);
+    } else {
+#pragma unroll
+      for (int it = 0; it < LPT; ++it) {
+        const int key = min(key0 + ch_row[it], n_keys - 1);   // keys past the end repeat the last key (masked)
+        const int col = ch_off[it] - ch_row[it] * D;
+        const uint16_t* base = key < L ? cache + (size_t)key * D : tree_rows + (size_t)(key - L) * D;
+        r[it] = *(const u32x4_t*)(base + col);
+      }
+    }
+  };
+  auto lstore = [&](unsigned char* tile, const u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int it = 0; it < LPT; ++it) *(u32x4_t*)(tile + ch_dst[it]) = r[it];
+  };
+
+  floatx4_t o[MT][DPW];
   float m_run[MT], l_run[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     m_run[mt] = -INFINITY;
     l_run[mt] = 0.f;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) o[mt][dt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    for (int dd = 0; dd < DPW; ++dd) o[mt][dd] = floatx4_t{0.f, 0.f, 0.f, 0.f};
   }
-  const float sc = a.scale * 1.4426950408889634f;      // scores are kept in log2 units
-  uint16_t* vt_lds = (uint16_t*)pool + wave * kBlkKeys * VSTR;
+  const float sc = a.scale * 1.4426950408889634f;        // scores are kept in log2 units
+  const int kf_off = (16 * wave + i16) * PITCH + q4 * 16;
+  const int p_wr_off = i16 * PPITCH + (16 * wave + 4 * q4) * 2;
+  const int p_rd_off = i16 * PPITCH + 8 * q4 * 2;
+  // transposed V read: lane r of a 16-lane group addresses V[8*q4 + r/4 (+4)][16*dd' + 4*(r%4) .. +3]
+  const int v_rd_off = (8 * q4 + (i16 >> 2)) * PITCH + (16 * (wave * DPW) + 4 * (i16 & 3)) * 2;
 
-  for (int blk = blk_lo + wave; blk < blk_hi; blk += 4) {
-    const bool is_tree = blk >= nblk_p;
-    const int key0 = (is_tree ? blk - nblk_p : blk) * kBlkKeys;
-    const int nvalid = is_tree ? T : L;
-    const uint16_t* kbase = is_tree ? kt : kc;
-    const uint16_t* vbase = is_tree ? vt : vc;
+  u32x4_t kreg[LPT], vreg[LPT];
+  if (n_iter > 0) {
+    gload(0, kc, kt, kreg);
+    gload(0, vc, vt, vreg);
+    lstore(s_k, kreg);
+    gload(1, kc, kt, kreg);
+  }
+  __syncthreads();
 
-    // K fragments (A operand): row = key, reduction = head dimension.  Rows past the valid
-    // range are redirected to the last valid row and masked below.
-    bf16x8_t kf[2][KS];
+  for (int i = 0; i < n_iter; ++i) {
+    // here: K of block i is in LDS, K of block i+1 and V of block i are in registers (or in flight)
+    const int key0 = (blk_lo + i) * kBlkKeys;
+    // ---- S^T for this wavefront's 16 keys, all query tiles ----
+    bf16x8_t kf[KS];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int key = min(key0 + 16 * j + i16, nvalid - 1);
-#pragma unroll
-      for (int c = 0; c < KS; ++c) kf[j][c] = *(const bf16x8_t*)(kbase + (size_t)key * D + 32 * c + 8 * q4);
-    }
-    // V tile -> this wavefront's LDS region, row-major with padded stride.
-    {
-      constexpr int CPR = D / 8;               // 16-byte chunks per row
-#pragma unroll
-      for (int it = 0; it < kBlkKeys * CPR / 64; ++it) {
-        const int id = it * 64 + lane;
-        const int row = id / CPR, col = id - row * CPR;
-        const int key = min(key0 + row, nvalid - 1);
-        const u32x4_t v = *(const u32x4_t*)(vbase + (size_t)key * D + col * 8);
-        *(u32x4_t*)(vt_lds + row * VSTR + col * 8) = v;
-      }
-    }
-
-    // S^T tiles and the online soft-max, one 16-row query tile at a time.
-    bf16x8_t pf[MT];
+    for (int c = 0; c < KS; ++c) kf[c] = *(const bf16x8_t*)(s_k + kf_off + c * 64);
+    floatx4_t sv[MT];
+    const bool all_visible = key0 + kBlkKeys <= L;
+    const int sh = L - key0;                              // position of tree node 0 inside the block
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-      floatx4_t s[2];
+      floatx4_t s = floatx4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        s[j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+      for (int c = 0; c < KS; ++c) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[c], qf[mt][c], s, 0, 0, 0);
+      s *= sc;
+      if (!all_visible) {
+        // keys key0 .. key0+63: prefix keys are visible to all, tree key L+u iff ancestor bit u
+        const uint64_t lo = s_anc[16 * mt + i16][0], hi = s_anc[16 * mt + i16][1];
+        uint64_t tree_bits;
+        if (sh >= 0) tree_bits = lo << sh;
+        else if (sh > -64) tree_bits = (lo >> (-sh)) | (hi << (64 + sh));
+        else tree_bits = hi >> (-sh - 64);
+        const uint64_t vis = tree_bits | (sh > 0 ? (1ull << sh) - 1ull : 0ull);
+        const uint32_t my = (uint32_t)(vis >> (16 * wave + 4 * q4));
 #pragma unroll
-        for (int c = 0; c < KS; ++c) s[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[j][c], qf[mt][c], s[j], 0, 0, 0);
+        for (int r = 0; r < 4; ++r) s[r] = (my >> r) & 1u ? s[r] : -INFINITY;
       }
-      // visibility of key (key0 + 16j + 4*q4 + r) for this lane's query column
-      uint32_t vis;
-      {
-        const int left = nvalid - key0;        // >= 1
-        vis = left >= 32 ? 0xffffffffu : ((1u << left) - 1u);
-        if (is_tree) vis &= (uint32_t)(a.tree->anc_mask[tq[mt]][key0 >> 6] >> (key0 & 63));
-      }
-      float mx = -INFINITY;
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const bool ok = (vis >> (16 * j + 4 * q4 + r)) & 1u;
-          const float v = ok ? s[j][r] * sc : -INFINITY;
-          s[j][r] = v;
-          mx = fmaxf(mx, v);
-        }
+      sv[mt] = s;
+      float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
       mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
       mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+      if (q4 == 0) s_max[wave][16 * mt + i16] = mx;
+    }
+    __syncthreads();        // A: block maxima are visible; every wavefront has left block i-1 and the K tile
+    // ---- online soft-max update, probabilities to LDS ----
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int c = 16 * mt + i16;
+      const float mx = fmaxf(fmaxf(s_max[0][c], s_max[1][c]), fmaxf(s_max[2][c], s_max[3][c]));
       const float m_new = fmaxf(m_run[mt], mx);
       const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = exp2f(m_run[mt] - m_safe);
-      float psum = 0.f;
-      float p[8];
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          p[4 * j + r] = exp2f(s[j][r] - m_safe);
-          psum += p[4 * j + r];
-        }
-      l_run[mt] = l_run[mt] * alpha + psum;
+      const float alpha = __builtin_amdgcn_exp2f(m_run[mt] - m_safe);
+      const float p0 = __builtin_amdgcn_exp2f(sv[mt][0] - m_safe), p1 = __builtin_amdgcn_exp2f(sv[mt][1] - m_safe);
+      const float p2 = __builtin_amdgcn_exp2f(sv[mt][2] - m_safe), p3 = __builtin_amdgcn_exp2f(sv[mt][3] - m_safe);
+      l_run[mt] = l_run[mt] * alpha + ((p0 + p1) + (p2 + p3));
       m_run[mt] = m_new;
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) o[mt][dt] *= alpha;
-      // P^T fragment (B operand): reduction slot e <-> key 4*q4 + e (tile 0), 16 + 4*q4 + e - 4 (tile 1)
-      u32x4_t packed;
-      packed.x = pack_bf16x2(p[0], p[1]);
-      packed.y = pack_bf16x2(p[2], p[3]);
-      packed.z = pack_bf16x2(p[4], p[5]);
-      packed.w = pack_bf16x2(p[6], p[7]);
-      pf[mt] = __builtin_bit_cast(bf16x8_t, packed);
+      for (int dd = 0; dd < DPW; ++dd) o[mt][dd] *= alpha;
+      u32x2_t w;
+      w.x = pack_bf16x2(p0, p1);
+      w.y = pack_bf16x2(p2, p3);
+      *(u32x2_t*)(s_p + 16 * mt * PPITCH + p_wr_off) = w;
     }
-
-    // O^T += V^T P^T.  A operand: row = head-dimension index, reduction slots as above.
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    // tiles: K of the next block (the K tile is free since barrier A), V of this block (the V tile
+    // was last read in block i-1, which every wavefront left before barrier A); then start the
+    // loads that will be parked one block from now
+    lstore(s_k, kreg);
+    lstore(s_v, vreg);
+    gload(i + 2, kc, kt, kreg);
+    gload(i + 1, vc, vt, vreg);
+    __syncthreads();        // B: probabilities, the V tile and the next K tile are visible
+    // ---- O^T += V^T P^T for this wavefront's slice of the head dimension ----
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      uint16_t e[8];
+    for (int ks = 0; ks < kBlkKeys / 32; ++ks) {
+      bf16x8_t pf[MT];
 #pragma unroll
-      for (int x = 0; x < 8; ++x) {
-        const int row = x < 4 ? 4 * q4 + x : 16 + 4 * q4 + (x - 4);
-        e[x] = vt_lds[row * VSTR + 16 * dt + i16];
+      for (int mt = 0; mt < MT; ++mt) pf[mt] = *(const bf16x8_t*)(s_p + 16 * mt * PPITCH + p_rd_off + 32 * ks * 2);
+#pragma unroll
+      for (int dd = 0; dd < DPW; ++dd) {
+        const unsigned char* vp = s_v + v_rd_off + 32 * ks * PITCH + 16 * dd * 2;
+        const short4_t v0 = lds_read_tr16(vp), v1 = lds_read_tr16(vp + 4 * PITCH);
+        typedef short short8_t __attribute__((ext_vector_type(8)));
+        const short8_t v8 = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+        const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, v8);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) o[mt][dd] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[mt], o[mt][dd], 0, 0, 0);
       }
-      u32x4_t packed;
-      packed.x = (uint32_t)e[0] | ((uint32_t)e[1] << 16);
-      packed.y = (uint32_t)e[2] | ((uint32_t)e[3] << 16);
-      packed.z = (uint32_t)e[4] | ((uint32_t)e[5] << 16);
-      packed.w = (uint32_t)e[6] | ((uint32_t)e[7] << 16);
-      const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, packed);
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) o[mt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[mt], o[mt][dt], 0, 0, 0);
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
   }
 
-  // ---- merge the four wavefronts (fixed order) -------------------------------------------
+  // ---- totals of the soft-max denominators: over this lane's key slots, lanes, wavefronts ----
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    l_run[mt] += __shfl_xor(l_run[mt], 16, kWave);
-    l_run[mt] += __shfl_xor(l_run[mt], 32, kWave);
-    if (q4 == 0) s_m[wave][16 * mt + i16] = m_run[mt];
+    float l = l_run[mt];
+    l += __shfl_xor(l, 16, kWave);
+    l += __shfl_xor(l, 32, kWave);
+    if (q4 == 0) s_sum[wave][16 * mt + i16] = l;
   }
-  __syncthreads();                               // also: every wavefront is done with its V tile
-  float m_all[MT];
+  __syncthreads();
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int c = 16 * mt + i16;
-    const float mm = fmaxf(fmaxf(s_m[0][c], s_m[1][c]), fmaxf(s_m[2][c], s_m[3][c]));
-    m_all[mt] = mm;
-    const float w = exp2f(m_run[mt] - (mm == -INFINITY ? 0.f : mm));
-    l_run[mt] *= w;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) o[mt][dt] *= w;
-  }
-  floatx4_t* mbuf = (floatx4_t*)pool;           // [2][MT*DT][64]
-  // round 1: waves 2,3 -> LDS; waves 0,1 add.  round 2: wave 1 -> LDS; wave 0 adds.
-  if (wave >= 2) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) mbuf[((wave - 2) * MT * DT + mt * DT + dt) * 64 + lane] = o[mt][dt];
-      if (q4 == 0) s_l[wave - 2][16 * mt + i16] = l_run[mt];
-    }
-  }
-  __syncthreads();
-  if (wave < 2) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) o[mt][dt] += mbuf[(wave * MT * DT + mt * DT + dt) * 64 + lane];
-      l_run[mt] += s_l[wave][16 * mt + i16];
-    }
-  }
-  __syncthreads();
-  if (wave == 1) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) mbuf[(mt * DT + dt) * 64 + lane] = o[mt][dt];
-      if (q4 == 0) s_l[0][16 * mt + i16] = l_run[mt];
-    }
-  }
-  __syncthreads();
-  if (wave != 0) return;
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) o[mt][dt] += mbuf[(mt * DT + dt) * 64 + lane];
-    l_run[mt] += s_l[0][16 * mt + i16];
+    l_run[mt] = (s_sum[0][c] + s_sum[1][c]) + (s_sum[2][c] + s_sum[3][c]);
   }
 
   // ---- write: final output (single split) or the split's partial ----------------------------
+  typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+  typedef float float4v_t __attribute__((ext_vector_type(4)));
+  uint16_t* og = (uint16_t*)a.out + ((size_t)b * a.Hq + (size_t)kvh * a.G) * T * D;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int r = row0 + 16 * mt + i16;
     if (r >= R) continue;
+    const float inv = l_run[mt] > 0.f ? 1.0f / l_run[mt] : 0.f;
     if (a.n_splits == 1) {
-      const float inv = 1.0f / l_run[mt];
-      uint16_t* orow = (uint16_t*)a.out + ((size_t)b * a.Hq + (size_t)kvh * a.G) * T * D + (size_t)r * D;
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
+      for (int dd = 0; dd < DPW; ++dd) {
         u32x2_t w;
-        w.x = pack_bf16x2(o[mt][dt][0] * inv, o[mt][dt][1] * inv);
-        w.y = pack_bf16x2(o[mt][dt][2] * inv, o[mt][dt][3] * inv);
-        *(u32x2_t*)(orow + 16 * dt + 4 * q4) = w;
+        w.x = pack_bf16x2(o[mt][dd][0] * inv, o[mt][dd][1] * inv);
+        w.y = pack_bf16x2(o[mt][dd][2] * inv, o[mt][dd][3] * inv);
+        *(u32x2_t*)(og + (size_t)r * D + 16 * (wave * DPW + dd) + 4 * q4) = w;
       }
     } else {
       const size_t unit = ((size_t)b * a.Hkv + kvh) * a.n_splits + split;
-      float* prow = a.ws_o + (unit * R + r) * D;
+      uint64_t* prow = a.ws_o + (unit * R + r) * (D / 4);
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) *(floatx4_t*)(prow + 16 * dt + 4 * q4) = o[mt][dt];
-      if (q4 == 0) {
-        a.ws_ml[(unit * R + r) * 2 + 0] = m_all[mt];
-        a.ws_ml[(unit * R + r) * 2 + 1] = l_run[mt];
+      for (int dd = 0; dd < DPW; ++dd) {
+        const float4v_t f = {o[mt][dd][0] * inv, o[mt][dd][1] * inv, o[mt][dd][2] * inv, o[mt][dd][3] * inv};
+        prow[4 * (wave * DPW + dd) + q4] = __builtin_bit_cast(uint64_t, __builtin_convertvector(f, half4_t));
+      }
+      if (wave == 0 && q4 == 0) {
+        const f32x2_t ml = {m_run[mt], l_run[mt]};
+        a.ws_ml[unit * R + r] = __builtin_bit_cast(uint64_t, ml);
       }
     }
   }
 }
 
-// Merge the splits of one query row.  grid (R, Hkv, B), D threads.
+// Merge the splits of a (sequence, KV head): grid (ceil(R*D/4 / 256), Hkv, B), 256 threads, one
+// thread per (query row, four output columns), splits in index order.
 template <int D>
-__global__ __launch_bounds__(D) void tree_attn_combine_kernel(AttnArgs a) {
-  const int r = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z, dcol = threadIdx.x;
+__global__ __launch_bounds__(256) void tree_attn_combine_kernel(AttnArgs a) {
+  typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+  const int u = blockIdx.x * 256 + threadIdx.x;
+  const int kvh = blockIdx.y, b = blockIdx.z;
+  const int R = a.R;
+  if (u >= R * (D / 4)) return;
+  const int r = u / (D / 4), c4 = u % (D / 4);
   const size_t unit0 = ((size_t)b * a.Hkv + kvh) * a.n_splits;
   float mm = -INFINITY;
-  for (int s = 0; s < a.n_splits; ++s) mm = fmaxf(mm, a.ws_ml[((unit0 + s) * a.R + r) * 2]);
-  float num = 0.f, den = 0.f;
-  for (int s = 0; s < a.n_splits; ++s) {
-    const size_t row = (unit0 + s) * a.R + r;
-    const float w = exp2f(a.ws_ml[row * 2] - mm);
-    den += w * a.ws_ml[row * 2 + 1];
-    num += w * a.ws_o[row * D + dcol];
+  for (int sp = 0; sp < a.n_splits; ++sp) {
+    const f32x2_t ml = __builtin_bit_cast(f32x2_t, a.ws_ml[(unit0 + sp) * R + r]);
+    mm = fmaxf(mm, ml[0]);
   }
-  uint16_t* orow = (uint16_t*)a.out + ((size_t)b * a.Hq + (size_t)kvh * a.G) * a.T * D + (size_t)r * D;
-  orow[dcol] = (uint16_t)float_to_bf16_bits(num / den);
+  float num[4] = {0.f, 0.f, 0.f, 0.f}, den = 0.f;
+  for (int sp = 0; sp < a.n_splits; ++sp) {
+    const f32x2_t ml = __builtin_bit_cast(f32x2_t, a.ws_ml[(unit0 + sp) * R + r]);
+    const float w = ml[1] > 0.f ? __builtin_amdgcn_exp2f(ml[0] - mm) * ml[1] : 0.f;
+    const half4_t h = __builtin_bit_cast(half4_t, a.ws_o[((unit0 + sp) * R + r) * (D / 4) + c4]);
+    den += w;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) num[e] += w * (float)h[e];
+  }
+  const float inv = 1.0f / den;
+  uint16_t* og = (uint16_t*)a.out + ((size_t)b * a.Hq + (size_t)kvh * a.G) * a.T * D;
+  u32x2_t w;
+  w.x = pack_bf16x2(num[0] * inv, num[1] * inv);
+  w.y = pack_bf16x2(num[2] * inv, num[3] * inv);
+  *(u32x2_t*)(og + (size_t)r * D + 4 * c4) = w;
 }
 
 struct Plan {
@@ -399,11 +428,14 @@ Plan make_plan(int B, int Hq, int Hkv, int T, int Lcap) {
   const int tiles = ceil_div(R, 16);
   p.mt = tiles >= 5 ? 5 : tiles;
   p.row_blocks = ceil_div(tiles, p.mt);
-  const int blocks = ceil_div(Lcap, kBlkKeys) + ceil_div(T, kBlkKeys);
+  const int blocks = ceil_div(Lcap + T, kBlkKeys);
   const int base = B * Hkv * p.row_blocks;
-  int want = ceil_div(384, base);
-  const int cap = blocks / 8 > 1 ? blocks / 8 : 1;   // at least ~256 keys per split
-  p.n_splits = want < 1 ? 1 : (want > cap ? cap : want);
+  // two workgroups fit on a CU: aim at ~2 x 256 of them, but keep at least four key blocks per
+  // split: each split costs a partial write and read of about 80 keys' worth of bytes
+  int want = 512 / base;
+  const int cap = blocks / 4 > 1 ? blocks / 4 : 1;
+  want = want < 1 ? 1 : (want > cap ? cap : want);
+  p.n_splits = ceil_div(blocks, ceil_div(blocks, want));
   return p;
 }
 
@@ -419,7 +451,8 @@ int launch_mfma(const AttnArgs& a, const Plan& p, hipStream_t stream) {
   }
   MEDUSA_LAUNCH_CHECK();
   if (a.n_splits > 1) {
-    hipLaunchKernelGGL((tree_attn_combine_kernel<D>), dim3(a.R, a.Hkv, a.B), dim3(D), 0, stream, a);
+    hipLaunchKernelGGL((tree_attn_combine_kernel<D>), dim3(ceil_div(a.R * (D / 4), 256), a.Hkv, a.B), dim3(256), 0,
+                       stream, a);
     MEDUSA_LAUNCH_CHECK();
   }
   return MEDUSA_OK;
@@ -431,7 +464,7 @@ extern "C" size_t tree_attention_workspace_bytes(int B, int Hq, int Hkv, int T, 
   if (B < 1 || Hq < 1 || Hkv < 1 || T < 1 || D < 1 || Lcap < 1 || Hq % Hkv != 0) return 0;
   const Plan p = make_plan(B, Hq, Hkv, T, Lcap);
   const size_t R = (size_t)(Hq / Hkv) * T;
-  const size_t bytes = (size_t)B * Hkv * p.n_splits * R * (D + 2) * sizeof(float);
+  const size_t bytes = (size_t)B * Hkv * p.n_splits * R * (D * 2 + 8);   // fp16 rows + (max, sum)
   return (bytes + 255) & ~(size_t)255;
 }
 
@@ -461,8 +494,8 @@ extern "C" int tree_attention(const void* q, const void* k_tree, const void* v_t
   a.n_splits = p.n_splits;
   a.row_blocks = p.row_blocks;
   a.scale = scale;
-  a.ws_o = (float*)workspace;
-  a.ws_ml = a.ws_o + (size_t)B * Hkv * p.n_splits * a.R * D;
+  a.ws_o = (uint64_t*)workspace;
+  a.ws_ml = a.ws_o + (size_t)B * Hkv * p.n_splits * a.R * (D / 4);
   if (dtype == MEDUSA_F32) {
     const dim3 grid(T, Hq, B), block(256);
     if (D == 64) hipLaunchKernelGGL((tree_attn_plain_kernel<float, 64>), grid, block, 0, stream, a);
