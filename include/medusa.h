@@ -83,6 +83,16 @@ const char* medusa_status_string(int status);
 int medusa_tree_create_cartesian(const int32_t* branching /* host [K] */, int K, medusa_tree_t** out);
 int medusa_tree_create_nodes(const int32_t* ranks /* host [n_nodes][K] */, int n_nodes, int K,
                              medusa_tree_t** out);
+/* medusa_tree_create_optimized (Sec. 2.3.3, appendix on the optimized tree): `accuracy` is a
+ *   host array [K][S]; accuracy[k-1][i] estimates how often the i-th best prediction of head k is
+ *   the right token (values in [0,1]).  A node (i_1..i_k) is estimated correct with probability
+ *   prod_j accuracy[j-1][i_j], which is also its contribution to the expected acceptance length;
+ *   the tree of n_nodes candidates maximising the sum is grown greedily from the root by always
+ *   adding the best child of an included node (ties: shallower, then lexicographically smaller).
+ *   K <= 8, S <= 16, n_nodes <= 127 and <= the number of nodes that exist.  If
+ *   expected_accept_len is not NULL it receives 1 + the sum of the chosen nodes' estimates. */
+int medusa_tree_create_optimized(const double* accuracy /* host [K][S] */, int K, int S, int n_nodes,
+                                 medusa_tree_t** out, double* expected_accept_len);
 int medusa_tree_destroy(medusa_tree_t* tree);
 
 /* Sizes: T tokens, K levels, n_leaves candidates (root-to-leaf paths), S = max_k S_k,

@@ -161,6 +161,36 @@ def tree_cartesian(branching: Sequence[int]) -> Tree:
     return tree_from_nodes(cand)
 
 
+def tree_optimized(accuracy: np.ndarray, n_nodes: int):
+    """Sec. 2.3.3: accuracy[k-1][i] is the accuracy of the i-th best prediction of head k; a node
+    (i_1..i_k) is estimated correct with probability prod_j accuracy[j-1][i_j] and contributes that
+    much to the expected acceptance length.  Nodes are added one by one: always the node connected
+    to the current tree (its parent is in it) with the highest estimate; ties go to the shallower
+    node, then to the lexicographically smaller rank tuple.  Returns (Tree, expected accept length
+    with the root counted)."""
+    accuracy = np.asarray(accuracy, dtype=np.float64)
+    K, S = accuracy.shape
+
+    def estimate(t):
+        p = 1.0
+        for j, r in enumerate(t):
+            p *= accuracy[j, r]
+        return p
+
+    tree_nodes = [()]
+    chosen: List[Tuple[int, ...]] = []
+    expect = 1.0
+    for _ in range(n_nodes):
+        cands = [t + (r,) for t in tree_nodes if len(t) < K for r in range(S) if t + (r,) not in tree_nodes]
+        if not cands:
+            raise ValueError("fewer nodes exist than requested")
+        best = min(cands, key=lambda t: (-estimate(t), len(t), t))
+        tree_nodes.append(best)
+        chosen.append(best)
+        expect += estimate(best)
+    return tree_from_nodes(chosen), expect
+
+
 # --------------------------------------------------------------------------
 # (1) candidate generation: Medusa heads (Sec. 2.1.1) and top-k / tree tokens (Sec. 2.1.2)
 # --------------------------------------------------------------------------

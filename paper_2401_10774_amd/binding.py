@@ -21,7 +21,8 @@ MEDUSA_F32, MEDUSA_BF16 = 0, 1
 MEDUSA_GREEDY, MEDUSA_TYPICAL = 0, 1
 
 EXPORTED_SYMBOLS = (
-    "medusa_status_string", "medusa_tree_create_cartesian", "medusa_tree_create_nodes", "medusa_tree_destroy",
+    "medusa_status_string", "medusa_tree_create_cartesian", "medusa_tree_create_nodes",
+    "medusa_tree_create_optimized", "medusa_tree_destroy",
     "medusa_tree_query", "medusa_tree_tables", "medusa_heads", "medusa_topk_tree_workspace_bytes",
     "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "medusa_accept_workspace_bytes",
     "medusa_accept", "kv_commit", "medusa_profile_set_events",
@@ -50,6 +51,7 @@ def lib() -> ctypes.CDLL:
         L.medusa_status_string.argtypes = [c_int]
         L.medusa_tree_create_cartesian.argtypes = [c_void_p, c_int, ctypes.POINTER(c_void_p)]
         L.medusa_tree_create_nodes.argtypes = [c_void_p, c_int, c_int, ctypes.POINTER(c_void_p)]
+        L.medusa_tree_create_optimized.argtypes = [c_void_p, c_int, c_int, c_int, ctypes.POINTER(c_void_p), c_void_p]
         L.medusa_tree_destroy.argtypes = [c_void_p]
         L.medusa_tree_query.argtypes = [c_void_p] + [c_void_p] * 5
         L.medusa_tree_tables.argtypes = [c_void_p] + [c_void_p] * 6
@@ -118,12 +120,23 @@ def _scratch(nbytes: int, device) -> torch.Tensor:
 class MedusaTree:
     """Handle of a candidate tree (Sec. 2.1.2) plus host copies of its tables."""
 
-    def __init__(self, branching: Optional[Sequence[int]] = None, nodes: Optional[Sequence[Sequence[int]]] = None):
+    def __init__(self, branching: Optional[Sequence[int]] = None, nodes: Optional[Sequence[Sequence[int]]] = None,
+                 accuracy=None, n_nodes: Optional[int] = None):
         L = lib()
         handle = ctypes.c_void_p()
-        if (branching is None) == (nodes is None):
-            raise MedusaError("give exactly one of branching / nodes")
-        if branching is not None:
+        self.expected_accept_len = None
+        if sum(x is not None for x in (branching, nodes, accuracy)) != 1:
+            raise MedusaError("give exactly one of branching / nodes / accuracy")
+        if accuracy is not None:
+            acc = np.ascontiguousarray(accuracy, dtype=np.float64)
+            if acc.ndim != 2 or n_nodes is None:
+                raise MedusaError("accuracy must be a [K][S] table and n_nodes given")
+            expect = ctypes.c_double()
+            _check(L.medusa_tree_create_optimized(acc.ctypes.data, acc.shape[0], acc.shape[1], int(n_nodes),
+                                                  ctypes.byref(handle), ctypes.addressof(expect)),
+                   "medusa_tree_create_optimized")
+            self.expected_accept_len = expect.value
+        elif branching is not None:
             arr = np.ascontiguousarray(branching, dtype=np.int32)
             _check(L.medusa_tree_create_cartesian(arr.ctypes.data, int(arr.size), ctypes.byref(handle)),
                    "medusa_tree_create_cartesian")

@@ -11,8 +11,6 @@
 //                     activation rows x 128 weight rows per workgroup (128 x 128 for M > 80).
 //   * fp32          : plain FMA version of the first scheme (small configurations only).
 // The residual block's epilogue applies SiLU, adds h and rounds once to the storage type.
-#include <stdlib.h>
-
 #include "common.hpp"
 
 namespace {
@@ -165,20 +163,23 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(GemmArgs a) {
 // bf16, M > 4: LDS-staged MFMA GEMM (v_mfma_f32_16x16x32_bf16).
 //
 // Workgroup tile BM x BN = (WM*16*MT activation rows) x (WN*16*NT weight rows), four wavefronts
-// arranged WM x WN, reduction in steps of BK = 64 elements = one 128-byte line per row.  Both
+// arranged WM x WN, reduction in steps of BK elements (64 = one 128-byte line per row; 128 measured no faster:
+// a stand-alone read kernel with this tile-wise pattern tops out at 5.3-5.7 TB/s on this chip
+// whatever the bytes per row and step, against 6.2-7.0 TB/s for whole rows read in sequence).  Both
 // operands are fetched with 16-byte loads in which 8 consecutive lanes cover one full 128-byte
-// line of a row (half as many L2 requests per byte as loading MFMA operand layout directly, which
+// line of a row (at most half as many L2 requests per byte as loading MFMA operand layout directly, which
 // measured request-bound at ~3.5 TB/s), held in registers PD reduction steps ahead of their use,
 // then written to a double-buffered, padded LDS tile from which the wavefronts read their MFMA
 // operands (lane l: row l%16, elements 8*(l/16)..+7 of a 32-element step).  One barrier per step.
 // Output layout of the MFMA: lane l holds column l%16 (weight row), rows 4*(l/16)..+3
 // (activation rows).  grid (ceil(N/BN), K, ceil(M/BM)), 256 threads.
 // ---------------------------------------------------------------------------------------
-template <int WM, int WN, int MT, int NT, int PD, int EPI>
+template <int WM, int WN, int MT, int NT, int BK, int PD, int EPI>
 __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
-  constexpr int BM = WM * 16 * MT, BN = WN * 16 * NT, BK = 64;
-  constexpr int PITCH = BK * 2 + 16;                  // bytes per LDS row: 128 data + 16 pad
-  constexpr int CHUNKS = (BM + BN) * 8;               // 16-byte chunks per reduction step
+  constexpr int BM = WM * 16 * MT, BN = WN * 16 * NT;
+  constexpr int CPR = BK / 8;                         // 16-byte chunks per row and reduction step
+  constexpr int PITCH = BK * 2 + 16;                  // bytes per LDS row: data + 16 pad
+  constexpr int CHUNKS = (BM + BN) * CPR;             // 16-byte chunks per reduction step
   constexpr int LPT = (CHUNKS + 255) / 256;           // chunks per thread per step
   constexpr int STAGE_BYTES = (BM + BN) * PITCH;
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
 #pragma unroll
   for (int it = 0; it < LPT; ++it) {
     const int id = min(it * 256 + tid, CHUNKS - 1);
-    const int row = id >> 3, c = id & 7;
+    const int row = id / CPR, c = id - row * CPR;
     src[it] = row < BM ? X + (size_t)min(m0 + row, a.M - 1) * a.xs_m + c * 8
                        : W + (size_t)min(n0 + row - BM, a.N - 1) * a.d + c * 8;
     dst[it] = row * PITCH + c * 16;
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
   auto compute = [&](int buf, uint32_t keep) {
     const unsigned char* base = lds + buf * STAGE_BYTES;
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
+    for (int kk = 0; kk < BK / 32; ++kk) {
       bf16x8_t xf[MT], wf[NT];
 #pragma unroll
       for (int t = 0; t < MT; ++t) {
@@ -285,8 +286,6 @@ hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
 // Weight rows per GEMV workgroup: 16 measured best on MI355X at 7B shapes (8, 32 and 64 were
 // 1-10 % slower); fewer for small matrices so that the grid still covers the chip.
 int gemv_rows_per_wg(int N, int K) {
-  static const int forced = [] { const char* e = getenv("MEDUSA_GEMV_ROWS"); return e ? atoi(e) : 0; }();
-  if (forced >= 8 && forced % 8 == 0) return forced;
   long rows = ((long)N * K / 1024) & ~7L;
   return rows < 8 ? 8 : (rows > 16 ? 16 : (int)rows);
 }
@@ -316,13 +315,12 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
     // skinny: every wavefront sees all activation rows; 128 weight rows per workgroup when that
     // still yields a few hundred workgroups, else 64
     const int MT = ceil_div(a.M, 16);
-    static const int force_wide = [] { const char* e = getenv("MEDUSA_GEMM_WIDE"); return e ? atoi(e) : -1; }();
-    const bool wide = force_wide >= 0 ? force_wide != 0 : (long)ceil_div(a.N, 128) * a.K >= 200;
+    const bool wide = (long)ceil_div(a.N, 128) * a.K >= 200;   // measured at V = 32000: 52 us wide, 63 us narrow
     const dim3 grid(ceil_div(a.N, wide ? 128 : 64), a.K, 1);
-#define MEDUSA_SKINNY(MT_)                                                                                        \
-  case MT_:                                                                                                       \
-    if (wide) hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 2, 4, EPI>), grid, block, 0, stream, a);        \
-    else hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 1, 4, EPI>), grid, block, 0, stream, a);             \
+#define MEDUSA_SKINNY(MT_)                                                                                         \
+  case MT_:                                                                                                        \
+    if (!wide) hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 1, 64, 4, EPI>), grid, block, 0, stream, a);    \
+    else hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 2, 64, 4, EPI>), grid, block, 0, stream, a);          \
     break;
     switch (MT) {
       MEDUSA_SKINNY(1) MEDUSA_SKINNY(2) MEDUSA_SKINNY(3) MEDUSA_SKINNY(4) MEDUSA_SKINNY(5)
@@ -331,7 +329,7 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
   } else {
     // 128 x 128 tile, wavefronts 2 x 2, each 64 x 64
     const dim3 grid(ceil_div(a.N, 128), a.K, ceil_div(a.M, 128));
-    hipLaunchKernelGGL((gemm_lds_bf16_kernel<2, 2, 4, 4, 2, EPI>), grid, block, 0, stream, a);
+    hipLaunchKernelGGL((gemm_lds_bf16_kernel<2, 2, 4, 4, 64, 2, EPI>), grid, block, 0, stream, a);
   }
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;

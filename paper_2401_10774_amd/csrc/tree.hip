@@ -208,6 +208,62 @@ extern "C" int medusa_tree_create_nodes(const int32_t* ranks, int n_nodes, int K
   return build(cand, K, out);
 }
 
+// Sec. 2.3.3: with a_k^(i) the accuracy of the i-th best prediction of head k, a node
+// (i_1..i_k) is estimated to be correct with probability prod_j a_j^(i_j) and adds exactly that
+// much to the expected acceptance length, so the best tree of a given size is grown greedily:
+// repeatedly add the not-yet-included child of an included node with the highest estimate.
+// Ties: shallower node first, then the lexicographically smaller rank tuple.
+extern "C" int medusa_tree_create_optimized(const double* accuracy, int K, int S, int n_nodes, medusa_tree_t** out,
+                                            double* expected_accept_len) {
+  if (!accuracy || !out || K < 1 || S < 1 || n_nodes < 0) return MEDUSA_EINVAL;
+  if (K > MEDUSA_MAX_HEADS || S > MEDUSA_MAX_TOPK || n_nodes + 1 > MEDUSA_MAX_TREE_TOKENS) return MEDUSA_EUNSUPPORTED;
+  for (int i = 0; i < K * S; ++i)
+    if (!(accuracy[i] >= 0.0 && accuracy[i] <= 1.0)) return MEDUSA_EINVAL;
+  struct Cand {
+    Node n;
+    double p;
+  };
+  auto better = [](const Cand& a, const Cand& b) {   // strict "a is chosen before b"
+    if (a.p != b.p) return a.p > b.p;
+    return node_less(a.n, b.n);
+  };
+  std::vector<Cand> frontier, chosen;
+  Node root;
+  root.r.fill(-1);
+  root.len = 0;
+  auto push_children = [&](const Node& parent, double p) {
+    if (parent.len >= K) return;
+    for (int r = 0; r < S; ++r) {
+      Cand c;
+      c.n = parent;
+      c.n.r[c.n.len++] = r;
+      c.p = p * accuracy[(size_t)parent.len * S + r];
+      frontier.push_back(c);
+    }
+  };
+  push_children(root, 1.0);
+  double expect = 1.0;                                // the root is always accepted
+  while ((int)chosen.size() < n_nodes && !frontier.empty()) {
+    size_t best = 0;
+    for (size_t i = 1; i < frontier.size(); ++i)
+      if (better(frontier[i], frontier[best])) best = i;
+    const Cand c = frontier[best];
+    frontier.erase(frontier.begin() + best);
+    chosen.push_back(c);
+    expect += c.p;
+    push_children(c.n, c.p);
+  }
+  if ((int)chosen.size() < n_nodes) return MEDUSA_EINVAL;   // fewer than n_nodes nodes exist for this K, S
+  std::vector<Node> cand;
+  int depth = 0;
+  for (const Cand& c : chosen) {
+    cand.push_back(c.n);
+    depth = std::max(depth, c.n.len);
+  }
+  if (expected_accept_len) *expected_accept_len = expect;
+  return build(cand, depth, out);
+}
+
 extern "C" int medusa_tree_destroy(medusa_tree_t* tree) {
   if (!tree) return MEDUSA_EINVAL;
   int rc = MEDUSA_OK;

@@ -28,7 +28,6 @@
 //     one workgroup pulling all partials of a head is a serial tail of several round trips.
 // fp32 path (and any D the MFMA path does not cover): one workgroup per query row, plain FMAs.
 #include <math.h>
-#include <stdlib.h>
 
 #include "common.hpp"
 

@@ -17,7 +17,7 @@ import torch
 import paper_2401_10774_amd as M
 from paper_2401_10774_amd.step import VerificationStep
 from oracle import medusa_oracle as O
-from workloads import get_config, make_step_inputs
+from workloads import get_config, make_step_inputs, synthetic_accuracy_table
 from _harness import TOL, bits, poison_tail, row_rel_err, to_dev, to_host_bits, to_host_f64
 
 pytestmark = pytest.mark.gpu
@@ -51,13 +51,19 @@ def topk_gap(logits_row, s):
     return float(np.min(v[:-1] - v[1:])) if v.size > 1 else np.inf
 
 
-def run_config(name, nl=None, plant_seed=None):
+def run_config(name, nl=None, plant_seed=None, sparse=False):
     cfg = get_config(name)
     dtype = cfg.dtype
     x = make_step_inputs(cfg, nl=nl)
     x["k_cache"] = poison_tail(x["k_cache"], x["prefix_len"])
     x["v_cache"] = poison_tail(x["v_cache"], x["prefix_len"])
-    gt, ot = M.MedusaTree(branching=cfg.branching), O.tree_cartesian(cfg.branching)
+    if sparse:
+        # optimized sparse tree of the same size (Sec. 2.3.3) grown from the synthetic accuracy table
+        acc_table = synthetic_accuracy_table(cfg.K, 10)
+        gt, (ot, _) = M.MedusaTree(accuracy=acc_table, n_nodes=cfg.N), O.tree_optimized(acc_table, cfg.N)
+        assert gt.T == cfg.T and gt.K == cfg.K and np.array_equal(gt.parent, ot.parent)
+    else:
+        gt, ot = M.MedusaTree(branching=cfg.branching), O.tree_cartesian(cfg.branching)
     step = VerificationStep({k: to_dev(v) for k, v in x.items()}, gt, cfg.accept, cfg.temperature, cfg.eps, cfg.delta)
     plant_dev = plant_host = None
     if plant_seed is not None:
@@ -143,6 +149,15 @@ def test_c2_7b_planted_paths():
 
 def test_c3_long_context_typical():
     run_config("C3")
+
+
+def test_c2_optimized_sparse_tree_planted():
+    a = run_config("C2", nl=2, plant_seed=17, sparse=True)
+    assert a.max() >= 1
+
+
+def test_c3_optimized_sparse_tree_typical():
+    run_config("C3", sparse=True)
 
 
 def test_c4_13b_batch4_ragged():

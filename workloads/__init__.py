@@ -5,7 +5,7 @@ It contains none of the method's arithmetic: no heads, no tree construction, no
 attention, no acceptance.  Both the CPU oracle's tests and the HIP path's
 tests/benchmarks import it so that the two sides see byte-identical inputs.
 """
-from .configs import CONFIGS, StepConfig, get_config, scaled_config
+from .configs import CONFIGS, StepConfig, get_config, scaled_config, synthetic_accuracy_table
 from .generate import (
     TENSOR_IDS,
     bf16_bits_from_f32,
@@ -20,6 +20,7 @@ __all__ = [
     "StepConfig",
     "get_config",
     "scaled_config",
+    "synthetic_accuracy_table",
     "TENSOR_IDS",
     "bf16_bits_from_f32",
     "f32_from_bf16_bits",

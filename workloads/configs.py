@@ -76,3 +76,14 @@ def get_config(name: str) -> StepConfig:
 def scaled_config(name: str, **overrides) -> StepConfig:
     """A named config with some sizes replaced (used for CPU-sized parity cases)."""
     return replace(CONFIGS[name], **overrides)
+
+
+def synthetic_accuracy_table(K: int, S: int):
+    """Stand-in for the calibration statistics of Sec. 2.3.3 (top-i accuracy of every head measured
+    on a calibration set, which is not available): accuracy of the i-th best prediction of head k
+    = 0.62 * 0.78**k * 0.45**i, i.e. later heads are less accurate and each further rank is about
+    half as likely as the one before.  Pure data, no method arithmetic."""
+    import numpy as np
+    k = np.arange(K, dtype=np.float64)[:, None]
+    i = np.arange(S, dtype=np.float64)[None, :]
+    return 0.62 * 0.78 ** k * 0.45 ** i
