@@ -4,7 +4,8 @@
 // One launch.  The only pass over the B*T*V logits: each (row, chunk) workgroup reduces its slice
 // to an arg-max key and, in typical mode, the soft-max statistics
 //   m = max z,  S = sum exp(z - m),  U = sum (z - m) exp(z - m),   z = logit / temperature,
-// from which  ln p(x) = z_x - m - ln S  and the entropy  H = ln S - U / S.
+// from which  ln p(x) = z_x - m - ln S  and the entropy  H = ln S - U / S  (kept in log2 units
+// inside the scan so that the exponential is the hardware's 2^x).
 // The last workgroup of a sequence to finish (ticket counter) then merges the chunks with one
 // thread per node, evaluates every node's test on its parent's row, turns the pass bits into
 // two 64-bit ballots and decides acceptance of node t as  (anc_mask[t] & ~pass) == 0  -- no
@@ -16,7 +17,7 @@
 
 namespace {
 
-constexpr int kAccChunks = 4;
+constexpr int kAccMaxChunks = 8;   // upper bound of workgroups per logits row (sizes the partial buffer)
 constexpr int kMaxBatch = 4096;
 
 // Ticket counters of the "last workgroup of a sequence" election; zero between launches.
@@ -31,8 +32,8 @@ struct RowPart {       // one per (row, chunk)
 
 __device__ __forceinline__ void stats_merge(float& m, float& S, float& U, float m2, float S2, float U2) {
   const float mn = fmaxf(m, m2);
-  const float c1 = S > 0.f ? expf(m - mn) : 0.f, d1 = S > 0.f ? m - mn : 0.f;
-  const float c2 = S2 > 0.f ? expf(m2 - mn) : 0.f, d2 = S2 > 0.f ? m2 - mn : 0.f;
+  const float c1 = S > 0.f ? __builtin_amdgcn_exp2f(m - mn) : 0.f, d1 = S > 0.f ? m - mn : 0.f;
+  const float c2 = S2 > 0.f ? __builtin_amdgcn_exp2f(m2 - mn) : 0.f, d2 = S2 > 0.f ? m2 - mn : 0.f;
   U = c1 * (U + d1 * S) + c2 * (U2 + d2 * S2);
   S = c1 * S + c2 * S2;
   m = mn;
@@ -40,45 +41,62 @@ __device__ __forceinline__ void stats_merge(float& m, float& S, float& U, float 
 
 template <bool TYPICAL>
 __device__ __forceinline__ void row_stats(const float* __restrict__ logits, int V, float inv_temp,
-                                          RowPart* __restrict__ part) {
+                                          RowPart* __restrict__ part, int chunks) {
   __shared__ uint64_t s_key[4];
   __shared__ float s_m[4], s_S[4], s_U[4];
   const size_t row = blockIdx.y;
   const float* src = logits + row * V;
-  uint64_t key = 0;
+  // arg-max: a thread visits its elements in increasing index order, so a strict ">" keeps the
+  // lowest index among equal values (and treats -0.0 as equal to +0.0)
+  float best = -INFINITY;
+  int best_i = -1;
+  // soft-max statistics in log2 units: t = z * log2(e), m = max t, S = sum 2^(t-m), U = sum (t-m) 2^(t-m)
   float m = -INFINITY, S = 0.f, U = 0.f;
+  const float k2 = inv_temp * 1.4426950408889634f;
   auto visit = [&](float x, int i) {
-    const uint64_t k2 = rank_key(x, (uint32_t)i);
-    key = k2 > key ? k2 : key;
+    if (x > best || best_i < 0) {
+      best = x;
+      best_i = i;
+    }
     if (TYPICAL) {
-      const float z = x * inv_temp;
-      if (z > m) {                       // new running maximum: rescale what has been summed
-        const float c = S > 0.f ? expf(m - z) : 0.f;
-        U = S > 0.f ? c * (U + (m - z) * S) : 0.f;
-        S = c * S + 1.f;                 // the new element contributes exp(0) = 1 and (z - z) * 1 = 0
-        m = z;
+      const float t = x * k2;
+      if (t > m) {                       // new running maximum: rescale what has been summed
+        const float c = S > 0.f ? __builtin_amdgcn_exp2f(m - t) : 0.f;
+        U = S > 0.f ? c * (U + (m - t) * S) : 0.f;
+        S = c * S + 1.f;                 // the new element contributes 2^0 = 1 and (t - t) * 1 = 0
+        m = t;
       } else {
-        const float e = expf(z - m);
+        const float e = __builtin_amdgcn_exp2f(t - m);
         S += e;
-        U += (z - m) * e;
+        U += (t - m) * e;
       }
     }
   };
   if ((V & 3) == 0) {                    // rows are 16-byte aligned: four logits per load
-    const int per = ceil_div(V >> 2, kAccChunks);
+    const int per = ceil_div(V >> 2, chunks);
     const int lo = blockIdx.x * per, hi = min(V >> 2, lo + per);
     const floatx4_t* src4 = (const floatx4_t*)src;
-#pragma unroll 4
-    for (int i = lo + threadIdx.x; i < hi; i += 256) {
-      const floatx4_t v = src4[i];
+    // eight independent 16-byte loads in flight per thread before the (branchy) visits consume them
+    constexpr int NB = 8;
+    for (int i0 = lo + threadIdx.x; i0 < hi; i0 += NB * 256) {
+      floatx4_t v[NB];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) visit(v[e], 4 * i + e);
+      for (int u = 0; u < NB; ++u) v[u] = src4[min(i0 + u * 256, hi - 1)];
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        const int i = i0 + u * 256;
+        if (i < hi) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) visit(v[u][e], 4 * i + e);
+        }
+      }
     }
   } else {
-    const int per = ceil_div(V, kAccChunks);
+    const int per = ceil_div(V, chunks);
     const int lo = blockIdx.x * per, hi = min(V, lo + per);
     for (int i = lo + threadIdx.x; i < hi; i += 256) visit(src[i], i);
   }
+  uint64_t key = best_i >= 0 ? rank_key(best, (uint32_t)best_i) : 0;
   key = wave_max_u64(key);
   if (TYPICAL) {
 #pragma unroll
@@ -100,7 +118,7 @@ __device__ __forceinline__ void row_stats(const float* __restrict__ logits, int 
       key = s_key[w] > key ? s_key[w] : key;
       if (TYPICAL) stats_merge(m, S, U, s_m[w], s_S[w], s_U[w]);
     }
-    RowPart* p = part + row * kAccChunks + blockIdx.x;
+    RowPart* p = part + row * kAccMaxChunks + blockIdx.x;
     store_agent(&p->key, key);
     store_agent(&p->m, m);
     store_agent(&p->S, S);
@@ -113,7 +131,7 @@ template <bool TYPICAL>
 __device__ __forceinline__ void accept_finalize(int b, const float* __restrict__ logits,
                                                 const int32_t* __restrict__ tree_tokens,
                                                 const TreeTables* __restrict__ tree, const RowPart* __restrict__ part,
-                                                int V, float inv_temp, float eps, float delta,
+                                                int V, int chunks, float inv_temp, float eps, float delta,
                                                 int32_t* __restrict__ accept_len, int32_t* __restrict__ best_node,
                                                 int32_t* __restrict__ path_nodes, int32_t* __restrict__ accepted_tokens,
                                                 int32_t* __restrict__ next_root) {
@@ -125,20 +143,21 @@ __device__ __forceinline__ void accept_finalize(int b, const float* __restrict__
   const int T = tree->T, K = tree->K;
   const int lane = t & 63, wave = t >> 6;
   if (t < T) {
-    const RowPart* p = part + ((size_t)b * T + t) * kAccChunks;
+    const RowPart* p = part + ((size_t)b * T + t) * kAccMaxChunks;
     uint64_t key = load_agent(&p[0].key);
     float m = load_agent(&p[0].m), S = load_agent(&p[0].S), U = load_agent(&p[0].U);
-    for (int c = 1; c < kAccChunks; ++c) {
+    for (int c = 1; c < chunks; ++c) {
       const uint64_t k2 = load_agent(&p[c].key);
       key = k2 > key ? k2 : key;
       if (TYPICAL) stats_merge(m, S, U, load_agent(&p[c].m), load_agent(&p[c].S), load_agent(&p[c].U));
     }
     s_arg[t] = (int32_t)rank_key_id(key);
     if (TYPICAL) {
+      // statistics are in log2 units: ln S stays ln S, the entropy is ln S - ln 2 * U / S
       const float lnS = logf(S);
       s_m[t] = m;
       s_lnS[t] = lnS;
-      s_H[t] = lnS - U / S;
+      s_H[t] = lnS - 0.6931471805599453f * U / S;
     }
   }
   __syncthreads();
@@ -150,8 +169,8 @@ __device__ __forceinline__ void accept_finalize(int b, const float* __restrict__
     if (!TYPICAL) {
       pass = tok == s_arg[par];
     } else if (tok >= 0 && tok < V) {
-      const float z = logits[((size_t)b * T + par) * V + tok] * inv_temp;
-      const float p_tok = expf(z - s_m[par] - s_lnS[par]);
+      const float t2 = logits[((size_t)b * T + par) * V + tok] * (inv_temp * 1.4426950408889634f);
+      const float p_tok = expf((t2 - s_m[par]) * 0.6931471805599453f - s_lnS[par]);
       const float thr = fminf(eps, delta * expf(-s_H[par]));
       pass = p_tok > thr;
     }
@@ -193,18 +212,19 @@ __device__ __forceinline__ void accept_finalize(int b, const float* __restrict__
   }
 }
 
-// grid (kAccChunks, B*T), 256 threads.
+// grid (chunks, B*T), 256 threads.
 template <bool TYPICAL>
 __global__ __launch_bounds__(256) void accept_kernel(const float* __restrict__ logits, const int32_t* __restrict__ tree_tokens,
                                                      const TreeTables* __restrict__ tree, RowPart* __restrict__ part, int V,
                                                      float inv_temp, float eps, float delta, int32_t* __restrict__ accept_len,
                                                      int32_t* __restrict__ best_node, int32_t* __restrict__ path_nodes,
                                                      int32_t* __restrict__ accepted_tokens, int32_t* __restrict__ next_root) {
-  row_stats<TYPICAL>(logits, V, inv_temp, part);
+  const int chunks = gridDim.x;
+  row_stats<TYPICAL>(logits, V, inv_temp, part, chunks);
   const int T = tree->T;
   const int b = blockIdx.y / T;
-  if (!last_workgroup_of(&g_accept_ticket[b], (unsigned)(kAccChunks * T))) return;
-  accept_finalize<TYPICAL>(b, logits, tree_tokens, tree, part, V, inv_temp, eps, delta, accept_len, best_node, path_nodes,
+  if (!last_workgroup_of(&g_accept_ticket[b], (unsigned)(chunks * T))) return;
+  accept_finalize<TYPICAL>(b, logits, tree_tokens, tree, part, V, chunks, inv_temp, eps, delta, accept_len, best_node, path_nodes,
                            accepted_tokens, next_root);
 }
 
@@ -213,7 +233,7 @@ __global__ __launch_bounds__(256) void accept_kernel(const float* __restrict__ l
 extern "C" size_t medusa_accept_workspace_bytes(int B, int T, int V) {
   (void)V;
   if (B < 1 || T < 1) return 0;
-  return (size_t)B * T * kAccChunks * sizeof(RowPart);
+  return (size_t)B * T * kAccMaxChunks * sizeof(RowPart);
 }
 
 extern "C" int medusa_accept(const float* logits, const int32_t* tree_tokens, const medusa_tree_t* tree, int B, int V,
@@ -232,7 +252,11 @@ extern "C" int medusa_accept(const float* logits, const int32_t* tree_tokens, co
     return MEDUSA_EWORKSPACE;
   hipStream_t stream = (hipStream_t)stream_;
   RowPart* part = (RowPart*)workspace;
-  const dim3 grid(kAccChunks, B * T);
+  // every workgroup ends with a ticket round trip, so few, fat workgroups win: about one per CU
+  // (measured at 65 rows: 8.3 us with 3-4 chunks, 12 us with 8; at 1040 rows: 35 us with 1, 65 us with 4)
+  int chunks = 260 / (B * T);
+  chunks = chunks < 1 ? 1 : (chunks > kAccMaxChunks ? kAccMaxChunks : chunks);
+  const dim3 grid(chunks, B * T);
   const float inv_temp = mode == MEDUSA_TYPICAL ? 1.0f / temperature : 1.0f;
   if (mode == MEDUSA_TYPICAL)
     hipLaunchKernelGGL(accept_kernel<true>, grid, dim3(256), 0, stream, logits, tree_tokens, tree->dev, part, V, inv_temp,

@@ -11,7 +11,7 @@
 
 namespace {
 
-constexpr int kChunks = 16;         // workgroups per logits row
+constexpr int kMaxChunks = 16;      // upper bound of workgroups per logits row (sizes the partial buffer)
 constexpr int kMaxS = MEDUSA_MAX_TOPK;
 constexpr int kMaxBatch = 4096;
 
@@ -49,7 +49,7 @@ __device__ __forceinline__ void wave_top(uint64_t (&list)[S], uint64_t (&out)[S]
 }
 
 // rows: [B*(K+1)] logits rows of length V; row index b*(K+1)+0 is the LM head, +h head h.
-// part: [rows][kChunks][S] keys (0 = empty).  grid (kChunks, B*(K+1)), 256 threads.
+// part: [rows][kMaxChunks][S] keys (0 = empty).  grid (chunks, B*(K+1)), 256 threads.
 template <int S>
 __global__ __launch_bounds__(256) void topk_tree_kernel(const float* __restrict__ medusa_logits,
                                                         const float* __restrict__ lm_logits, int V, int K_heads,
@@ -60,6 +60,7 @@ __global__ __launch_bounds__(256) void topk_tree_kernel(const float* __restrict_
   __shared__ uint64_t cand[4][S];
   __shared__ int32_t flat[1 + MEDUSA_MAX_HEADS * kMaxS];
   const int K = tree->K;
+  const int chunks = gridDim.x;
   const int row = blockIdx.y;                       // b*(K+1) + h
   const int b = row / (K + 1), h = row - b * (K + 1);
   const float* src = h == 0 ? lm_logits + (size_t)b * V : medusa_logits + ((size_t)b * K_heads + (h - 1)) * V;
@@ -68,16 +69,25 @@ __global__ __launch_bounds__(256) void topk_tree_kernel(const float* __restrict_
 #pragma unroll
   for (int i = 0; i < S; ++i) list[i] = 0;
   if ((V & 3) == 0) {                               // rows are 16-byte aligned: four logits per load
-    const int per = ceil_div(V >> 2, kChunks);
+    const int per = ceil_div(V >> 2, chunks);
     const int lo = blockIdx.x * per, hi = min(V >> 2, lo + per);
     const floatx4_t* src4 = (const floatx4_t*)src;
-    for (int i = lo + threadIdx.x; i < hi; i += 256) {
-      const floatx4_t v = src4[i];
+    // independent 16-byte loads first, the (branchy) insertions after
+    for (int i0 = lo + threadIdx.x; i0 < hi; i0 += 2 * 256) {
+      floatx4_t v[2];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) list_insert<S>(list, rank_key(v[e], (uint32_t)(4 * i + e)));
+      for (int u = 0; u < 2; ++u) v[u] = src4[min(i0 + u * 256, hi - 1)];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int i = i0 + u * 256;
+        if (i < hi) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) list_insert<S>(list, rank_key(v[u][e], (uint32_t)(4 * i + e)));
+        }
+      }
     }
   } else {
-    const int per = ceil_div(V, kChunks);
+    const int per = ceil_div(V, chunks);
     const int lo = blockIdx.x * per, hi = min(V, lo + per);
     for (int i = lo + threadIdx.x; i < hi; i += 256) list_insert<S>(list, rank_key(src[i], (uint32_t)i));
   }
@@ -91,7 +101,7 @@ __global__ __launch_bounds__(256) void topk_tree_kernel(const float* __restrict_
   if (wave == 0) {
     // 4*S <= 64 candidates, one per lane; S rounds of wavefront max
     uint64_t mine = lane < 4 * S ? cand[lane / S][lane % S] : 0;
-    uint64_t* dst = part + ((size_t)row * kChunks + blockIdx.x) * S;
+    uint64_t* dst = part + ((size_t)row * kMaxChunks + blockIdx.x) * S;
 #pragma unroll
     for (int r = 0; r < S; ++r) {
       const uint64_t best = wave_max_u64(mine);
@@ -101,16 +111,16 @@ __global__ __launch_bounds__(256) void topk_tree_kernel(const float* __restrict_
   }
 
   // ---- the sequence's last workgroup merges the chunk winners and fills the tree ------------
-  if (!last_workgroup_of(&g_topk_ticket[b], (unsigned)(kChunks * (K + 1)))) return;
+  if (!last_workgroup_of(&g_topk_ticket[b], (unsigned)(chunks * (K + 1)))) return;
   const int Smax = tree->S, T = tree->T;
   if (wave == 0) {
     for (int hh = 0; hh <= K; ++hh) {
       const int want = hh == 0 ? 1 : tree->topk_per_head[hh - 1];
-      const uint64_t* p = part + ((size_t)b * (K + 1) + hh) * kChunks * S;
-      constexpr int PER_LANE = (kChunks * S + 63) / 64;
+      const uint64_t* p = part + ((size_t)b * (K + 1) + hh) * kMaxChunks * S;
+      constexpr int PER_LANE = (kMaxChunks * S + 63) / 64;
       uint64_t c[PER_LANE];
 #pragma unroll
-      for (int j = 0; j < PER_LANE; ++j) c[j] = j * 64 + lane < kChunks * S ? load_agent(p + j * 64 + lane) : 0;
+      for (int j = 0; j < PER_LANE; ++j) c[j] = j * 64 + lane < chunks * S ? load_agent(p + j * 64 + lane) : 0;
       for (int r = 0; r < want; ++r) {
         uint64_t mx = c[0];
 #pragma unroll
@@ -146,7 +156,7 @@ __global__ __launch_bounds__(256) void topk_tree_kernel(const float* __restrict_
 
 extern "C" size_t medusa_topk_tree_workspace_bytes(int B, int K) {
   if (B < 1 || K < 0) return 0;
-  return (size_t)B * (K + 1) * kChunks * kMaxS * sizeof(uint64_t);
+  return (size_t)B * (K + 1) * kMaxChunks * kMaxS * sizeof(uint64_t);
 }
 
 extern "C" int medusa_topk_tree(const float* medusa_logits, const float* lm_logits, const medusa_tree_t* tree,
@@ -164,7 +174,10 @@ extern "C" int medusa_topk_tree(const float* medusa_logits, const float* lm_logi
     return MEDUSA_EWORKSPACE;
   hipStream_t stream = (hipStream_t)stream_;
   uint64_t* part = (uint64_t*)workspace;
-  const dim3 grid(kChunks, B * (K + 1)), block(256);
+  // every workgroup ends with a ticket round trip: aim at about one workgroup per CU
+  int chunks = 256 / (B * (K + 1));
+  chunks = chunks < 1 ? 1 : (chunks > kMaxChunks ? kMaxChunks : chunks);
+  const dim3 grid(chunks, B * (K + 1)), block(256);
   const int Sc = S <= 1 ? 1 : (S <= 2 ? 2 : (S <= 4 ? 4 : (S <= 8 ? 8 : 16)));
 #define MEDUSA_TOPK(S_)                                                                                         \
   hipLaunchKernelGGL(topk_tree_kernel<S_>, grid, block, 0, stream, medusa_logits, lm_logits, V, K_heads, part, \

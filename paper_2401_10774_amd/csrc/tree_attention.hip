@@ -159,7 +159,7 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char s_k[TENSOR_BYTES];
   __shared__ __attribute__((aligned(16))) unsigned char s_v[TENSOR_BYTES];
   __shared__ __attribute__((aligned(16))) unsigned char s_p[16 * MT * PPITCH];
-  __shared__ float s_max[4][16 * MT];
+  __shared__ __attribute__((aligned(16))) float s_max[16 * MT][4];   // block maximum per query row and wavefront
   __shared__ float s_sum[4][16 * MT];
   __shared__ uint64_t s_anc[16 * MT][2];        // ancestor mask of every query row of this workgroup
 
@@ -287,14 +287,15 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
       float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
       mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
       mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-      if (q4 == 0) s_max[wave][16 * mt + i16] = mx;
+      if (q4 == 0) s_max[16 * mt + i16][wave] = mx;
     }
     __syncthreads();        // A: block maxima are visible; every wavefront has left block i-1 and the K tile
     // ---- online soft-max update, probabilities to LDS ----
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       const int c = 16 * mt + i16;
-      const float mx = fmaxf(fmaxf(s_max[0][c], s_max[1][c]), fmaxf(s_max[2][c], s_max[3][c]));
+      const floatx4_t m4 = *(const floatx4_t*)s_max[c];
+      const float mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
       const float m_new = fmaxf(m_run[mt], mx);
       const float m_safe = m_new == -INFINITY ? 0.f : m_new;
       const float alpha = __builtin_amdgcn_exp2f(m_run[mt] - m_safe);
@@ -302,8 +303,12 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
       const float p2 = __builtin_amdgcn_exp2f(sv[mt][2] - m_safe), p3 = __builtin_amdgcn_exp2f(sv[mt][3] - m_safe);
       l_run[mt] = l_run[mt] * alpha + ((p0 + p1) + (p2 + p3));
       m_run[mt] = m_new;
+      // after the first blocks the running maximum rarely moves: skip the rescale when no row of
+      // this tile needs it (alpha is exactly 1 then)
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-      for (int dd = 0; dd < DPW; ++dd) o[mt][dd] *= alpha;
+        for (int dd = 0; dd < DPW; ++dd) o[mt][dd] *= alpha;
+      }
       u32x2_t w;
       w.x = pack_bf16x2(p0, p1);
       w.y = pack_bf16x2(p2, p3);
