@@ -18,7 +18,13 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libmedusa_hip.so")
 
-SOURCES = ["tree.hip", "heads.hip", "topk_tree.hip", "tree_attention.hip", "accept.hip", "kv_commit.hip"]
+SOURCES = ["tree.hip", "heads.hip", "gemm_big.hip", "topk_tree.hip", "tree_attention.hip", "accept.hip", "kv_commit.hip"]
+
+# Per-file code-generation options.  gemm_big.hip keeps MFMA accumulators in ordinary vector
+# registers: with the compiler's default choice its large accumulator tile is copied between the
+# two register files in every loop iteration (several hundred moves per 96 MFMAs).
+PER_FILE_FLAGS = {"gemm_big.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
 
 # Packed-fp32 VALU forms are switched off for every device compile.
 HIPCC_FLAGS = [
@@ -52,7 +58,7 @@ def build_library(verbose: bool = False) -> str:
 
         def compile_one(pair):
             src, obj = pair
-            return _run([hipcc, *HIPCC_FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj])
+            return _run([hipcc, *HIPCC_FLAGS, *PER_FILE_FLAGS.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj])
 
         with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
             logs = list(ex.map(compile_one, zip(SOURCES, objs)))

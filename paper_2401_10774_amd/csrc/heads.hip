@@ -11,42 +11,9 @@
 //                     activation rows x 128 weight rows per workgroup (128 x 128 for M > 80).
 //   * fp32          : plain FMA version of the first scheme (small configurations only).
 // The residual block's epilogue applies SiLU, adds h and rounds once to the storage type.
-#include "common.hpp"
+#include "gemm_args.hpp"
 
 namespace {
-
-enum { EPI_LOGITS = 0, EPI_RESID = 1 };
-
-
-// acc[m][n] = sum_j W[k][n][j] * X[m*xs_m + k*xs_k + j]
-struct GemmArgs {
-  const void* W;       // [K][N][d]
-  const void* X;       // activations, see strides
-  const void* hidden;  // [M][d] residual source (EPI_RESID, N == d)
-  void* out;           // EPI_LOGITS: float [M][K][N];  EPI_RESID: dtype [M][K][N]
-  int M, N, d, K;
-  long xs_m, xs_k;     // element strides of X between rows m and between heads k
-  int rows_per_wg;     // GEMV kernels: weight rows per workgroup (multiple of 8)
-};
-
-typedef __bf16 dot2_t __attribute__((__vector_size__(2 * sizeof(__bf16))));
-
-__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
-  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dot2_t, a), __builtin_bit_cast(dot2_t, b), c, false);
-}
-
-__device__ __forceinline__ float silu_f32(float u) { return u / (1.0f + expf(-u)); }
-
-template <int EPI, typename T>
-__device__ __forceinline__ void epilogue_store(const GemmArgs& a, int m, int k, int n, float acc) {
-  const size_t o = ((size_t)m * a.K + k) * a.N + n;
-  if (EPI == EPI_LOGITS) {
-    ((float*)a.out)[o] = acc;
-  } else {
-    const float h = load_as_float<T>((const T*)a.hidden + (size_t)m * a.d + n);
-    store_from_float<T>((T*)a.out + o, silu_f32(acc) + h);
-  }
-}
 
 // ---------------------------------------------------------------------------------------
 // bf16, M <= 4 per block of rows: wave-per-row streaming GEMV.
@@ -178,7 +145,8 @@ template <int WM, int WN, int MT, int NT, int BK, int PD, int EPI>
 __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
   constexpr int BM = WM * 16 * MT, BN = WN * 16 * NT;
   constexpr int CPR = BK / 8;                         // 16-byte chunks per row and reduction step
-  constexpr int PITCH = BK * 2 + 16;                  // bytes per LDS row: data + 16 pad
+  static_assert(BK == 64, "the LDS swizzle below assumes 128-byte rows");
+  constexpr int PITCH = BK * 2;                       // bytes per LDS row (unpadded, chunks swizzled)
   constexpr int CHUNKS = (BM + BN) * CPR;             // 16-byte chunks per reduction step
   constexpr int LPT = (CHUNKS + 255) / 256;           // chunks per thread per step
   constexpr int STAGE_BYTES = (BM + BN) * PITCH;
@@ -202,7 +170,7 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
     const int row = id / CPR, c = id - row * CPR;
     src[it] = row < BM ? X + (size_t)min(m0 + row, a.M - 1) * a.xs_m + c * 8
                        : W + (size_t)min(n0 + row - BM, a.N - 1) * a.d + c * 8;
-    dst[it] = row * PITCH + c * 16;
+    dst[it] = row * PITCH + ((c ^ ((row >> 1) & 7)) << 4);
   }
 
   floatx4_t acc[MT][NT];
@@ -222,8 +190,12 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
 #pragma unroll
     for (int it = 0; it < LPT; ++it) *(u32x4_t*)(lds + buf * STAGE_BYTES + dst[it]) = r[it];
   };
-  const int x_off = ((wm * MT) * 16 + i16) * PITCH + q4 * 16;
-  const int w_off = (BM + (wn * NT) * 16 + i16) * PITCH + q4 * 16;
+  // 16-byte chunk c of row r sits at chunk slot c ^ ((r >> 1) & 7): the fragment reads below (16 rows
+  // x 4 chunks per instruction) and the row-major stores above then touch every LDS bank equally often
+  // within each group of lanes the hardware serves together, which a padded pitch does not achieve.
+  const int swz = (i16 >> 1) & 7;
+  const int x_off = ((wm * MT) * 16 + i16) * PITCH;
+  const int w_off = (BM + (wn * NT) * 16 + i16) * PITCH;
   auto compute = [&](int buf, uint32_t keep) {
     const unsigned char* base = lds + buf * STAGE_BYTES;
 #pragma unroll
@@ -231,12 +203,13 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
       bf16x8_t xf[MT], wf[NT];
 #pragma unroll
       for (int t = 0; t < MT; ++t) {
-        u32x4_t bits = *(const u32x4_t*)(base + x_off + t * 16 * PITCH + kk * 64);
+        u32x4_t bits = *(const u32x4_t*)(base + x_off + t * 16 * PITCH + (((kk * 4 + q4) ^ swz) << 4));
         bits &= keep;
         xf[t] = __builtin_bit_cast(bf16x8_t, bits);
       }
 #pragma unroll
-      for (int j = 0; j < NT; ++j) wf[j] = *(const bf16x8_t*)(base + w_off + j * 16 * PITCH + kk * 64);
+      for (int j = 0; j < NT; ++j)
+        wf[j] = *(const bf16x8_t*)(base + w_off + j * 16 * PITCH + (((kk * 4 + q4) ^ swz) << 4));
 #pragma unroll
       for (int t = 0; t < MT; ++t)
 #pragma unroll
@@ -326,10 +299,16 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
       MEDUSA_SKINNY(1) MEDUSA_SKINNY(2) MEDUSA_SKINNY(3) MEDUSA_SKINNY(4) MEDUSA_SKINNY(5)
     }
 #undef MEDUSA_SKINNY
-  } else {
-    // 128 x 128 tile, wavefronts 2 x 2, each 64 x 64
+  } else if ((size_t)a.N * a.d >= ((size_t)1 << 31) || (size_t)a.M * a.xs_m >= ((size_t)1 << 31)) {
+    // byte offsets beyond 32 bits: 128 x 128 tile with 64-bit addressing, wavefronts 2 x 2, each 64 x 64
     const dim3 grid(ceil_div(a.N, 128), a.K, ceil_div(a.M, 128));
     hipLaunchKernelGGL((gemm_lds_bf16_kernel<2, 2, 4, 4, 64, 2, EPI>), grid, block, 0, stream, a);
+  } else if ((size_t)a.N * a.d >= ((size_t)1 << 31) || (size_t)a.M * a.xs_m >= ((size_t)1 << 31)) {
+    // element offsets beyond 31 bits: 128 x 128 tile with 64-bit addressing, wavefronts 2 x 2, each 64 x 64
+    const dim3 grid(ceil_div(a.N, 128), a.K, ceil_div(a.M, 128));
+    hipLaunchKernelGGL((gemm_lds_bf16_kernel<2, 2, 4, 4, 64, 2, EPI>), grid, block, 0, stream, a);
+  } else {
+    return launch_gemm_big(a, EPI, stream);
   }
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;
