@@ -379,6 +379,73 @@ def kv_commit_ref(k_cache, v_cache, k_tree, v_tree, path_nodes, accept_len, pref
 
 
 # --------------------------------------------------------------------------
+# backbone operators on the tree tokens (App. G: table of operator shapes, "Parallel decoding"
+# rows, and the simplified block of the latency model)
+# --------------------------------------------------------------------------
+
+def tree_linear_ref(x, w, dtype: str, mul=None):
+    """App. G, operator table, parallel-decoding rows X W_Q / X W_K / X W_V / X W_u / X W_g /
+    X W_d: every tree token's feature row times a weight matrix.  x [M, d_in], w [d_out, d_in]
+    (stored out x in, as for the heads), result [M, d_out] rounded once to the storage dtype.
+    With ``mul`` [M, d_out] given, the result is SiLU(x w^T) * mul before rounding (the gated
+    feed-forward of the Llama family the appendix models: gate and up projections combined)."""
+    y = widen(x) @ widen(w).T
+    if mul is not None:
+        y = silu(y) * widen(mul)
+    return round_to_storage(y, dtype)
+
+
+def rope_ref(x, position_ids, theta: float, dtype: str):
+    """Rotary position embedding at the tree's positional indices (Sec. 2.1.2: the indices follow
+    the tree structure, i.e. position = prefix length + depth of the node; they are an input
+    here).  x [B, H, T, D]; position_ids [B, T].  Half-split pairing of the Llama family: element
+    j < D/2 is paired with element j + D/2 and the pair is rotated by the angle
+    position * theta**(-2j/D).  Result rounded once to the storage dtype."""
+    xv = widen(x)
+    B, H, T, D = xv.shape
+    half = D // 2
+    inv_freq = theta ** (-(2.0 * np.arange(half, dtype=np.float64)) / D)
+    ang = np.asarray(position_ids, np.float64)[:, None, :, None] * inv_freq[None, None, None, :]   # [B,1,T,half]
+    c, sn = np.cos(ang), np.sin(ang)
+    lo, hi = xv[..., :half], xv[..., half:]
+    out = np.concatenate([lo * c - hi * sn, hi * c + lo * sn], axis=-1)
+    return round_to_storage(out, dtype)
+
+
+def to_heads(y, B: int, T: int, H: int):
+    """[B*T, H*Dh] token-major -> [B, H, T, Dh] head-major (pure re-indexing)."""
+    return np.ascontiguousarray(np.asarray(y).reshape(B, T, H, -1).transpose(0, 2, 1, 3))
+
+
+def from_heads(y):
+    """[B, H, T, Dh] head-major -> [B*T, H*Dh] token-major (pure re-indexing)."""
+    B, H, T, Dh = np.asarray(y).shape
+    return np.ascontiguousarray(np.asarray(y).transpose(0, 2, 1, 3).reshape(B * T, H * Dh))
+
+
+def simplified_block_ref(x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, tree: Tree,
+                         Hq: int, Hkv: int, scale: float, theta: float, dtype: str):
+    """The simplified decoder block whose latency App. G models, run on the tree tokens: the
+    operators X W_Q, X W_K, X W_V, Q K^T, P V, X W_u, X W_g, X W_d in sequence.  The appendix
+    lists the operators only; the data flow taken here is the Llama one without norms, output
+    projection and residuals: q, k, v = x W^T, rotary embedding of q and k at the tree positions,
+    tree attention against the cache, then down(SiLU(gate(a)) * up(a)) on the attention output a.
+    x [B*T, h] token-major.  Every operator's result is rounded to the storage dtype.  Returns a
+    dict of all intermediates (float64 values on the storage grid)."""
+    B = len(prefix_len)
+    T = tree.T
+    q = rope_ref(to_heads(tree_linear_ref(x, wq, dtype), B, T, Hq), position_ids, theta, dtype)
+    k = rope_ref(to_heads(tree_linear_ref(x, wk, dtype), B, T, Hkv), position_ids, theta, dtype)
+    v = to_heads(tree_linear_ref(x, wv, dtype), B, T, Hkv)
+    attn = round_to_storage(tree_attention_ref(q, k, v, k_cache, v_cache, prefix_len, tree, scale), dtype)
+    a = from_heads(attn)
+    up = tree_linear_ref(a, wu, dtype)
+    act = tree_linear_ref(a, wg, dtype, mul=up)
+    out = tree_linear_ref(act, wd, dtype)
+    return {"q": q, "k": k, "v": v, "attn": attn, "up": up, "act": act, "out": out}
+
+
+# --------------------------------------------------------------------------
 # the whole step, chained (Sec. 2, opening paragraph: the three substeps of a decoding step)
 # --------------------------------------------------------------------------
 
