@@ -38,6 +38,9 @@ def parse_args():
     ap.add_argument("--config", default="C2", help="workload name (C1..C5); the headline metric is quoted on C2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also time every library call on its own (stderr)")
+    ap.add_argument("--block", action="store_true",
+                    help="time the simplified decoder block of App. G on the tree tokens instead of the verification "
+                         "step (its own JSON line; the headline metric stays the verification step)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three plain 1 GiB device copies (reference kernel of known size for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -87,6 +90,9 @@ def main():
         sys.exit(1)
     cfg = get_config(args.config)
     torch.cuda.set_device(0)
+    if args.block:
+        bench_block(args, cfg)
+        return
 
     t0 = time.time()
     x = make_step_inputs(cfg)
@@ -186,6 +192,89 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, x)
     print(json.dumps(out), flush=True)
+
+
+def bench_block(args, cfg):
+    """One step = one simplified decoder block (X W_Q, X W_K, X W_V, rotary embedding, tree attention,
+    X W_u, X W_g, X W_d) on the B*T tree tokens of the named workload's shapes; weights and cache of
+    the layer rotate over several distinct sets so that every step streams them from HBM."""
+    import torch
+
+    import paper_2401_10774_amd as M
+    from paper_2401_10774_amd.block import SimplifiedBlock
+
+    inter = {4096: 11008, 5120: 13824}.get(cfg.d, ((cfg.d * 8 // 3 + 255) // 256) * 256)      # Llama-family widths
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    es = 2 if cfg.dtype == "bf16" else 4
+    tree = M.MedusaTree(branching=cfg.branching)
+    B, T, h, Hq, Hkv, D = cfg.B, tree.T, cfg.d, cfg.Hq, cfg.Hkv, cfg.D
+    gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    layer_bytes = (Hq * D * h + 2 * Hkv * D * h + 2 * inter * Hq * D + h * inter) * es + 2 * B * Hkv * cfg.Lcap * D * es
+    n_sets = max(2, min(16, int(3e9 // layer_bytes)))
+    rnd = lambda *shape, std=1.0: (torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32) * std).to(dt)
+    sets = []
+    for _ in range(n_sets):
+        sets.append(dict(wq=rnd(Hq * D, h, std=h ** -0.5), wk=rnd(Hkv * D, h, std=h ** -0.5), wv=rnd(Hkv * D, h, std=h ** -0.5),
+                         wu=rnd(inter, Hq * D, std=h ** -0.5), wg=rnd(inter, Hq * D, std=h ** -0.5),
+                         wd=rnd(h, inter, std=inter ** -0.5), kc=rnd(B, Hkv, cfg.Lcap, D), vc=rnd(B, Hkv, cfg.Lcap, D)))
+    x = rnd(B * T, h)
+    pl = torch.randint(cfg.L_min, cfg.L_max + 1, (B,), generator=gen, device="cuda", dtype=torch.int32)
+    depth = torch.from_numpy(tree.depth).to(device="cuda", dtype=torch.int32)
+    pos = (pl[:, None] + depth[None, :]).to(torch.int32).contiguous()
+    blk = SimplifiedBlock(tree, B, h, Hq, Hkv, D, inter, cfg.Lcap, dt)
+    scale = 1.0 / math.sqrt(D)
+
+    def run(i):
+        w = sets[i % n_sets]
+        blk.run(x, w["wq"], w["wk"], w["wv"], w["wu"], w["wg"], w["wd"], w["kc"], w["vc"], pl, pos, scale)
+
+    K, W = args.steps, args.warmup
+    for i in range(W):
+        run(i)
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for i in range(K):
+        run(i)
+    stop.record()
+    torch.cuda.synchronize()
+    ms = start.elapsed_time(stop) / K
+    mean_L = float(pl.float().mean())
+    M_rows = B * T
+    w_bytes = (Hq * D * h + 2 * Hkv * D * h + 2 * inter * Hq * D + h * inter) * es
+    act_bytes = (3 * M_rows * h + 2 * M_rows * (Hq + 2 * Hkv) * D + 2 * M_rows * Hq * D + 3 * M_rows * Hq * D
+                 + 4 * M_rows * inter + M_rows * h) * es
+    kv_bytes = int(2 * B * Hkv * mean_L * D * es)
+    total = w_bytes + act_bytes + kv_bytes
+    flops = 2.0 * M_rows * (Hq * D * h + 2 * Hkv * D * h + 2 * inter * Hq * D + h * inter) + 4.0 * B * Hq * T * (mean_L + T) * D
+    if args.breakdown:
+        names = ["X W_Q", "X W_K", "X W_V", "rotary", "QK^T, PV", "X W_u", "X W_g", "X W_d"]
+        stream = torch.cuda.current_stream().cuda_stream
+        plans = [blk._calls(x, w["wq"], w["wk"], w["wv"], w["wu"], w["wg"], w["wd"], w["kc"], w["vc"], pl, pos, scale)
+                 for w in sets]
+        for j, name in enumerate(names):
+            for i in range(5):
+                _, fn, a = plans[i % n_sets][j]
+                fn(*a, stream)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(56):
+                _, fn, a = plans[i % n_sets][j]
+                fn(*a, stream)
+            e1.record()
+            torch.cuda.synchronize()
+            print(f"[bench]   {name:10s} {e0.elapsed_time(e1) / 56 * 1e3:8.1f} us", file=sys.stderr, flush=True)
+    print(json.dumps({
+        "metric": "simplified decoder block (App. G) on the tree tokens", "value": round(1e3 / ms, 2), "unit": "blocks/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name} shapes: B={B} T={T} h={h} inter={inter} heads={Hq}/{Hkv}x{D} prefix=[{cfg.L_min},{cfg.L_max}]",
+                   "weight_sets_rotated": n_sets},
+        "block_hbm": {"algorithmic_bytes": total, "achieved_GBps": round(total / ms / 1e6, 1),
+                      "frac_of_peak": round(total / ms / 1e6 / HBM_PEAK_GBS, 4)},
+        "block_flops": {"useful_TFLOPs": round(flops / ms / 1e9, 1)},
+    }), flush=True)
 
 
 def breakdown(step, cfg, parts):

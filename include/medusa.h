@@ -210,6 +210,41 @@ int kv_commit(void* k_cache, void* v_cache, const void* k_tree, const void* v_tr
               int NL, int B, int Hkv, int T, int D, int Lcap, medusa_dtype_t dtype, medusa_stream_t stream);
 
 /* ----------------------------------------------------------------------------------
+ * Backbone operators on the tree tokens (App. G: operator table, "Parallel decoding" rows
+ * X W_Q, X W_K, X W_V, X W_u, X W_g, X W_d; Sec. 2.1.2 for the positional indices).  Together
+ * with tree_attention they make up the simplified decoder block whose latency App. G models.
+ *
+ * tree_linear:  y = x . w^T,  or  y = SiLU(x . w^T) * mul  when mul != NULL (gate projection
+ * combined with the up projection), accumulated in fp32 and rounded once to dtype.
+ *   x    token-major [B*T, d_in] (x_heads == 0) or head-major [B, x_heads, T, d_in/x_heads]
+ *        (the layout tree_attention writes), dtype
+ *   w    [d_out, d_in] dtype, out x in
+ *   mul  [B*T, d_out] token-major dtype, or NULL
+ *   y    token-major [B*T, d_out] (y_heads == 0) or head-major [B, y_heads, T, d_out/y_heads]
+ *        (the layout tree_attention and tree_rope read), dtype; must not alias x or mul
+ *   workspace  device scratch of at least tree_linear_workspace_bytes(...) bytes (may be 0: then
+ *        NULL is fine), caller-owned, contents irrelevant before and after.  It holds the fp32
+ *        partial tiles when the reduction over d_in is split across workgroups, which the library
+ *        does for few tree tokens and small d_out so that the whole chip streams the weights; with
+ *        NULL or too small a workspace the call still works, unsplit and slower.  Calls that use
+ *        the workspace must not overlap on one GPU (they share a ticket table).
+ * Limits: B*T <= 4096; d_in (and d_in/x_heads) a multiple of 8 (bf16: of 64); d_out a multiple
+ * of y_heads.  All pointers are device pointers; returns MEDUSA_EINVAL / MEDUSA_EUNSUPPORTED
+ * without launching anything when a limit is violated.
+ * -------------------------------------------------------------------------------- */
+size_t tree_linear_workspace_bytes(int B, int T, int d_in, int d_out, medusa_dtype_t dtype);
+int tree_linear(const void* x, const void* w, const void* mul, void* y, int B, int T, int d_in, int d_out,
+                int x_heads, int y_heads, medusa_dtype_t dtype, void* workspace, size_t workspace_bytes,
+                medusa_stream_t stream);
+
+/* tree_rope: rotary position embedding, in place, of q [B, Hq, T, D] and k [B, Hkv, T, D] (dtype)
+ * at position_ids [B, T] (int32, device; the table medusa_topk_tree writes: prefix length +
+ * depth of the node).  Element j < D/2 is paired with element j + D/2; the pair is rotated by
+ * position * theta^(-2j/D).  D must be even. */
+int tree_rope(void* q, void* k, const int32_t* position_ids, int B, int Hq, int Hkv, int T, int D, float theta,
+              medusa_dtype_t dtype, medusa_stream_t stream);
+
+/* ----------------------------------------------------------------------------------
  * Benchmark hook (no counterpart in the paper): while a pair of hipEvent_t handles is set,
  * every medusa_heads call with w1 != NULL records `start` right before and `stop` right after
  * its vocabulary-projection kernel (the W2 stream, the largest single read of the step) on the

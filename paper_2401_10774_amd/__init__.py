@@ -16,10 +16,13 @@ from .binding import (
     medusa_topk_tree,
     tree_attention,
     tree_attention_workspace_bytes,
+    tree_linear,
+    tree_linear_workspace_bytes,
+    tree_rope,
 )
 
 __all__ = [
     "MedusaError", "MedusaTree", "kv_commit", "lib", "library_path", "medusa_accept",
     "medusa_accept_workspace_bytes", "medusa_heads", "medusa_topk_tree", "tree_attention",
-    "tree_attention_workspace_bytes",
+    "tree_attention_workspace_bytes", "tree_linear", "tree_linear_workspace_bytes", "tree_rope",
 ]

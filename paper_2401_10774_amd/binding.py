@@ -25,7 +25,8 @@ EXPORTED_SYMBOLS = (
     "medusa_tree_create_optimized", "medusa_tree_destroy",
     "medusa_tree_query", "medusa_tree_tables", "medusa_heads", "medusa_topk_tree_workspace_bytes",
     "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "medusa_accept_workspace_bytes",
-    "medusa_accept", "kv_commit", "medusa_profile_set_events",
+    "medusa_accept", "kv_commit", "tree_linear_workspace_bytes", "tree_linear", "tree_rope",
+    "medusa_profile_set_events",
 )
 
 
@@ -67,6 +68,10 @@ def lib() -> ctypes.CDLL:
         L.medusa_accept.argtypes = ([c_void_p] * 3 + [c_int] * 3 + [c_float] * 3 + [c_void_p] * 5 +
                                     [c_void_p, c_size_t, c_void_p])
         L.kv_commit.argtypes = ([c_void_p] * 5 + [c_int, c_void_p, c_void_p] + [c_int] * 6 + [c_int, c_void_p])
+        L.tree_linear_workspace_bytes.restype = c_size_t
+        L.tree_linear_workspace_bytes.argtypes = [c_int] * 5
+        L.tree_linear.argtypes = [c_void_p] * 4 + [c_int] * 7 + [c_void_p, c_size_t, c_void_p]
+        L.tree_rope.argtypes = [c_void_p] * 3 + [c_int] * 5 + [c_float, c_int, c_void_p]
         L.medusa_profile_set_events.argtypes = [c_void_p, c_void_p]
         for name in EXPORTED_SYMBOLS:
             fn = getattr(L, name)
@@ -316,3 +321,54 @@ def kv_commit(k_cache: torch.Tensor, v_cache: torch.Tensor, k_tree: torch.Tensor
     _check(lib().kv_commit(k_cache.data_ptr(), v_cache.data_ptr(), k_tree.data_ptr(), v_tree.data_ptr(),
                            path_nodes.data_ptr(), int(path_nodes.shape[1]), accept_len.data_ptr(),
                            prefix_len.data_ptr(), NL, B, Hkv, T, D, Lcap, code, _stream(stream)), "kv_commit")
+
+
+def tree_linear_workspace_bytes(B: int, T: int, d_in: int, d_out: int, dtype: torch.dtype) -> int:
+    code = 1 if dtype == torch.bfloat16 else 0
+    return int(lib().tree_linear_workspace_bytes(B, T, d_in, d_out, code))
+
+
+def tree_linear(x: torch.Tensor, w: torch.Tensor, B: int, T: int, mul: Optional[torch.Tensor] = None,
+                y: Optional[torch.Tensor] = None, y_heads: int = 0, workspace: Optional[torch.Tensor] = None,
+                stream=None) -> torch.Tensor:
+    """y = x w^T (or SiLU(x w^T) * mul) on the B*T tree tokens.  x is token-major [B*T, d_in] or
+    head-major [B, H, T, Dh] (as tree_attention writes it); y is token-major [B*T, d_out] or, with
+    y_heads > 0, head-major [B, y_heads, T, d_out / y_heads]."""
+    code = _dtype_code(x)
+    d_out, d_in = w.shape
+    if x.dim() == 2:
+        x_heads = 0
+        _dev(x, "x", shape=(B * T, d_in))
+    elif x.dim() == 4:
+        x_heads = int(x.shape[1])
+        _dev(x, "x", shape=(B, x_heads, T, d_in // max(x_heads, 1)))
+    else:
+        raise MedusaError("x must be [B*T, d_in] or [B, H, T, Dh]")
+    _dev(w, "w", dtype=x.dtype, shape=(d_out, d_in))
+    if mul is not None:
+        _dev(mul, "mul", dtype=x.dtype, shape=(B * T, d_out))
+    shape = (B * T, d_out) if y_heads == 0 else (B, y_heads, T, d_out // y_heads)
+    if y is None:
+        y = torch.empty(shape, dtype=x.dtype, device=x.device)
+    _dev(y, "y", dtype=x.dtype, shape=shape)
+    if workspace is None:
+        need = tree_linear_workspace_bytes(B, T, d_in, d_out, x.dtype)
+        workspace = _scratch(need, x.device) if need else None
+    _check(lib().tree_linear(x.data_ptr(), w.data_ptr(), None if mul is None else mul.data_ptr(), y.data_ptr(),
+                             B, T, d_in, d_out, x_heads, y_heads, code,
+                             None if workspace is None else workspace.data_ptr(),
+                             0 if workspace is None else workspace.numel() * workspace.element_size(),
+                             _stream(stream)), "tree_linear")
+    return y
+
+
+def tree_rope(q: torch.Tensor, k: torch.Tensor, position_ids: torch.Tensor, theta: float = 10000.0, stream=None) -> None:
+    """Rotary embedding of q [B, Hq, T, D] and k [B, Hkv, T, D] in place at position_ids [B, T] (int32)."""
+    B, Hq, T, D = q.shape
+    Hkv = k.shape[1]
+    code = _dtype_code(q)
+    _dev(q, "q")
+    _dev(k, "k", dtype=q.dtype, shape=(B, Hkv, T, D))
+    _dev(position_ids, "position_ids", dtype=torch.int32, shape=(B, T))
+    _check(lib().tree_rope(q.data_ptr(), k.data_ptr(), position_ids.data_ptr(), B, Hq, Hkv, T, D, float(theta), code,
+                           _stream(stream)), "tree_rope")

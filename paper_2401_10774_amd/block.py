@@ -1,0 +1,73 @@
+"""The simplified decoder block of App. G on the tree tokens, chained from the library's calls:
+X W_Q, X W_K, X W_V (tree_linear), rotary embedding at the tree positions (tree_rope), Q K^T and
+P V against the cache (tree_attention), X W_u, X W_g, X W_d (tree_linear).  Buffers are allocated
+once and the calls' arguments are marshalled once per set of operands; ``run`` only launches
+kernels.  Argument marshalling only -- every operator runs in the HIP library."""
+from __future__ import annotations
+
+import torch
+
+from . import binding as _b
+
+
+class SimplifiedBlock:
+    def __init__(self, tree: "_b.MedusaTree", B: int, h: int, Hq: int, Hkv: int, D: int, inter: int, Lcap: int,
+                 dtype: torch.dtype, device="cuda", theta: float = 10000.0):
+        self.tree, self.B, self.T = tree, B, tree.T
+        self.h, self.Hq, self.Hkv, self.D, self.inter, self.Lcap, self.theta = h, Hq, Hkv, D, inter, Lcap, theta
+        T = tree.T
+        mk = lambda *shape: torch.empty(shape, dtype=dtype, device=device)
+        self.q, self.k, self.v = mk(B, Hq, T, D), mk(B, Hkv, T, D), mk(B, Hkv, T, D)
+        self.attn = mk(B, Hq, T, D)
+        self.up, self.act, self.out = mk(B * T, inter), mk(B * T, inter), mk(B * T, h)
+        self.ws = _b._scratch(_b.tree_attention_workspace_bytes(B, Hq, Hkv, T, D, Lcap), device)
+        need = max(_b.tree_linear_workspace_bytes(B, T, d_in, d_out, dtype)
+                   for d_in, d_out in ((h, Hq * D), (h, Hkv * D), (Hq * D, inter), (inter, h)))
+        self.ws_lin = _b._scratch(need, device)
+        self._plans = {}
+
+    def _calls(self, x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale):
+        key = tuple(t.data_ptr() for t in (x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids)) + (scale,)
+        plan = self._plans.get(key)
+        if plan is not None:
+            return plan
+        dt = self.q.dtype
+        B, T, h, Hq, Hkv, D, inter = self.B, self.T, self.h, self.Hq, self.Hkv, self.D, self.inter
+        _b._dev(x, "x", dtype=dt, shape=(B * T, h))
+        for name, w, shape in (("wq", wq, (Hq * D, h)), ("wk", wk, (Hkv * D, h)), ("wv", wv, (Hkv * D, h)),
+                               ("wu", wu, (inter, Hq * D)), ("wg", wg, (inter, Hq * D)), ("wd", wd, (h, inter))):
+            _b._dev(w, name, dtype=dt, shape=shape)
+        _b._dev(k_cache, "k_cache", dtype=dt, shape=(B, Hkv, self.Lcap, D))
+        _b._dev(v_cache, "v_cache", dtype=dt, shape=(B, Hkv, self.Lcap, D))
+        _b._dev(prefix_len, "prefix_len", dtype=torch.int32, shape=(B,))
+        _b._dev(position_ids, "position_ids", dtype=torch.int32, shape=(B, T))
+        L, code, p = _b.lib(), _b._dtype_code(x), (lambda t: t.data_ptr())
+        nb = lambda t: t.numel() * t.element_size()
+        lin = lambda xin, w, mul, y, d_in, d_out, xh, yh: (
+            "tree_linear", L.tree_linear, (p(xin), p(w), None if mul is None else p(mul), p(y), B, T, d_in, d_out, xh, yh,
+                                           code, p(self.ws_lin), nb(self.ws_lin)))
+        plan = [
+            lin(x, wq, None, self.q, h, Hq * D, 0, Hq),
+            lin(x, wk, None, self.k, h, Hkv * D, 0, Hkv),
+            lin(x, wv, None, self.v, h, Hkv * D, 0, Hkv),
+            ("tree_rope", L.tree_rope, (p(self.q), p(self.k), p(position_ids), B, Hq, Hkv, T, D, float(self.theta), code)),
+            ("tree_attention", L.tree_attention, (p(self.q), p(self.k), p(self.v), p(k_cache), p(v_cache), p(prefix_len),
+                                                  self.tree.handle, p(self.attn), B, Hq, Hkv, D, self.Lcap, float(scale),
+                                                  code, p(self.ws), nb(self.ws))),
+            lin(self.attn, wu, None, self.up, Hq * D, inter, Hq, 0),
+            lin(self.attn, wg, self.up, self.act, Hq * D, inter, Hq, 0),
+            lin(self.act, wd, None, self.out, inter, h, 0, 0),
+        ]
+        self._plans[key] = plan
+        return plan
+
+    def run(self, x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale: float):
+        """x [B*T, h]; weights out x in; k_cache, v_cache [B, Hkv, Lcap, D] of one layer.  Enqueues the
+        block on the current stream and returns its output [B*T, h]; intermediates stay in
+        self.q/k/v/attn/up/act."""
+        stream = torch.cuda.current_stream().cuda_stream
+        for name, fn, args in self._calls(x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale):
+            rc = fn(*args, stream)
+            if rc != 0:
+                _b._check(rc, name)
+        return self.out

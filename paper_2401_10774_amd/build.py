@@ -18,7 +18,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libmedusa_hip.so")
 
-SOURCES = ["tree.hip", "heads.hip", "gemm_big.hip", "topk_tree.hip", "tree_attention.hip", "accept.hip", "kv_commit.hip"]
+SOURCES = ["tree.hip", "heads.hip", "gemm_big.hip", "rope.hip", "topk_tree.hip", "tree_attention.hip", "accept.hip", "kv_commit.hip"]
 
 # Per-file code-generation options.  gemm_big.hip keeps MFMA accumulators in ordinary vector
 # registers: with the compiler's default choice its large accumulator tile is copied between the

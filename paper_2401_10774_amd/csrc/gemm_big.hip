@@ -26,6 +26,13 @@
 
 namespace {
 
+// SiLU from the hardware's exp2 and reciprocal instructions (about 1e-6 relative error; the result
+// is rounded to bf16, 4e-3, right after).  The library expf is a function call here, and a call with
+// the whole accumulator tile live spills it.
+__device__ __forceinline__ float silu_fast(float u) {
+  return u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * u));
+}
+
 template <int MT, int NT, int EPI>
 __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m_tiles, int n_tiles) {
   constexpr int BM = 32 * MT, BN = 32 * NT, ROWS = BM + BN;
@@ -45,7 +52,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
   if (n_tile >= n_tiles) return;                      // whole workgroup leaves before any barrier
   const int m0 = (slot - nt_local * m_tiles) * BM, n0 = n_tile * BN;
   const int k = blockIdx.y;
-  const unsigned char* Xb = (const unsigned char*)a.X + (size_t)k * a.xs_k * 2;
+  const unsigned char* Xb = (const unsigned char*)a.X;
   const unsigned char* Wb = (const unsigned char*)a.W + (size_t)k * a.N * a.d * 2;
 
   // Chunk `it` of a thread: tile row it*32 + tid/8 (activation rows first, then weight rows), 16-byte
@@ -54,15 +61,17 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
 #pragma unroll
   for (int it = 0; it < LPT; ++it) {
     const int row = it * 32 + (tid >> 3), c = tid & 7;
-    goff[it] = it < MT ? (uint32_t)(((size_t)min(m0 + row, a.M - 1) * a.xs_m + c * 8) * 2)
+    goff[it] = it < MT ? (uint32_t)((x_row_offset(a, min(m0 + row, a.M - 1), k) + c * 8) * 2)
                        : (uint32_t)(((size_t)min(n0 + row - BM, a.N - 1) * a.d + c * 8) * 2);
   }
   const int nk = a.d >> 6;
   u32x4_t G[LPT];
   auto gload = [&](int step, u32x4_t (&g)[LPT]) __attribute__((always_inline)) {
-    const uint32_t so = (uint32_t)min(step, nk - 1) * 128u;      // past the end: harmless reload
+    const int j0 = min(step, nk - 1) * 64;                       // past the end: harmless reload
+    const uint32_t so_w = (uint32_t)j0 * 2u;
+    const uint32_t so_x = (uint32_t)x_col_offset(a, j0) * 2u;    // differs from so_w for head-major activations
 #pragma unroll
-    for (int it = 0; it < LPT; ++it) g[it] = *(const u32x4_t*)((it < MT ? Xb : Wb) + (goff[it] + so));
+    for (int it = 0; it < LPT; ++it) g[it] = *(const u32x4_t*)((it < MT ? Xb : Wb) + (goff[it] + (it < MT ? so_x : so_w)));
   };
   const int st_off = (tid >> 3) * 128 + (((tid & 7) ^ ((tid >> 4) & 7)) << 4);
   auto lstore = [&](int buf, const u32x4_t (&g)[LPT]) __attribute__((always_inline)) {
@@ -141,22 +150,86 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
     __builtin_amdgcn_sched_group_barrier(0x008, NMF, 0);
   }
 
+  // Epilogue.  An MFMA result tile has four consecutive rows of one column per lane -- no two
+  // neighbouring columns in one lane -- so storing from the registers would issue 2- and 4-byte
+  // accesses.  Each wavefront therefore passes its tile, 16 rows at a time, through a private LDS
+  // area (fp32, row pitch 132 words: conflict-free both ways) and reads it back with 8 consecutive
+  // columns per lane: 16- and 32-byte accesses, four lanes covering a contiguous 32-column run.
+  __syncthreads();                                    // every wavefront is done with the stage buffers
+  constexpr int EP_PITCH = 16 * NT + 4;               // words
+  float* ep = (float*)lds + wave * 16 * EP_PITCH;
+  static_assert(4 * 16 * EP_PITCH * 4 <= 2 * STAGE, "epilogue area must fit the stage buffers");
+  const int er = lane >> 2, ec = (lane & 3) * 8;      // read-back: row, first column of the lane's 8
+  const bool vec = a.vec_epilogue != 0;
 #pragma unroll
-  for (int t = 0; t < MT; ++t)
+  for (int t = 0; t < MT; ++t) {
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
-      const int n = n0 + (wn * NT + j) * 16 + i16;
-      const int mb = m0 + (wm * MT + t) * 16 + 4 * q4;
-      if (n < a.N) {
+    for (int j = 0; j < NT; ++j)
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (mb + r < a.M) epilogue_store<EPI, uint16_t>(a, mb + r, k, n, acc[t][j][r]);
+      for (int r = 0; r < 4; ++r) ep[(4 * q4 + r) * EP_PITCH + j * 16 + i16] = acc[t][j][r];
+    const int m = m0 + (wm * MT + t) * 16 + er;
+    const size_t row_off = m < a.M ? out_row_offset(a, m, k) : 0;
+#pragma unroll
+    for (int c = 0; c < NT / 2; ++c) {
+      const floatx4_t v0 = *(const floatx4_t*)(ep + er * EP_PITCH + c * 32 + ec);
+      const floatx4_t v1 = *(const floatx4_t*)(ep + er * EP_PITCH + c * 32 + ec + 4);
+      const float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+      const int n = n0 + wn * 16 * NT + c * 32 + ec;
+      if (m >= a.M || n >= a.N) continue;
+      if (vec && n + 8 <= a.N) {
+        const size_t o = row_off + out_col_offset(a, n);
+        if (EPI == EPI_LOGITS) {
+          float* dst = (float*)a.out + o;
+          *(floatx4_t*)dst = v0;
+          *(floatx4_t*)(dst + 4) = v1;
+        } else {
+          float y[8];
+          if (EPI == EPI_PLAIN) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] = v[e];
+          } else {
+            // EPI_RESID: hidden[m][n..] with row length d (= N);  EPI_GATED: mul[m][n..] with row length N
+            const u32x4_t h = *(const u32x4_t*)((const uint16_t*)a.hidden + (size_t)m * a.N + n);
+            const uint32_t hw[4] = {h.x, h.y, h.z, h.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              const float u = bf16_bits_to_float((hw[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+              y[e] = EPI == EPI_RESID ? silu_fast(v[e]) + u : silu_fast(v[e]) * u;
+            }
+          }
+          u32x4_t w;
+          w.x = pack_bf16x2(y[0], y[1]);
+          w.y = pack_bf16x2(y[2], y[3]);
+          w.z = pack_bf16x2(y[4], y[5]);
+          w.w = pack_bf16x2(y[6], y[7]);
+          *(u32x4_t*)((uint16_t*)a.out + o) = w;
+        }
+      } else {
+        // ragged or unaligned output: one element at a time
+        for (int e = 0; e < 8; ++e) {
+          if (n + e >= a.N) break;
+          const size_t o = row_off + out_col_offset(a, n + e);
+          if (EPI == EPI_LOGITS) {
+            ((float*)a.out)[o] = v[e];
+          } else if (EPI == EPI_PLAIN) {
+            ((uint16_t*)a.out)[o] = (uint16_t)float_to_bf16_bits(v[e]);
+          } else {
+            const float u = bf16_bits_to_float(((const uint16_t*)a.hidden)[(size_t)m * a.N + n + e]);
+            ((uint16_t*)a.out)[o] = (uint16_t)float_to_bf16_bits(EPI == EPI_RESID ? silu_fast(v[e]) + u : silu_fast(v[e]) * u);
+          }
+        }
       }
     }
+  }
 }
 
 template <int EPI>
-int launch(const GemmArgs& a, hipStream_t stream) {
+int launch(const GemmArgs& a_in, hipStream_t stream) {
+  GemmArgs a = a_in;
+  // 16-byte epilogue accesses need 8-column runs that are contiguous and aligned in the output and
+  // in the tensor the epilogue reads
+  const size_t align = (size_t)a.out | (size_t)(EPI == EPI_RESID || EPI == EPI_GATED ? a.hidden : nullptr);
+  a.vec_epilogue = a.N % 8 == 0 && align % 16 == 0 && (a.y_dh == 0 || a.y_dh % 8 == 0) ? 1 : 0;
   // 192 x 256 or 128 x 256 tile, whichever pads M less (ties to the larger)
   const int n_tiles = ceil_div(a.N, 256);
   const bool tall = ceil_div(a.M, 192) * 192 <= ceil_div(a.M, 128) * 128;
@@ -172,6 +245,12 @@ int launch(const GemmArgs& a, hipStream_t stream) {
 
 int launch_gemm_big(const GemmArgs& a, int epi, hipStream_t stream) {
   if (a.d % 64 != 0 || a.d < 64) return MEDUSA_EUNSUPPORTED;
-  if ((size_t)a.N * a.d >= ((size_t)1 << 31) || (size_t)a.M * a.xs_m >= ((size_t)1 << 31)) return MEDUSA_EUNSUPPORTED;
-  return epi == EPI_LOGITS ? launch<EPI_LOGITS>(a, stream) : launch<EPI_RESID>(a, stream);
+  if ((size_t)a.N * a.d >= ((size_t)1 << 31) || x_extent(a) >= ((size_t)1 << 31)) return MEDUSA_EUNSUPPORTED;
+  switch (epi) {
+    case EPI_LOGITS: return launch<EPI_LOGITS>(a, stream);
+    case EPI_RESID: return launch<EPI_RESID>(a, stream);
+    case EPI_PLAIN: return launch<EPI_PLAIN>(a, stream);
+    case EPI_GATED: return launch<EPI_GATED>(a, stream);
+  }
+  return MEDUSA_EINVAL;
 }

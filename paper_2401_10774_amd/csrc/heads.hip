@@ -15,6 +15,8 @@
 
 namespace {
 
+constexpr int kMaxSplitTiles = 1024;       // output tiles x heads a split reduction may cover
+
 // ---------------------------------------------------------------------------------------
 // bf16, M <= 4 per block of rows: wave-per-row streaming GEMV.
 // grid (row blocks, K, m blocks), 256 threads.  LDS: MB x d bf16.
@@ -30,7 +32,7 @@ __global__ __launch_bounds__(256) void gemv_bf16_kernel(GemmArgs a) {
   for (int i = threadIdx.x; i < MB * chunks; i += 256) {
     const int mm = i / chunks, c = i - mm * chunks;
     u32x4_t v = {0, 0, 0, 0};
-    if (m0 + mm < a.M) v = *(const u32x4_t*)(X + (size_t)(m0 + mm) * a.xs_m + (size_t)k * a.xs_k + (size_t)c * 8);
+    if (m0 + mm < a.M) v = *(const u32x4_t*)(X + x_row_offset(a, m0 + mm, k) + x_col_offset(a, c * 8));
     xs[i] = v;
   }
   __syncthreads();
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(GemmArgs a) {
   for (int i = threadIdx.x; i < MB * chunks; i += 256) {
     const int mm = i / chunks, c = i - mm * chunks;
     floatx4_t v = {0.f, 0.f, 0.f, 0.f};
-    if (m0 + mm < a.M) v = *(const floatx4_t*)(X + (size_t)(m0 + mm) * a.xs_m + (size_t)k * a.xs_k + (size_t)c * 4);
+    if (m0 + mm < a.M) v = *(const floatx4_t*)(X + x_row_offset(a, m0 + mm, k) + x_col_offset(a, c * 4));
     xs[i] = v;
   }
   __syncthreads();
@@ -140,7 +142,16 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(GemmArgs a) {
 // operands (lane l: row l%16, elements 8*(l/16)..+7 of a 32-element step).  One barrier per step.
 // Output layout of the MFMA: lane l holds column l%16 (weight row), rows 4*(l/16)..+3
 // (activation rows).  grid (ceil(N/BN), K, ceil(M/BM)), 256 threads.
+//
+// Split reduction (WM == 1 only, where one workgroup spans all activation rows and grid.z is
+// free): when N is so small that N/BN workgroups would leave most of the chip idle (the d x d
+// and d x 4d/3 projections of a decoder block), grid.z = ksplit workgroups share an output tile,
+// each reducing a contiguous 1/ksplit of d.  They park their fp32 partial tiles in a workspace;
+// the workgroup that arrives last adds them up in split order (so the result does not depend on
+// which one that is) and runs the epilogue.
 // ---------------------------------------------------------------------------------------
+__device__ unsigned int g_gemm_ticket[kMaxSplitTiles];
+
 template <int WM, int WN, int MT, int NT, int BK, int PD, int EPI>
 __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
   constexpr int BM = WM * 16 * MT, BN = WN * 16 * NT;
@@ -156,19 +167,22 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
   const int i16 = lane & 15, q4 = lane >> 4;
   const int wm = wave / WN, wn = wave - wm * WN;
   const int k = blockIdx.y;
-  const int n0 = blockIdx.x * BN, m0 = blockIdx.z * BM;
+  const int n_split = WM == 1 ? a.ksplit : 1, split = WM == 1 ? blockIdx.z : 0;
+  const int n0 = blockIdx.x * BN, m0 = WM == 1 ? 0 : blockIdx.z * BM;
   const uint16_t* W = (const uint16_t*)a.W + (size_t)k * a.N * a.d;
-  const uint16_t* X = (const uint16_t*)a.X + (size_t)k * a.xs_k;
+  const uint16_t* X = (const uint16_t*)a.X;
 
   // Per-thread source pointers and LDS offsets of its LPT chunks (rows clamped into range; the
   // surplus chunk ids of the last slot repeat the final chunk, which is harmless).
   const uint16_t* src[LPT];
   int dst[LPT];
+  bool is_x[LPT];
 #pragma unroll
   for (int it = 0; it < LPT; ++it) {
     const int id = min(it * 256 + tid, CHUNKS - 1);
     const int row = id / CPR, c = id - row * CPR;
-    src[it] = row < BM ? X + (size_t)min(m0 + row, a.M - 1) * a.xs_m + c * 8
+    is_x[it] = row < BM;
+    src[it] = row < BM ? X + x_row_offset(a, min(m0 + row, a.M - 1), k) + c * 8
                        : W + (size_t)min(n0 + row - BM, a.N - 1) * a.d + c * 8;
     dst[it] = row * PITCH + ((c ^ ((row >> 1) & 7)) << 4);
   }
@@ -179,12 +193,15 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
 #pragma unroll
     for (int j = 0; j < NT; ++j) acc[t][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
-  const int nk = a.d / BK;
+  const int nk_all = a.d / BK;
+  const int step0 = (int)((long)nk_all * split / n_split);
+  const int nk = (int)((long)nk_all * (split + 1) / n_split) - step0;    // this workgroup's share of the reduction (>= 1)
   u32x4_t regs[PD][LPT];
   auto gload = [&](int step, u32x4_t (&r)[LPT]) {
-    const int off = min(step, nk - 1) * BK;
+    const int off_w = (step0 + min(step, nk - 1)) * BK;
+    const int off_x = (int)x_col_offset(a, off_w);       // differs from off_w for head-major activations
 #pragma unroll
-    for (int it = 0; it < LPT; ++it) r[it] = *(const u32x4_t*)(src[it] + off);
+    for (int it = 0; it < LPT; ++it) r[it] = *(const u32x4_t*)(src[it] + (is_x[it] ? off_x : off_w));
   };
   auto lstore = [&](int buf, const u32x4_t (&r)[LPT]) {
 #pragma unroll
@@ -239,6 +256,52 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
     }
   }
 
+  if (WM == 1 && n_split > 1) {
+    // partial tile of this split: [fragment][register pair][thread], 8 bytes per thread and store
+    const unsigned int tile = k * gridDim.x + blockIdx.x;
+    constexpr int PART = MT * NT * 2 * 256;              // 8-byte words per partial tile
+    uint64_t* part = (uint64_t*)a.ws + (size_t)tile * n_split * PART;
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int rp = 0; rp < 2; ++rp) {
+          const uint64_t v = (uint64_t)__float_as_uint(acc[t][j][2 * rp]) | ((uint64_t)__float_as_uint(acc[t][j][2 * rp + 1]) << 32);
+          store_agent(part + (size_t)split * PART + ((t * NT + j) * 2 + rp) * 256 + tid, v);
+        }
+    if (!last_workgroup_of(&g_gemm_ticket[tile], (unsigned int)n_split)) return;
+    // Sum in split order.  The loads of a group of slots are all issued before the first sum (each is a
+    // round trip to the memory side of the L2, where the other workgroups' stores are visible); splits
+    // past the last one re-read the last one and are not added.
+    constexpr int SLOTS = MT * NT * 2, GROUP = 4, MAXS = 8;
+#pragma unroll
+    for (int s0 = 0; s0 < SLOTS; s0 += GROUP) {
+      uint64_t v[GROUP][MAXS];
+#pragma unroll
+      for (int g = 0; g < GROUP; ++g)
+#pragma unroll
+        for (int z = 0; z < MAXS; ++z) {
+          const int slot = s0 + g < SLOTS ? s0 + g : SLOTS - 1;
+          v[g][z] = load_agent(part + (size_t)min(z, n_split - 1) * PART + slot * 256 + tid);
+        }
+#pragma unroll
+      for (int g = 0; g < GROUP; ++g) {
+        if (s0 + g >= SLOTS) continue;
+        float lo = 0.f, hi = 0.f;
+#pragma unroll
+        for (int z = 0; z < MAXS; ++z)
+          if (z < n_split) {
+            lo += __uint_as_float((uint32_t)v[g][z]);
+            hi += __uint_as_float((uint32_t)(v[g][z] >> 32));
+          }
+        const int slot = s0 + g, frag = slot >> 1, rp = slot & 1;
+        acc[frag / NT][frag % NT][2 * rp] = lo;
+        acc[frag / NT][frag % NT][2 * rp + 1] = hi;
+      }
+    }
+  }
+
 #pragma unroll
   for (int t = 0; t < MT; ++t)
 #pragma unroll
@@ -251,6 +314,33 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
           if (mb + r < a.M) epilogue_store<EPI, uint16_t>(a, mb + r, k, n, acc[t][j][r]);
       }
     }
+}
+
+// Tile width and number of reduction splits of the skinny kernel: 128-row tiles when they alone
+// give a few hundred workgroups, else 64-row tiles, with the reduction split when even those are
+// too few.  (Measured at M = 65, N = d = 4096: 64-row tiles x 8 splits 21 us, 128-row tiles x 8
+// splits 27 us, unsplit 37 us: the number of workgroups matters more than the activation re-reads.)
+struct SkinnyPlan {
+  bool wide;
+  int ksplit;
+};
+SkinnyPlan skinny_plan(int M, int N, int d, int K, bool have_ws) {
+  SkinnyPlan p;
+  p.wide = (long)ceil_div(N, 128) * K >= 200;               // measured at V = 32000: 52 us wide, 63 us narrow
+  p.ksplit = 1;
+  if (p.wide || !have_ws || M <= 4 || M > 80) return p;
+  const long tiles = (long)ceil_div(N, 64) * K;
+  if (tiles >= 192 || tiles > kMaxSplitTiles) return p;
+  long s = 512 / tiles;
+  const long by_steps = (d / 64) / 8;                       // at least 8 reduction steps per split
+  s = s < by_steps ? s : by_steps;
+  p.ksplit = (int)(s < 1 ? 1 : (s > 8 ? 8 : s));
+  return p;
+}
+size_t skinny_ws_bytes(int M, int N, int d, int K) {
+  const SkinnyPlan p = skinny_plan(M, N, d, K, true);
+  if (p.ksplit <= 1) return 0;
+  return (size_t)ceil_div(N, p.wide ? 128 : 64) * K * p.ksplit * ceil_div(M, 16) * (p.wide ? 2 : 1) * 4 * 256 * sizeof(float);
 }
 
 // Optional event pair recorded around the vocabulary-projection launch (benchmark hook).
@@ -266,6 +356,7 @@ int gemv_rows_per_wg(int N, int K) {
 template <int EPI>
 int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) {
   GemmArgs a = a_in;
+  a.ksplit = 1;
   a.rows_per_wg = gemv_rows_per_wg(a.N, a.K);
   const int kGemvRowsPerWg = a.rows_per_wg;
   const dim3 block(256);
@@ -285,11 +376,13 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
     else if (MB == 2) hipLaunchKernelGGL((gemv_bf16_kernel<2, EPI>), grid, block, lds, stream, a);
     else hipLaunchKernelGGL((gemv_bf16_kernel<4, EPI>), grid, block, lds, stream, a);
   } else if (a.M <= 80) {
-    // skinny: every wavefront sees all activation rows; 128 weight rows per workgroup when that
-    // still yields a few hundred workgroups, else 64
+    // skinny: every wavefront sees all activation rows; 128 or 64 weight rows per workgroup, the
+    // reduction split over several workgroups when the output is narrow (skinny_plan)
     const int MT = ceil_div(a.M, 16);
-    const bool wide = (long)ceil_div(a.N, 128) * a.K >= 200;   // measured at V = 32000: 52 us wide, 63 us narrow
-    const dim3 grid(ceil_div(a.N, wide ? 128 : 64), a.K, 1);
+    const SkinnyPlan plan = skinny_plan(a.M, a.N, a.d, a.K, a.ws != nullptr);
+    const bool wide = plan.wide;
+    a.ksplit = plan.ksplit;
+    const dim3 grid(ceil_div(a.N, wide ? 128 : 64), a.K, a.ksplit);
 #define MEDUSA_SKINNY(MT_)                                                                                         \
   case MT_:                                                                                                        \
     if (!wide) hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 1, 64, 4, EPI>), grid, block, 0, stream, a);    \
@@ -299,16 +392,19 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
       MEDUSA_SKINNY(1) MEDUSA_SKINNY(2) MEDUSA_SKINNY(3) MEDUSA_SKINNY(4) MEDUSA_SKINNY(5)
     }
 #undef MEDUSA_SKINNY
-  } else if ((size_t)a.N * a.d >= ((size_t)1 << 31) || (size_t)a.M * a.xs_m >= ((size_t)1 << 31)) {
-    // byte offsets beyond 32 bits: 128 x 128 tile with 64-bit addressing, wavefronts 2 x 2, each 64 x 64
-    const dim3 grid(ceil_div(a.N, 128), a.K, ceil_div(a.M, 128));
-    hipLaunchKernelGGL((gemm_lds_bf16_kernel<2, 2, 4, 4, 64, 2, EPI>), grid, block, 0, stream, a);
-  } else if ((size_t)a.N * a.d >= ((size_t)1 << 31) || (size_t)a.M * a.xs_m >= ((size_t)1 << 31)) {
-    // element offsets beyond 31 bits: 128 x 128 tile with 64-bit addressing, wavefronts 2 x 2, each 64 x 64
-    const dim3 grid(ceil_div(a.N, 128), a.K, ceil_div(a.M, 128));
-    hipLaunchKernelGGL((gemm_lds_bf16_kernel<2, 2, 4, 4, 64, 2, EPI>), grid, block, 0, stream, a);
   } else {
-    return launch_gemm_big(a, EPI, stream);
+    // The large tile pays off only when there is about one tile per CU or more; below that (the
+    // d x d and 4d/3 x d projections at a few hundred rows) the 128 x 128 kernel's three to four
+    // times as many workgroups win (measured 10-30 % at M = 356 and 1040).
+    const bool tall = ceil_div(a.M, 192) * 192 <= ceil_div(a.M, 128) * 128;
+    const long big_tiles = (long)ceil_div(a.M, tall ? 192 : 128) * ceil_div(a.N, 256) * a.K;
+    const bool wide_offsets = (size_t)a.N * a.d >= ((size_t)1 << 31) || x_extent(a) >= ((size_t)1 << 31);
+    if (big_tiles < 200 || wide_offsets) {     // (the large-tile kernel addresses with 32-bit element offsets)
+      const dim3 grid(ceil_div(a.N, 128), a.K, ceil_div(a.M, 128));
+      hipLaunchKernelGGL((gemm_lds_bf16_kernel<2, 2, 4, 4, 64, 2, EPI>), grid, block, 0, stream, a);
+    } else {
+      return launch_gemm_big(a, EPI, stream);
+    }
   }
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;
@@ -325,7 +421,7 @@ extern "C" int medusa_heads(const void* hidden, const void* w1, const void* w2, 
   if (dtype == MEDUSA_BF16 ? (d % 64 != 0) : (d % 8 != 0)) return MEDUSA_EUNSUPPORTED;
   if ((size_t)M * K * V >= (size_t)1 << 40) return MEDUSA_EUNSUPPORTED;
   hipStream_t stream = (hipStream_t)stream_;
-  GemmArgs a;
+  GemmArgs a = {};
   a.d = d;
   a.M = M;
   a.K = K;
@@ -355,6 +451,52 @@ extern "C" int medusa_heads(const void* hidden, const void* w1, const void* w2, 
   const int rc = launch_gemm<EPI_LOGITS>(a, dtype, stream);
   if (prof && rc == MEDUSA_OK) MEDUSA_HIP_TRY(hipEventRecord(g_prof_stop, stream));
   return rc;
+}
+
+// Backbone linear layer on the tree tokens (App. G, operator table, parallel-decoding rows).
+extern "C" size_t tree_linear_workspace_bytes(int B, int T, int d_in, int d_out, medusa_dtype_t dtype) {
+  if (dtype != MEDUSA_BF16 || B < 1 || T < 1 || d_in < 64 || d_out < 1) return 0;
+  return skinny_ws_bytes(B * T, d_out, d_in, 1);
+}
+
+extern "C" int tree_linear(const void* x, const void* w, const void* mul, void* y, int B, int T, int d_in, int d_out,
+                           int x_heads, int y_heads, medusa_dtype_t dtype, void* workspace, size_t workspace_bytes,
+                           medusa_stream_t stream_) {
+  if (!x || !w || !y) return MEDUSA_EINVAL;
+  if (B < 1 || T < 1 || d_in < 1 || d_out < 1 || x_heads < 0 || y_heads < 0) return MEDUSA_EINVAL;
+  if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;
+  const long M = (long)B * T;
+  if (M > 4096 || d_in > 65536) return MEDUSA_EUNSUPPORTED;
+  const int gran = dtype == MEDUSA_BF16 ? 64 : 8;       // reduction elements the kernels fetch as one contiguous piece
+  if (d_in % gran != 0) return MEDUSA_EUNSUPPORTED;
+  if (x_heads > 0 && (d_in % x_heads != 0 || (d_in / x_heads) % gran != 0)) return MEDUSA_EUNSUPPORTED;
+  if (y_heads > 0 && d_out % y_heads != 0) return MEDUSA_EINVAL;
+  GemmArgs a = {};
+  a.W = w;
+  a.X = x;
+  a.hidden = mul;
+  a.out = y;
+  a.M = (int)M;
+  a.N = d_out;
+  a.d = d_in;
+  a.K = 1;
+  a.xs_m = d_in;
+  a.xs_k = 0;
+  if (x_heads > 0) {
+    a.x_T = T;
+    a.x_heads = x_heads;
+    a.x_dh = d_in / x_heads;
+  }
+  if (y_heads > 0) {
+    a.y_T = T;
+    a.y_heads = y_heads;
+    a.y_dh = d_out / y_heads;
+  }
+  // the split reduction is an optimisation: without (enough) workspace the call runs unsplit
+  if (workspace && dtype == MEDUSA_BF16 && workspace_bytes >= skinny_ws_bytes(a.M, a.N, a.d, 1) && skinny_ws_bytes(a.M, a.N, a.d, 1) > 0)
+    a.ws = workspace;
+  hipStream_t stream = (hipStream_t)stream_;
+  return mul ? launch_gemm<EPI_GATED>(a, dtype, stream) : launch_gemm<EPI_PLAIN>(a, dtype, stream);
 }
 
 extern "C" int medusa_profile_set_events(void* start, void* stop) {

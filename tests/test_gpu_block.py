@@ -1,0 +1,142 @@
+"""GPU parity of the backbone operators on the tree tokens (App. G operator table and simplified
+block; Sec. 2.1.2 positional indices) against the CPU oracle, through the C ABI."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2401_10774_amd as M
+from paper_2401_10774_amd.block import SimplifiedBlock
+from oracle import medusa_oracle as O
+from workloads import draw_normal
+from _harness import TOL, row_rel_err, to_dev, to_host_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _bits_to_f64(x):
+    return O.widen(x)
+
+
+def linear_case(dtype, B, T, d_in, d_out, x_heads, y_heads, gated, seed):
+    Mrows = B * T
+    x = draw_normal(seed, 0, (Mrows, d_in), 1.0, dtype)
+    w = draw_normal(seed, 1, (d_out, d_in), 0.02, dtype)
+    mul = draw_normal(seed, 2, (Mrows, d_out), 1.0, dtype) if gated else None
+    xd = to_dev(x)
+    if x_heads:
+        xd = xd.view(B, T, x_heads, d_in // x_heads).permute(0, 2, 1, 3).contiguous()     # head-major copy of the same values
+    y = M.tree_linear(xd, to_dev(w), B, T, mul=None if mul is None else to_dev(mul), y_heads=y_heads)
+    torch.cuda.synchronize()
+    ref = O.tree_linear_ref(x, w, dtype, mul=mul)
+    got = to_host_f64(y)
+    if y_heads:
+        got = O.from_heads(got)
+    err = row_rel_err(got, ref)
+    assert err <= TOL[dtype], f"tree_linear rel err {err}"
+
+
+@pytest.mark.parametrize("rows", [(1, 1), (1, 3), (1, 10), (1, 65), (2, 50), (4, 89)])
+@pytest.mark.parametrize("variant", ["plain", "gated", "heads_in", "heads_out"])
+def test_linear_bf16(rows, variant):
+    B, T = rows
+    linear_case("bf16", B, T, 512, 384, 4 if variant == "heads_in" else 0, 3 if variant == "heads_out" else 0,
+                variant == "gated", 300 + B * T)
+
+
+def test_linear_bf16_large_m_and_ragged_n():
+    linear_case("bf16", 16, 65, 256, 1000, 0, 0, False, 401)          # 1040 rows: the large-M kernel, N not a tile multiple
+    linear_case("bf16", 16, 65, 256, 1024, 2, 8, True, 402)           # all options at once
+    linear_case("bf16", 3, 70, 1024, 200, 8, 0, False, 403)
+
+
+def test_linear_bf16_large_tile_kernel():
+    # enough output tiles (M/192 x N/256 >= 200) for the large-tile kernel: its vector epilogues,
+    # both layouts on both sides, and the element-wise fallback for a ragged N
+    linear_case("bf16", 16, 65, 128, 8704, 0, 0, False, 420)
+    linear_case("bf16", 16, 65, 128, 8704, 2, 68, True, 421)
+    linear_case("bf16", 16, 65, 128, 8700, 0, 0, True, 422)
+    linear_case("bf16", 4, 89, 192, 25600, 0, 0, False, 423)          # 356 rows: two 192-row tiles
+
+
+def test_linear_f32():
+    linear_case("f32", 1, 10, 256, 96, 0, 0, False, 410)
+    linear_case("f32", 2, 10, 256, 128, 4, 2, True, 411)
+
+
+def test_linear_rejects_bad_shapes():
+    x = torch.zeros((4, 96), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((64, 96), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(M.MedusaError):
+        M.tree_linear(x, w, 1, 4)                                      # d_in not a multiple of 64
+
+
+@pytest.mark.parametrize("dtype,D,maxpos", [("bf16", 128, 8300), ("bf16", 64, 300), ("f32", 64, 200), ("f32", 128, 9000)])
+def test_rope(dtype, D, maxpos):
+    B, Hq, Hkv, T = 2, 4, 2, 9
+    q = draw_normal(500, 0, (B, Hq, T, D), 1.0, dtype)
+    k = draw_normal(500, 1, (B, Hkv, T, D), 1.0, dtype)
+    rng = np.random.default_rng(7)
+    pos = rng.integers(0, maxpos, size=(B, T)).astype(np.int32)
+    pos[0, 0] = 0
+    pos[1, -1] = maxpos
+    qd, kd = to_dev(q), to_dev(k)
+    M.tree_rope(qd, kd, to_dev(pos), 10000.0)
+    torch.cuda.synchronize()
+    for got, src in ((qd, q), (kd, k)):
+        ref = O.rope_ref(src, pos, 10000.0, dtype)
+        err = row_rel_err(to_host_f64(got), ref)
+        assert err <= TOL[dtype], f"tree_rope rel err {err}"
+
+
+def block_case(dtype, branching, B, h, Hq, Hkv, D, inter, Lcap, prefix, seed):
+    tree_o = O.tree_cartesian(branching)
+    tree_g = M.MedusaTree(branching=branching)
+    T = tree_o.T
+    x = draw_normal(seed, 0, (B * T, h), 1.0, dtype)
+    ws = {n: draw_normal(seed, 10 + i, shape, 1.0 / math.sqrt(shape[1]), dtype)
+          for i, (n, shape) in enumerate((("wq", (Hq * D, h)), ("wk", (Hkv * D, h)), ("wv", (Hkv * D, h)),
+                                          ("wu", (inter, Hq * D)), ("wg", (inter, Hq * D)), ("wd", (h, inter))))}
+    kc = draw_normal(seed, 20, (B, Hkv, Lcap, D), 1.0, dtype)
+    vc = draw_normal(seed, 21, (B, Hkv, Lcap, D), 1.0, dtype)
+    pl = np.asarray(prefix, np.int32)
+    pos = (pl[:, None] + np.asarray(tree_o.depth, np.int32)[None, :]).astype(np.int32)
+    scale, theta = 1.0 / math.sqrt(D), 10000.0
+    blk = SimplifiedBlock(tree_g, B, h, Hq, Hkv, D, inter, Lcap, torch.bfloat16 if dtype == "bf16" else torch.float32)
+    out = blk.run(to_dev(x), *(to_dev(ws[n]) for n in ("wq", "wk", "wv", "wu", "wg", "wd")), to_dev(kc), to_dev(vc),
+                  to_dev(pl), to_dev(pos), scale)
+    torch.cuda.synchronize()
+    ref = O.simplified_block_ref(x, ws["wq"], ws["wk"], ws["wv"], ws["wu"], ws["wg"], ws["wd"], kc, vc, pl, pos, tree_o,
+                                 Hq, Hkv, scale, theta, dtype)
+    got = {"q": blk.q, "k": blk.k, "v": blk.v, "attn": blk.attn, "up": blk.up, "act": blk.act, "out": out}
+    # end to end every intermediate inherits the rounding differences of its predecessors: a few
+    # storage roundings deep, so the bound is the per-operator tolerance times the chain length
+    depth = {"q": 2, "k": 2, "v": 1, "attn": 3, "up": 4, "act": 5, "out": 6}
+    for name in ("q", "k", "v", "attn", "up", "act", "out"):
+        err = row_rel_err(to_host_f64(got[name]), ref[name])
+        assert err <= TOL[dtype] * depth[name], f"{name}: rel err {err}"
+    # stage-wise, from the GPU's own inputs: each operator alone meets the per-operator tolerance
+    g64 = {n: to_host_f64(t) for n, t in got.items()}
+    a_tok = O.from_heads(g64["attn"])
+    checks = {
+        "attn": (O.round_to_storage(O.tree_attention_ref(g64["q"], g64["k"], g64["v"], kc, vc, pl, tree_o, scale), dtype), g64["attn"]),
+        "up": (O.tree_linear_ref(a_tok, ws["wu"], dtype), g64["up"]),
+        "act": (O.tree_linear_ref(a_tok, ws["wg"], dtype, mul=g64["up"]), g64["act"]),
+        "out": (O.tree_linear_ref(g64["act"], ws["wd"], dtype), g64["out"]),
+    }
+    for name, (want, have) in checks.items():
+        err = row_rel_err(have, want)
+        assert err <= TOL[dtype], f"{name} (stage-wise): rel err {err}"
+
+
+def test_block_f32_small():
+    block_case("f32", (3, 2), 1, 256, 4, 4, 64, 512, 160, [128], 600)
+
+
+def test_block_bf16_gqa_ragged():
+    block_case("bf16", (4, 3, 2, 1), 2, 512, 8, 2, 64, 1024, 700, [600, 37], 601)
+
+
+def test_block_bf16_head_dim_128():
+    block_case("bf16", (2, 2, 1), 1, 512, 4, 4, 128, 768, 400, [300], 602)
