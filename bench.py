@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--block", action="store_true",
                     help="time the simplified decoder block of App. G on the tree tokens instead of the verification "
                          "step (its own JSON line; the headline metric stays the verification step)")
+    ap.add_argument("--speed-model", action="store_true",
+                    help="measure the simplified block at 1..112 candidate tokens and print the appendix's simulated "
+                         "speedup for this GPU (its own JSON line)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three plain 1 GiB device copies (reference kernel of known size for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -92,6 +95,9 @@ def main():
     torch.cuda.set_device(0)
     if args.block:
         bench_block(args, cfg)
+        return
+    if args.speed_model:
+        bench_speed_model(args, cfg)
         return
 
     t0 = time.time()
@@ -275,6 +281,84 @@ def bench_block(args, cfg):
                       "frac_of_peak": round(total / ms / 1e6 / HBM_PEAK_GBS, 4)},
         "block_flops": {"useful_TFLOPs": round(flops / ms / 1e9, 1)},
     }), flush=True)
+
+
+def bench_speed_model(args, cfg):
+    """The simulation of the appendix on hardware constraints with measured MI355X latencies: one
+    simplified block at q = 1, 16, ..., 112 candidate tokens (q = 1 is plain decoding), speedup(q) =
+    0.477 log2(q) * latency(1) / latency(q); batch and prefix length sweeps as in the appendix's
+    three experiments.  Trees: the greedy sparse tree of q - 1 nodes on the synthetic accuracy table."""
+    import torch
+
+    import paper_2401_10774_amd as M
+    from paper_2401_10774_amd import speed_model as S
+    from paper_2401_10774_amd.block import SimplifiedBlock
+    from workloads import synthetic_accuracy_table
+
+    h, Hq, Hkv, D = cfg.d, cfg.Hq, cfg.Hkv, cfg.D
+    inter = {4096: 11008, 5120: 13824}.get(h, ((h * 8 // 3 + 255) // 256) * 256)
+    shape = S.BlockShape(h=h, inter=inter, n_heads=Hq, n_kv_heads=Hkv, d=D)
+    dt = torch.bfloat16
+    gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    rnd = lambda *shp, std=1.0: (torch.randn(shp, generator=gen, device="cuda", dtype=torch.float32) * std).to(dt)
+    n_sets = 6
+    wsets = [dict(wq=rnd(Hq * D, h, std=h ** -0.5), wk=rnd(Hkv * D, h, std=h ** -0.5), wv=rnd(Hkv * D, h, std=h ** -0.5),
+                  wu=rnd(inter, Hq * D, std=h ** -0.5), wg=rnd(inter, Hq * D, std=h ** -0.5), wd=rnd(h, inter, std=inter ** -0.5))
+             for _ in range(n_sets)]
+    qs = [1, 16, 32, 48, 64, 80, 96, 112]
+    acc = synthetic_accuracy_table(5, 10)
+    trees = {q: (M.MedusaTree(nodes=[]) if q == 1 else M.MedusaTree(accuracy=acc, n_nodes=q - 1)) for q in qs}
+    scale = 1.0 / math.sqrt(D)
+    experiments = [("batch 1, prefix 1024", 1, 1024), ("batch 4, prefix 1024", 4, 1024), ("batch 16, prefix 1024", 16, 1024),
+                   ("batch 32, prefix 1024", 32, 1024), ("batch 4, prefix 4096", 4, 4096)]
+    results = {}
+    for label, B, s_len in experiments:
+        Lcap = s_len + 128
+        caches = [(rnd(B, Hkv, Lcap, D), rnd(B, Hkv, Lcap, D)) for _ in range(max(2, min(n_sets, int(1.5e9 // (4 * B * Hkv * Lcap * D)))))]
+        pl = torch.full((B,), s_len, dtype=torch.int32, device="cuda")
+        lat = {}
+        for q in qs:
+            tree = trees[q]
+            T = tree.T
+            blk = SimplifiedBlock(tree, B, h, Hq, Hkv, D, inter, Lcap, dt)
+            x = rnd(B * T, h)
+            pos = (pl[:, None] + torch.from_numpy(tree.depth).to(device="cuda", dtype=torch.int32)[None, :]).to(torch.int32).contiguous()
+
+            def run(i):
+                w = wsets[i % n_sets]
+                kc, vc = caches[i % len(caches)]
+                blk.run(x, w["wq"], w["wk"], w["wv"], w["wu"], w["wg"], w["wd"], kc, vc, pl, pos, scale)
+
+            for i in range(12):
+                run(i)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            n = 60
+            e0.record()
+            for i in range(n):
+                run(i)
+            e1.record()
+            torch.cuda.synchronize()
+            lat[q] = e0.elapsed_time(e1) / n * 1e-3
+            del blk
+        rows = S.simulate_speedup(lambda q: lat[q], qs)
+        roof = S.simulate_speedup(lambda q: S.roofline_latency(shape, B, q, s_len, 2.5e15, 8e12), qs)
+        results[label] = {"best_candidates": S.best_candidates(rows), "best_speedup": round(max(r["speedup"] for r in rows), 3),
+                          "latency_us": {str(q): round(lat[q] * 1e6, 1) for q in qs},
+                          "speedup": {str(r["candidates"]): round(r["speedup"], 3) for r in rows},
+                          "roofline_best_candidates": S.best_candidates(roof)}
+        print(f"[bench] {label}:", file=sys.stderr)
+        for r, rr in zip(rows, roof):
+            print(f"[bench]   q={r['candidates']:4d}  block {r['latency'] * 1e6:8.1f} us  x{r['normalized_latency']:5.2f}  "
+                  f"acc_rate {r['acc_rate']:5.2f}  speedup {r['speedup']:5.2f}   (roofline-only speedup {rr['speedup']:5.2f})",
+                  file=sys.stderr, flush=True)
+        del caches
+    print(json.dumps({
+        "metric": "simulated Medusa speedup of the simplified decoder block (appendix model, measured latencies)",
+        "value": results[experiments[0][0]]["best_speedup"], "unit": "x vs. one token per block", "n_gpus": 1, "steps": 60, "warmup": 12,
+        "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name} block shapes h={h} inter={inter} heads={Hq}/{Hkv}x{D}; candidates {qs}"},
+        "experiments": results}), flush=True)
 
 
 def breakdown(step, cfg, parts):

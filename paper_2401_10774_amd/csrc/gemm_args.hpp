@@ -31,24 +31,33 @@ struct GemmArgs {
 
 // Element offset of X(m, k, 0) and of column j relative to it.  Chunks of up to x_dh consecutive
 // j (aligned) are contiguous in either layout.
+// The head-major forms exist only for the epilogues tree_linear uses (HM): the kernels of
+// medusa_heads are compiled without them.
+template <int EPI>
+constexpr bool kHeadMajor = EPI == 2 || EPI == 3;      // EPI_PLAIN, EPI_GATED
+
+template <bool HM>
 __device__ __forceinline__ size_t x_row_offset(const GemmArgs& a, int m, int k) {
-  if (a.x_dh == 0) return (size_t)m * a.xs_m + (size_t)k * a.xs_k;
+  if (!HM || a.x_dh == 0) return (size_t)m * a.xs_m + (size_t)k * a.xs_k;
   const int b = m / a.x_T, t = m - b * a.x_T;
   return ((size_t)b * a.x_heads * a.x_T + t) * a.x_dh;
 }
+template <bool HM>
 __device__ __forceinline__ size_t x_col_offset(const GemmArgs& a, int j) {
-  if (a.x_dh == 0) return (size_t)j;
+  if (!HM || a.x_dh == 0) return (size_t)j;
   const int head = j / a.x_dh;
   return (size_t)head * a.x_T * a.x_dh + (j - head * a.x_dh);
 }
 // Element offset of the output at (m, k, n) = out_row_offset + out_col_offset.
+template <bool HM>
 __device__ __forceinline__ size_t out_row_offset(const GemmArgs& a, int m, int k) {
-  if (a.y_dh == 0) return ((size_t)m * a.K + k) * a.N;
+  if (!HM || a.y_dh == 0) return ((size_t)m * a.K + k) * a.N;
   const int b = m / a.y_T, t = m - b * a.y_T;
   return ((size_t)b * a.y_heads * a.y_T + t) * a.y_dh;
 }
+template <bool HM>
 __device__ __forceinline__ size_t out_col_offset(const GemmArgs& a, int n) {
-  if (a.y_dh == 0) return (size_t)n;
+  if (!HM || a.y_dh == 0) return (size_t)n;
   const int head = n / a.y_dh;
   return (size_t)head * a.y_T * a.y_dh + (n - head * a.y_dh);
 }
@@ -63,7 +72,7 @@ __device__ __forceinline__ float silu_f32(float u) { return u / (1.0f + expf(-u)
 
 template <int EPI, typename T>
 __device__ __forceinline__ void epilogue_store(const GemmArgs& a, int m, int k, int n, float acc) {
-  const size_t o = out_row_offset(a, m, k) + out_col_offset(a, n);
+  const size_t o = out_row_offset<kHeadMajor<EPI>>(a, m, k) + out_col_offset<kHeadMajor<EPI>>(a, n);
   if (EPI == EPI_LOGITS) {
     ((float*)a.out)[o] = acc;
   } else if (EPI == EPI_RESID) {

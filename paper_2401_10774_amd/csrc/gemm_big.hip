@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
 #pragma unroll
   for (int it = 0; it < LPT; ++it) {
     const int row = it * 32 + (tid >> 3), c = tid & 7;
-    goff[it] = it < MT ? (uint32_t)((x_row_offset(a, min(m0 + row, a.M - 1), k) + c * 8) * 2)
+    goff[it] = it < MT ? (uint32_t)((x_row_offset<kHeadMajor<EPI>>(a, min(m0 + row, a.M - 1), k) + c * 8) * 2)
                        : (uint32_t)(((size_t)min(n0 + row - BM, a.N - 1) * a.d + c * 8) * 2);
   }
   const int nk = a.d >> 6;
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
   auto gload = [&](int step, u32x4_t (&g)[LPT]) __attribute__((always_inline)) {
     const int j0 = min(step, nk - 1) * 64;                       // past the end: harmless reload
     const uint32_t so_w = (uint32_t)j0 * 2u;
-    const uint32_t so_x = (uint32_t)x_col_offset(a, j0) * 2u;    // differs from so_w for head-major activations
+    const uint32_t so_x = (uint32_t)x_col_offset<kHeadMajor<EPI>>(a, j0) * 2u;    // differs from so_w for head-major activations
 #pragma unroll
     for (int it = 0; it < LPT; ++it) g[it] = *(const u32x4_t*)((it < MT ? Xb : Wb) + (goff[it] + (it < MT ? so_x : so_w)));
   };
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
 #pragma unroll
       for (int r = 0; r < 4; ++r) ep[(4 * q4 + r) * EP_PITCH + j * 16 + i16] = acc[t][j][r];
     const int m = m0 + (wm * MT + t) * 16 + er;
-    const size_t row_off = m < a.M ? out_row_offset(a, m, k) : 0;
+    const size_t row_off = m < a.M ? out_row_offset<kHeadMajor<EPI>>(a, m, k) : 0;
 #pragma unroll
     for (int c = 0; c < NT / 2; ++c) {
       const floatx4_t v0 = *(const floatx4_t*)(ep + er * EP_PITCH + c * 32 + ec);
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
       const int n = n0 + wn * 16 * NT + c * 32 + ec;
       if (m >= a.M || n >= a.N) continue;
       if (vec && n + 8 <= a.N) {
-        const size_t o = row_off + out_col_offset(a, n);
+        const size_t o = row_off + out_col_offset<kHeadMajor<EPI>>(a, n);
         if (EPI == EPI_LOGITS) {
           float* dst = (float*)a.out + o;
           *(floatx4_t*)dst = v0;
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
         // ragged or unaligned output: one element at a time
         for (int e = 0; e < 8; ++e) {
           if (n + e >= a.N) break;
-          const size_t o = row_off + out_col_offset(a, n + e);
+          const size_t o = row_off + out_col_offset<kHeadMajor<EPI>>(a, n + e);
           if (EPI == EPI_LOGITS) {
             ((float*)a.out)[o] = v[e];
           } else if (EPI == EPI_PLAIN) {

@@ -32,7 +32,7 @@ __global__ __launch_bounds__(256) void gemv_bf16_kernel(GemmArgs a) {
   for (int i = threadIdx.x; i < MB * chunks; i += 256) {
     const int mm = i / chunks, c = i - mm * chunks;
     u32x4_t v = {0, 0, 0, 0};
-    if (m0 + mm < a.M) v = *(const u32x4_t*)(X + x_row_offset(a, m0 + mm, k) + x_col_offset(a, c * 8));
+    if (m0 + mm < a.M) v = *(const u32x4_t*)(X + x_row_offset<kHeadMajor<EPI>>(a, m0 + mm, k) + x_col_offset<kHeadMajor<EPI>>(a, c * 8));
     xs[i] = v;
   }
   __syncthreads();
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(GemmArgs a) {
   for (int i = threadIdx.x; i < MB * chunks; i += 256) {
     const int mm = i / chunks, c = i - mm * chunks;
     floatx4_t v = {0.f, 0.f, 0.f, 0.f};
-    if (m0 + mm < a.M) v = *(const floatx4_t*)(X + x_row_offset(a, m0 + mm, k) + x_col_offset(a, c * 4));
+    if (m0 + mm < a.M) v = *(const floatx4_t*)(X + x_row_offset<kHeadMajor<EPI>>(a, m0 + mm, k) + x_col_offset<kHeadMajor<EPI>>(a, c * 4));
     xs[i] = v;
   }
   __syncthreads();
@@ -143,16 +143,15 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(GemmArgs a) {
 // Output layout of the MFMA: lane l holds column l%16 (weight row), rows 4*(l/16)..+3
 // (activation rows).  grid (ceil(N/BN), K, ceil(M/BM)), 256 threads.
 //
-// Split reduction (WM == 1 only, where one workgroup spans all activation rows and grid.z is
-// free): when N is so small that N/BN workgroups would leave most of the chip idle (the d x d
-// and d x 4d/3 projections of a decoder block), grid.z = ksplit workgroups share an output tile,
-// each reducing a contiguous 1/ksplit of d.  They park their fp32 partial tiles in a workspace;
+// Split reduction: when the output has so few tiles that most of the chip would idle (the d x d
+// and d x 4d/3 projections of a decoder block), ksplit workgroups share an output tile, each
+// reducing a contiguous 1/ksplit of d (grid.z = m-tiles x ksplit).  They park their fp32 partial tiles in a workspace;
 // the workgroup that arrives last adds them up in split order (so the result does not depend on
 // which one that is) and runs the epilogue.
 // ---------------------------------------------------------------------------------------
 __device__ unsigned int g_gemm_ticket[kMaxSplitTiles];
 
-template <int WM, int WN, int MT, int NT, int BK, int PD, int EPI>
+template <int WM, int WN, int MT, int NT, int BK, int PD, int EPI, bool SPLIT = false>
 __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
   constexpr int BM = WM * 16 * MT, BN = WN * 16 * NT;
   constexpr int CPR = BK / 8;                         // 16-byte chunks per row and reduction step
@@ -167,8 +166,10 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
   const int i16 = lane & 15, q4 = lane >> 4;
   const int wm = wave / WN, wn = wave - wm * WN;
   const int k = blockIdx.y;
-  const int n_split = WM == 1 ? a.ksplit : 1, split = WM == 1 ? blockIdx.z : 0;
-  const int n0 = blockIdx.x * BN, m0 = WM == 1 ? 0 : blockIdx.z * BM;
+  // (the split reduction is a template switch: its merge code would otherwise cost every
+  // instantiation registers, and with them occupancy)
+  const int n_split = SPLIT ? a.ksplit : 1, m_tile = blockIdx.z / n_split, split = blockIdx.z - m_tile * n_split;
+  const int n0 = blockIdx.x * BN, m0 = m_tile * BM;
   const uint16_t* W = (const uint16_t*)a.W + (size_t)k * a.N * a.d;
   const uint16_t* X = (const uint16_t*)a.X;
 
@@ -182,7 +183,7 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
     const int id = min(it * 256 + tid, CHUNKS - 1);
     const int row = id / CPR, c = id - row * CPR;
     is_x[it] = row < BM;
-    src[it] = row < BM ? X + x_row_offset(a, min(m0 + row, a.M - 1), k) + c * 8
+    src[it] = row < BM ? X + x_row_offset<kHeadMajor<EPI>>(a, min(m0 + row, a.M - 1), k) + c * 8
                        : W + (size_t)min(n0 + row - BM, a.N - 1) * a.d + c * 8;
     dst[it] = row * PITCH + ((c ^ ((row >> 1) & 7)) << 4);
   }
@@ -199,7 +200,7 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
   u32x4_t regs[PD][LPT];
   auto gload = [&](int step, u32x4_t (&r)[LPT]) {
     const int off_w = (step0 + min(step, nk - 1)) * BK;
-    const int off_x = (int)x_col_offset(a, off_w);       // differs from off_w for head-major activations
+    const int off_x = (int)x_col_offset<kHeadMajor<EPI>>(a, off_w);       // differs from off_w for head-major activations
 #pragma unroll
     for (int it = 0; it < LPT; ++it) r[it] = *(const u32x4_t*)(src[it] + (is_x[it] ? off_x : off_w));
   };
@@ -256,9 +257,9 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
     }
   }
 
-  if (WM == 1 && n_split > 1) {
+  if (SPLIT && n_split > 1) {
     // partial tile of this split: [fragment][register pair][thread], 8 bytes per thread and store
-    const unsigned int tile = k * gridDim.x + blockIdx.x;
+    const unsigned int tile = (k * gridDim.x + blockIdx.x) * (gridDim.z / n_split) + m_tile;
     constexpr int PART = MT * NT * 2 * 256;              // 8-byte words per partial tile
     uint64_t* part = (uint64_t*)a.ws + (size_t)tile * n_split * PART;
 #pragma unroll
@@ -274,7 +275,7 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
     // Sum in split order.  The loads of a group of slots are all issued before the first sum (each is a
     // round trip to the memory side of the L2, where the other workgroups' stores are visible); splits
     // past the last one re-read the last one and are not added.
-    constexpr int SLOTS = MT * NT * 2, GROUP = 4, MAXS = 8;
+    constexpr int SLOTS = MT * NT * 2, GROUP = SLOTS >= 32 ? 8 : 4, MAXS = 8;
 #pragma unroll
     for (int s0 = 0; s0 < SLOTS; s0 += GROUP) {
       uint64_t v[GROUP][MAXS];
@@ -316,31 +317,60 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
     }
 }
 
-// Tile width and number of reduction splits of the skinny kernel: 128-row tiles when they alone
-// give a few hundred workgroups, else 64-row tiles, with the reduction split when even those are
-// too few.  (Measured at M = 65, N = d = 4096: 64-row tiles x 8 splits 21 us, 128-row tiles x 8
-// splits 27 us, unsplit 37 us: the number of workgroups matters more than the activation re-reads.)
-struct SkinnyPlan {
+// Which kernel a bf16 GEMM of M rows goes to, and in what shape.
+//   M <= 4                         wave-per-row GEMV.
+//   about one 192/128 x 256 tile per CU or more (M > 80)   the large-tile kernel (gemm_big.hip).
+//   otherwise                      the LDS-staged kernel in its skinny arrangement: row blocks of
+//     16*mt <= 128 activation rows (every wavefront sees all rows of its block), 128 weight rows
+//     per workgroup when that alone gives a few hundred workgroups, else 64, and the reduction
+//     split over up to 8 workgroups when even those are too few.  (Measured at M = 65,
+//     N = d = 4096: 64-row tiles x 8 splits 21 us, 128-row tiles x 8 splits 27 us, unsplit 37 us:
+//     the number of workgroups matters more than the activation re-reads.)
+//   M > 80 and at least 200 tiles of 128 x 128: those tiles, wavefronts 2 x 2, unsplit (at M = 356
+//     and 1040 the skinny arrangement was up to 1.5x faster below that tile count and up to 1.6x
+//     slower above it; splitting the 128 x 128 kernel's reduction never paid for its 64 KB partials).
+struct GemmPlan {
+  enum { GEMV, SKINNY, SQUARE, BIG } kind;
   bool wide;
-  int ksplit;
+  int mt, m_blocks, ksplit;
 };
-SkinnyPlan skinny_plan(int M, int N, int d, int K, bool have_ws) {
-  SkinnyPlan p;
-  p.wide = (long)ceil_div(N, 128) * K >= 200;               // measured at V = 32000: 52 us wide, 63 us narrow
-  p.ksplit = 1;
-  if (p.wide || !have_ws || M <= 4 || M > 80) return p;
-  const long tiles = (long)ceil_div(N, 64) * K;
-  if (tiles >= 192 || tiles > kMaxSplitTiles) return p;
+GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) {
+  GemmPlan p = {GemmPlan::GEMV, false, 1, 1, 1};
+  if (M <= 4) return p;
+  if (M > 80 && !wide_offsets) {                            // (the large-tile kernel addresses with 32-bit element offsets)
+    const bool tall = ceil_div(M, 192) * 192 <= ceil_div(M, 128) * 128;
+    if ((long)ceil_div(M, tall ? 192 : 128) * ceil_div(N, 256) * K >= 200) {
+      p.kind = GemmPlan::BIG;
+      return p;
+    }
+  }
+  p.m_blocks = ceil_div(M, 128);
+  if (M > 80 && (long)ceil_div(N, 128) * p.m_blocks * K >= 200) {
+    // enough 128 x 128 tiles to fill the chip: wavefronts 2 x 2 (half the LDS reads per MFMA of the
+    // skinny arrangement), never split
+    p.kind = GemmPlan::SQUARE;
+    p.wide = true;
+    p.mt = 4;
+    return p;
+  }
+  p.kind = GemmPlan::SKINNY;
+  p.mt = ceil_div(ceil_div(M, p.m_blocks), 16);
+  p.wide = (long)ceil_div(N, 128) * K * p.m_blocks >= 200;  // measured at V = 32000, M = 65: 52 us wide, 63 us narrow
+  if (!have_ws) return p;
+  const long tiles = (long)ceil_div(N, p.wide ? 128 : 64) * K * p.m_blocks;
+  if (tiles >= 384 || tiles > kMaxSplitTiles) return p;
   long s = 512 / tiles;
   const long by_steps = (d / 64) / 8;                       // at least 8 reduction steps per split
   s = s < by_steps ? s : by_steps;
   p.ksplit = (int)(s < 1 ? 1 : (s > 8 ? 8 : s));
   return p;
 }
-size_t skinny_ws_bytes(int M, int N, int d, int K) {
-  const SkinnyPlan p = skinny_plan(M, N, d, K, true);
-  if (p.ksplit <= 1) return 0;
-  return (size_t)ceil_div(N, p.wide ? 128 : 64) * K * p.ksplit * ceil_div(M, 16) * (p.wide ? 2 : 1) * 4 * 256 * sizeof(float);
+// Workspace for the fp32 partial tiles of a split reduction (0 if this shape is not split).
+size_t gemm_ws_bytes(int M, int N, int d, int K) {
+  const GemmPlan p = plan_gemm(M, N, d, K, true, false);
+  if (p.kind != GemmPlan::SKINNY || p.ksplit <= 1) return 0;
+  const int frags = p.mt * (p.wide ? 2 : 1);                // accumulator fragments per thread
+  return (size_t)ceil_div(N, p.wide ? 128 : 64) * K * p.m_blocks * p.ksplit * frags * 4 * 256 * sizeof(float);
 }
 
 // Optional event pair recorded around the vocabulary-projection launch (benchmark hook).
@@ -375,36 +405,37 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
     if (MB == 1) hipLaunchKernelGGL((gemv_bf16_kernel<1, EPI>), grid, block, lds, stream, a);
     else if (MB == 2) hipLaunchKernelGGL((gemv_bf16_kernel<2, EPI>), grid, block, lds, stream, a);
     else hipLaunchKernelGGL((gemv_bf16_kernel<4, EPI>), grid, block, lds, stream, a);
-  } else if (a.M <= 80) {
-    // skinny: every wavefront sees all activation rows; 128 or 64 weight rows per workgroup, the
-    // reduction split over several workgroups when the output is narrow (skinny_plan)
-    const int MT = ceil_div(a.M, 16);
-    const SkinnyPlan plan = skinny_plan(a.M, a.N, a.d, a.K, a.ws != nullptr);
+  } else {
+    const bool wide_offsets = (size_t)a.N * a.d >= ((size_t)1 << 31) || x_extent(a) >= ((size_t)1 << 31);
+    const GemmPlan plan = plan_gemm(a.M, a.N, a.d, a.K, a.ws != nullptr, wide_offsets);
+    if (plan.kind == GemmPlan::BIG) return launch_gemm_big(a, EPI, stream);
     const bool wide = plan.wide;
     a.ksplit = plan.ksplit;
-    const dim3 grid(ceil_div(a.N, wide ? 128 : 64), a.K, a.ksplit);
-#define MEDUSA_SKINNY(MT_)                                                                                         \
-  case MT_:                                                                                                        \
-    if (!wide) hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 1, 64, 4, EPI>), grid, block, 0, stream, a);    \
-    else hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 2, 64, 4, EPI>), grid, block, 0, stream, a);          \
+    // split reductions exist for the epilogues tree_linear uses (medusa_heads passes no workspace)
+    constexpr bool kCanSplit = EPI == EPI_PLAIN || EPI == EPI_GATED;
+    const bool split = kCanSplit && a.ksplit > 1;
+    if (!split) a.ksplit = 1;
+    const dim3 grid(ceil_div(a.N, wide ? 128 : 64), a.K, plan.m_blocks * a.ksplit);
+    if (plan.kind == GemmPlan::SQUARE) {
+      hipLaunchKernelGGL((gemm_lds_bf16_kernel<2, 2, 4, 4, 64, 2, EPI, false>), grid, block, 0, stream, a);
+      MEDUSA_LAUNCH_CHECK();
+      return MEDUSA_OK;
+    }
+#define MEDUSA_SKINNY(MT_)                                                                                                     \
+  case MT_:                                                                                                                    \
+    if (split) {                                                                                                               \
+      if (!wide) hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 1, 64, 4, EPI, kCanSplit>), grid, block, 0, stream, a);   \
+      else hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 2, 64, 4, EPI, kCanSplit>), grid, block, 0, stream, a);         \
+    } else {                                                                                                                   \
+      if (!wide) hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 1, 64, 4, EPI, false>), grid, block, 0, stream, a);       \
+      else hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 2, 64, 4, EPI, false>), grid, block, 0, stream, a);             \
+    }                                                                                                                          \
     break;
-    switch (MT) {
-      MEDUSA_SKINNY(1) MEDUSA_SKINNY(2) MEDUSA_SKINNY(3) MEDUSA_SKINNY(4) MEDUSA_SKINNY(5)
+    switch (plan.mt) {
+      MEDUSA_SKINNY(1) MEDUSA_SKINNY(2) MEDUSA_SKINNY(3) MEDUSA_SKINNY(4) MEDUSA_SKINNY(5) MEDUSA_SKINNY(6)
+      MEDUSA_SKINNY(7) MEDUSA_SKINNY(8)
     }
 #undef MEDUSA_SKINNY
-  } else {
-    // The large tile pays off only when there is about one tile per CU or more; below that (the
-    // d x d and 4d/3 x d projections at a few hundred rows) the 128 x 128 kernel's three to four
-    // times as many workgroups win (measured 10-30 % at M = 356 and 1040).
-    const bool tall = ceil_div(a.M, 192) * 192 <= ceil_div(a.M, 128) * 128;
-    const long big_tiles = (long)ceil_div(a.M, tall ? 192 : 128) * ceil_div(a.N, 256) * a.K;
-    const bool wide_offsets = (size_t)a.N * a.d >= ((size_t)1 << 31) || x_extent(a) >= ((size_t)1 << 31);
-    if (big_tiles < 200 || wide_offsets) {     // (the large-tile kernel addresses with 32-bit element offsets)
-      const dim3 grid(ceil_div(a.N, 128), a.K, ceil_div(a.M, 128));
-      hipLaunchKernelGGL((gemm_lds_bf16_kernel<2, 2, 4, 4, 64, 2, EPI>), grid, block, 0, stream, a);
-    } else {
-      return launch_gemm_big(a, EPI, stream);
-    }
   }
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;
@@ -456,7 +487,7 @@ extern "C" int medusa_heads(const void* hidden, const void* w1, const void* w2, 
 // Backbone linear layer on the tree tokens (App. G, operator table, parallel-decoding rows).
 extern "C" size_t tree_linear_workspace_bytes(int B, int T, int d_in, int d_out, medusa_dtype_t dtype) {
   if (dtype != MEDUSA_BF16 || B < 1 || T < 1 || d_in < 64 || d_out < 1) return 0;
-  return skinny_ws_bytes(B * T, d_out, d_in, 1);
+  return gemm_ws_bytes(B * T, d_out, d_in, 1);
 }
 
 extern "C" int tree_linear(const void* x, const void* w, const void* mul, void* y, int B, int T, int d_in, int d_out,
@@ -493,7 +524,7 @@ extern "C" int tree_linear(const void* x, const void* w, const void* mul, void* 
     a.y_dh = d_out / y_heads;
   }
   // the split reduction is an optimisation: without (enough) workspace the call runs unsplit
-  if (workspace && dtype == MEDUSA_BF16 && workspace_bytes >= skinny_ws_bytes(a.M, a.N, a.d, 1) && skinny_ws_bytes(a.M, a.N, a.d, 1) > 0)
+  if (workspace && dtype == MEDUSA_BF16 && workspace_bytes >= gemm_ws_bytes(a.M, a.N, a.d, 1) && gemm_ws_bytes(a.M, a.N, a.d, 1) > 0)
     a.ws = workspace;
   hipStream_t stream = (hipStream_t)stream_;
   return mul ? launch_gemm<EPI_GATED>(a, dtype, stream) : launch_gemm<EPI_PLAIN>(a, dtype, stream);
