@@ -144,6 +144,27 @@ template <typename T>
 __device__ __forceinline__ void store_agent(T* p, T v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// All-reduce over the four 16-lane rows of a wavefront (lanes l%16 + {0, 16, 32, 48}) with the
+// row-swap instructions of gfx950: v_permlane16_swap exchanges the odd rows of its first operand with
+// the even rows of its second, v_permlane32_swap the upper half of the first with the lower half of
+// the second, so op(first, second) after a swap of (x, x) combines x with its partner row / half in
+// every lane.  Two vector-ALU instructions per step instead of an LDS round trip (ds_bpermute).
+typedef unsigned int u32pair_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float rows_max(float x) {
+  const unsigned int u = __float_as_uint(x);
+  const u32pair_t a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const unsigned int v = __float_as_uint(fmaxf(__uint_as_float(a.x), __uint_as_float(a.y)));
+  const u32pair_t b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return fmaxf(__uint_as_float(b.x), __uint_as_float(b.y));
+}
+__device__ __forceinline__ float rows_sum(float x) {
+  const unsigned int u = __float_as_uint(x);
+  const u32pair_t a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const unsigned int v = __float_as_uint(__uint_as_float(a.x) + __uint_as_float(a.y));
+  const u32pair_t b = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return __uint_as_float(b.x) + __uint_as_float(b.y);
+}
+
 __device__ __forceinline__ bool last_workgroup_of(unsigned int* counter, unsigned int total) {
   __shared__ unsigned int s_ticket;
   __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wavefront's loads and stores are complete

@@ -9,7 +9,7 @@
 //   * Keys are numbered prefix first, tree after (key L+u is tree node u), and processed in
 //     64-key blocks; a split owns a contiguous run of blocks, computed from prefix_len[b] on
 //     the device.  K and V tiles are fetched with full-line 16-byte loads one block ahead of
-//     their use (registers), then parked in padded LDS tiles; K of block i+1 and V of block i
+//     their use (registers), then parked in swizzled LDS tiles; K of block i+1 and V of block i
 //     are written between the two barriers of block i, so single tiles suffice and two
 //     workgroups fit on a CU to cover each other's latencies.
 //   * Scores are formed transposed, S^T = K Q^T: wavefront w owns keys 16w..16w+15 of the block
@@ -151,9 +151,18 @@ template <int D, int MT>
 __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
   constexpr int KS = D / 32;                    // reduction steps of K Q^T
   constexpr int DPW = D / 64;                   // 16-wide output tiles of the head dimension per wavefront
-  constexpr int PITCH = D * 2 + 16;             // LDS row pitch of the K and V tiles (bytes)
+  // LDS tiles are unpadded; the 16-byte chunk c of row r is stored at chunk slot c ^ swz(r), chosen
+  // per tile so that its reads are bank-conflict free (a 64-lane 16-byte read is served in four
+  // groups of 16 lanes that are not consecutive lanes, an 8-byte read in groups of 16 consecutive
+  // lanes; padded pitches leave both kinds of read two-way conflicted):
+  //   K, read as MFMA operands (16 rows x 4 chunks per instruction): swz = r & 15 (256-byte rows) or
+  //     (r >> 1) & 7 (128-byte rows);
+  //   V, read 8 bytes per lane transposed (4 rows x 32 bytes per 16 lanes): swz = 2 (r & 7), resp.
+  //     2 ((r >> 1) & 3);
+  //   P (128-byte rows, MFMA-operand reads, 8-byte writes): swz = (r >> 1) & 7.
+  constexpr int PITCH = D * 2;                  // bytes per row of the K and V tiles
   constexpr int TENSOR_BYTES = kBlkKeys * PITCH;
-  constexpr int PPITCH = kBlkKeys * 2 + 16;     // LDS row pitch of the probability tile (bytes)
+  constexpr int PPITCH = kBlkKeys * 2;          // bytes per row of the probability tile
   constexpr int CPR = D / 8;                    // 16-byte chunks per K/V row
   constexpr int LPT = kBlkKeys * CPR / 256;     // chunks per thread per block and tensor
   __shared__ __attribute__((aligned(16))) unsigned char s_k[TENSOR_BYTES];
@@ -198,14 +207,17 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
   }
 
   // This thread's chunks of a K (or V) block: row in the block, element offset, LDS offset.
-  int ch_row[LPT], ch_off[LPT], ch_dst[LPT];
+  auto swz_k = [](int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); };
+  auto swz_v = [](int r) { return D == 128 ? 2 * (r & 7) : 2 * ((r >> 1) & 3); };
+  int ch_row[LPT], ch_off[LPT], ch_dst_k[LPT], ch_dst_v[LPT];
 #pragma unroll
   for (int it = 0; it < LPT; ++it) {
     const int id = it * 256 + tid;
     ch_row[it] = id / CPR;
-    const int col = (id - ch_row[it] * CPR) * 8;
-    ch_off[it] = ch_row[it] * D + col;
-    ch_dst[it] = ch_row[it] * PITCH + col * 2;
+    const int chunk = id - ch_row[it] * CPR;
+    ch_off[it] = ch_row[it] * D + chunk * 8;
+    ch_dst_k[it] = ch_row[it] * PITCH + ((chunk ^ swz_k(ch_row[it])) << 4);
+    ch_dst_v[it] = ch_row[it] * PITCH + ((chunk ^ swz_v(ch_row[it])) << 4);
   }
   // One tensor's rows of block `iter` of this split (index clamped into the split's range;
   // the redundant reloads past the end are never used).
@@ -225,9 +237,9 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
       }
     }
   };
-  auto lstore = [&](unsigned char* tile, const u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
+  auto lstore = [&](unsigned char* tile, const int (&dst)[LPT], const u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int it = 0; it < LPT; ++it) *(u32x4_t*)(tile + ch_dst[it]) = r[it];
+    for (int it = 0; it < LPT; ++it) *(u32x4_t*)(tile + dst[it]) = r[it];
   };
 
   floatx4_t o[MT][DPW];
@@ -240,17 +252,20 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
     for (int dd = 0; dd < DPW; ++dd) o[mt][dd] = floatx4_t{0.f, 0.f, 0.f, 0.f};
   }
   const float sc = a.scale * 1.4426950408889634f;        // scores are kept in log2 units
-  const int kf_off = (16 * wave + i16) * PITCH + q4 * 16;
-  const int p_wr_off = i16 * PPITCH + (16 * wave + 4 * q4) * 2;
-  const int p_rd_off = i16 * PPITCH + 8 * q4 * 2;
+  const int kswz = swz_k(i16);                           // (a wavefront's 16-key tile starts at a multiple of 16)
+  const int kf_off = (16 * wave + i16) * PITCH;
+  const int pswz = (i16 >> 1) & 7;
+  const int p_wr_off = i16 * PPITCH + (((2 * wave + (q4 >> 1)) ^ pswz) << 4) + 8 * (q4 & 1);
+  const int p_rd_off = i16 * PPITCH;
   // transposed V read: lane r of a 16-lane group addresses V[8*q4 + r/4 (+4)][16*dd' + 4*(r%4) .. +3]
-  const int v_rd_off = (8 * q4 + (i16 >> 2)) * PITCH + (16 * (wave * DPW) + 4 * (i16 & 3)) * 2;
+  const int v_row = 8 * q4 + (i16 >> 2);
+  const int v_chunk0 = 2 * (wave * DPW) + ((i16 & 3) >> 1), v_half = 8 * (i16 & 1);
 
   u32x4_t kreg[LPT], vreg[LPT];
   if (n_iter > 0) {
     gload(0, kc, kt, kreg);
     gload(0, vc, vt, vreg);
-    lstore(s_k, kreg);
+    lstore(s_k, ch_dst_k, kreg);
     gload(1, kc, kt, kreg);
   }
   __syncthreads();
@@ -261,7 +276,7 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
     // ---- S^T for this wavefront's 16 keys, all query tiles ----
     bf16x8_t kf[KS];
 #pragma unroll
-    for (int c = 0; c < KS; ++c) kf[c] = *(const bf16x8_t*)(s_k + kf_off + c * 64);
+    for (int c = 0; c < KS; ++c) kf[c] = *(const bf16x8_t*)(s_k + kf_off + (((4 * c + q4) ^ kswz) << 4));
     floatx4_t sv[MT];
     const bool all_visible = key0 + kBlkKeys <= L;
     const int sh = L - key0;                              // position of tree node 0 inside the block
@@ -285,8 +300,7 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
       }
       sv[mt] = s;
       float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-      mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+      mx = rows_max(mx);
       if (q4 == 0) s_max[16 * mt + i16][wave] = mx;
     }
     __syncthreads();        // A: block maxima are visible; every wavefront has left block i-1 and the K tile
@@ -317,8 +331,8 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
     // tiles: K of the next block (the K tile is free since barrier A), V of this block (the V tile
     // was last read in block i-1, which every wavefront left before barrier A); then start the
     // loads that will be parked one block from now
-    lstore(s_k, kreg);
-    lstore(s_v, vreg);
+    lstore(s_k, ch_dst_k, kreg);
+    lstore(s_v, ch_dst_v, vreg);
     gload(i + 2, kc, kt, kreg);
     gload(i + 1, vc, vt, vreg);
     __syncthreads();        // B: probabilities, the V tile and the next K tile are visible
@@ -327,11 +341,13 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
     for (int ks = 0; ks < kBlkKeys / 32; ++ks) {
       bf16x8_t pf[MT];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) pf[mt] = *(const bf16x8_t*)(s_p + 16 * mt * PPITCH + p_rd_off + 32 * ks * 2);
+      for (int mt = 0; mt < MT; ++mt)
+        pf[mt] = *(const bf16x8_t*)(s_p + 16 * mt * PPITCH + p_rd_off + (((4 * ks + q4) ^ pswz) << 4));
 #pragma unroll
       for (int dd = 0; dd < DPW; ++dd) {
-        const unsigned char* vp = s_v + v_rd_off + 32 * ks * PITCH + 16 * dd * 2;
-        const short4_t v0 = lds_read_tr16(vp), v1 = lds_read_tr16(vp + 4 * PITCH);
+        const int r0 = 32 * ks + v_row, r1 = r0 + 4;
+        const short4_t v0 = lds_read_tr16(s_v + r0 * PITCH + (((v_chunk0 + 2 * dd) ^ swz_v(r0)) << 4) + v_half);
+        const short4_t v1 = lds_read_tr16(s_v + r1 * PITCH + (((v_chunk0 + 2 * dd) ^ swz_v(r1)) << 4) + v_half);
         typedef short short8_t __attribute__((ext_vector_type(8)));
         const short8_t v8 = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
         const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, v8);
@@ -345,8 +361,7 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     float l = l_run[mt];
-    l += __shfl_xor(l, 16, kWave);
-    l += __shfl_xor(l, 32, kWave);
+    l = rows_sum(l);
     if (q4 == 0) s_sum[wave][16 * mt + i16] = l;
   }
   __syncthreads();
