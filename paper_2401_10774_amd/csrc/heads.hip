@@ -28,7 +28,38 @@ __global__ __launch_bounds__(256) void gemv_bf16_kernel(GemmArgs a) {
   u32x4_t* xs = (u32x4_t*)smem;                 // [MB][d/8] 16-byte chunks
   const int chunks = a.d >> 3;
   const int k = blockIdx.y, m0 = blockIdx.z * MB;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint16_t* X = (const uint16_t*)a.X;
+  const uint16_t* W = (const uint16_t*)a.W + (size_t)k * a.N * a.d;
+  const int n_begin = blockIdx.x * a.rows_per_wg;
+  const int n_end = min(n_begin + a.rows_per_wg, a.N);
+  constexpr int R = 2, U = 4;
+
+  // Work of a wavefront: row pairs nb = n_begin + 2 wave, + 8, ...; each row pair in batches of
+  // U x 64 chunks.  The batches are software-pipelined: batch i+1 is requested before batch i is
+  // multiplied, and the first batch before the activations are staged in LDS, so the weight stream
+  // starts with the first instruction of the kernel.
+  const int cpb = 64 * U;                       // chunks per batch and row
+  const int bpr = (chunks + cpb - 1) / cpb;     // batches per row pair
+  const int first_nb = n_begin + wave * R;
+  const int n_pairs = first_nb < n_end ? (n_end - first_nb + 4 * R - 1) / (4 * R) : 0;
+  const int n_batches = n_pairs * bpr;
+  auto load_batch = [&](int bi, u32x4_t (&w)[R][U]) __attribute__((always_inline)) {
+    const int pair = bi / bpr, c0 = (bi - pair * bpr) * cpb;
+    const int nb = first_nb + pair * 4 * R;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const u32x4_t* wrow = (const u32x4_t*)(W + (size_t)min(nb + r, a.N - 1) * a.d);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int c = c0 + u * 64 + lane;
+        w[r][u] = c < chunks ? __builtin_nontemporal_load(wrow + c) : u32x4_t{0, 0, 0, 0};
+      }
+    }
+  };
+  u32x4_t wa[R][U], wb[R][U];
+  if (n_batches > 0) load_batch(0, wa);
+
   for (int i = threadIdx.x; i < MB * chunks; i += 256) {
     const int mm = i / chunks, c = i - mm * chunks;
     u32x4_t v = {0, 0, 0, 0};
@@ -37,53 +68,49 @@ __global__ __launch_bounds__(256) void gemv_bf16_kernel(GemmArgs a) {
   }
   __syncthreads();
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint16_t* W = (const uint16_t*)a.W + (size_t)k * a.N * a.d;
-  const int n_begin = blockIdx.x * a.rows_per_wg;
-  constexpr int R = 2, U = 4;
-  for (int nb = n_begin + wave * R; nb < n_begin + a.rows_per_wg && nb < a.N; nb += 4 * R) {
-    float acc[R][MB];
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-      for (int mm = 0; mm < MB; ++mm) acc[r][mm] = 0.f;
-    const u32x4_t* wrow[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) wrow[r] = (const u32x4_t*)(W + (size_t)min(nb + r, a.N - 1) * a.d);
-    for (int c0 = 0; c0 < chunks; c0 += 64 * U) {
-      u32x4_t w[R][U];
+  float acc[R][MB];
+  auto multiply = [&](int bi, const u32x4_t (&w)[R][U]) __attribute__((always_inline)) {
+    const int pair = bi / bpr, c0 = (bi - pair * bpr) * cpb;
+    if (c0 == 0) {
 #pragma unroll
       for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const int c = c0 + u * 64 + lane;
-          w[r][u] = c < chunks ? __builtin_nontemporal_load(wrow[r] + c) : u32x4_t{0, 0, 0, 0};
-        }
+        for (int mm = 0; mm < MB; ++mm) acc[r][mm] = 0.f;
+    }
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int c = min(c0 + u * 64 + lane, chunks - 1);
+    for (int u = 0; u < U; ++u) {
+      const int c = min(c0 + u * 64 + lane, chunks - 1);
 #pragma unroll
-        for (int mm = 0; mm < MB; ++mm) {
-          const u32x4_t x = xs[mm * chunks + c];
+      for (int mm = 0; mm < MB; ++mm) {
+        const u32x4_t x = xs[mm * chunks + c];
 #pragma unroll
-          for (int r = 0; r < R; ++r) {
-            float s = acc[r][mm];
-            s = dot2_bf16(w[r][u].x, x.x, s);
-            s = dot2_bf16(w[r][u].y, x.y, s);
-            s = dot2_bf16(w[r][u].z, x.z, s);
-            s = dot2_bf16(w[r][u].w, x.w, s);
-            acc[r][mm] = s;
-          }
+        for (int r = 0; r < R; ++r) {
+          float s = acc[r][mm];
+          s = dot2_bf16(w[r][u].x, x.x, s);
+          s = dot2_bf16(w[r][u].y, x.y, s);
+          s = dot2_bf16(w[r][u].z, x.z, s);
+          s = dot2_bf16(w[r][u].w, x.w, s);
+          acc[r][mm] = s;
         }
       }
     }
+    if (c0 + cpb >= chunks) {                   // last batch of the row pair: reduce and store
+      const int nb = first_nb + pair * 4 * R;
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+      for (int r = 0; r < R; ++r)
 #pragma unroll
-      for (int mm = 0; mm < MB; ++mm) {
-        const float s = wave_sum(acc[r][mm]);
-        if (lane == 0 && nb + r < a.N && m0 + mm < a.M) epilogue_store<EPI, uint16_t>(a, m0 + mm, k, nb + r, s);
-      }
+        for (int mm = 0; mm < MB; ++mm) {
+          const float s = wave_sum(acc[r][mm]);
+          if (lane == 0 && nb + r < a.N && m0 + mm < a.M) epilogue_store<EPI, uint16_t>(a, m0 + mm, k, nb + r, s);
+        }
+    }
+  };
+  for (int bi = 0; bi < n_batches; bi += 2) {
+    if (bi + 1 < n_batches) load_batch(bi + 1, wb);
+    multiply(bi, wa);
+    if (bi + 1 >= n_batches) break;
+    if (bi + 2 < n_batches) load_batch(bi + 2, wa);
+    multiply(bi + 1, wb);
   }
 }
 
