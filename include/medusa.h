@@ -202,12 +202,15 @@ int medusa_accept(const float* logits, const int32_t* tree_tokens, const medusa_
  *   k_cache, v_cache [NL, B, Hkv, Lcap, D] dtype  in/out
  *   k_tree, v_tree   [NL, B, Hkv, T, D]    dtype
  *   path_nodes       [B, path_stride] int32, accept_len [B] int32 (from medusa_accept)
- *   prefix_len       [B] int32 in/out
+ *   prefix_len       [B] int32 in (in/out when prefix_len_out is NULL)
+ *   prefix_len_out   [B] int32 out, or NULL to update prefix_len in place; a caller that keeps
+ *                    the lengths of consecutive steps in two arrays passes the other one here
  * Limits: D * sizeof(dtype) a multiple of 16.
  * -------------------------------------------------------------------------------- */
 int kv_commit(void* k_cache, void* v_cache, const void* k_tree, const void* v_tree,
               const int32_t* path_nodes, int path_stride, const int32_t* accept_len, int32_t* prefix_len,
-              int NL, int B, int Hkv, int T, int D, int Lcap, medusa_dtype_t dtype, medusa_stream_t stream);
+              int32_t* prefix_len_out, int NL, int B, int Hkv, int T, int D, int Lcap, medusa_dtype_t dtype,
+              medusa_stream_t stream);
 
 /* ----------------------------------------------------------------------------------
  * Backbone operators on the tree tokens (App. G: operator table, "Parallel decoding" rows

@@ -67,7 +67,7 @@ def lib() -> ctypes.CDLL:
         L.medusa_accept_workspace_bytes.argtypes = [c_int] * 3
         L.medusa_accept.argtypes = ([c_void_p] * 3 + [c_int] * 3 + [c_float] * 3 + [c_void_p] * 5 +
                                     [c_void_p, c_size_t, c_void_p])
-        L.kv_commit.argtypes = ([c_void_p] * 5 + [c_int, c_void_p, c_void_p] + [c_int] * 6 + [c_int, c_void_p])
+        L.kv_commit.argtypes = ([c_void_p] * 5 + [c_int, c_void_p, c_void_p, c_void_p] + [c_int] * 6 + [c_int, c_void_p])
         L.tree_linear_workspace_bytes.restype = c_size_t
         L.tree_linear_workspace_bytes.argtypes = [c_int] * 5
         L.tree_linear.argtypes = [c_void_p] * 4 + [c_int] * 7 + [c_void_p, c_size_t, c_void_p]
@@ -304,8 +304,10 @@ def medusa_accept(logits: torch.Tensor, tree_tokens: torch.Tensor, tree: MedusaT
 
 
 def kv_commit(k_cache: torch.Tensor, v_cache: torch.Tensor, k_tree: torch.Tensor, v_tree: torch.Tensor,
-              path_nodes: torch.Tensor, accept_len: torch.Tensor, prefix_len: torch.Tensor, stream=None) -> None:
-    """Append the accepted path's K/V rows to every cache layer and advance prefix_len, in place."""
+              path_nodes: torch.Tensor, accept_len: torch.Tensor, prefix_len: torch.Tensor,
+              prefix_len_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Append the accepted path's K/V rows to every cache layer and advance prefix_len (in place, or
+    into prefix_len_out)."""
     NL, B, Hkv, Lcap, D = k_cache.shape
     T = k_tree.shape[3]
     code = _dtype_code(k_cache)
@@ -318,9 +320,12 @@ def kv_commit(k_cache: torch.Tensor, v_cache: torch.Tensor, k_tree: torch.Tensor
         raise MedusaError("path_nodes must be [B, K+1]")
     _dev(accept_len, "accept_len", dtype=torch.int32, shape=(B,))
     _dev(prefix_len, "prefix_len", dtype=torch.int32, shape=(B,))
+    if prefix_len_out is not None:
+        _dev(prefix_len_out, "prefix_len_out", dtype=torch.int32, shape=(B,))
     _check(lib().kv_commit(k_cache.data_ptr(), v_cache.data_ptr(), k_tree.data_ptr(), v_tree.data_ptr(),
                            path_nodes.data_ptr(), int(path_nodes.shape[1]), accept_len.data_ptr(),
-                           prefix_len.data_ptr(), NL, B, Hkv, T, D, Lcap, code, _stream(stream)), "kv_commit")
+                           prefix_len.data_ptr(), None if prefix_len_out is None else prefix_len_out.data_ptr(),
+                           NL, B, Hkv, T, D, Lcap, code, _stream(stream)), "kv_commit")
 
 
 def tree_linear_workspace_bytes(B: int, T: int, d_in: int, d_out: int, dtype: torch.dtype) -> int:

@@ -2,7 +2,7 @@
 // append the accepted path's tree K/V rows to every layer of the cache, then grow prefix_len.
 // Pure index arithmetic and 16-byte copies: bit-exact by construction.  One launch: every
 // workgroup reads the old prefix_len before it takes a ticket, and the workgroup that draws the
-// last ticket advances prefix_len once all others are done with it.
+// last ticket writes the new lengths (in place, or to a second array) once all others are done.
 #include "common.hpp"
 
 namespace {
@@ -17,8 +17,8 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(u32x4_t* __restrict__ k_
                                                         const u32x4_t* __restrict__ k_tree, const u32x4_t* __restrict__ v_tree,
                                                         const int32_t* __restrict__ path_nodes, int path_stride,
                                                         const int32_t* __restrict__ accept_len,
-                                                        int32_t* __restrict__ prefix_len, int B, int Hkv, int T,
-                                                        int Lcap, int vec_per_row) {
+                                                        const int32_t* prefix_len, int32_t* prefix_len_out, int B,
+                                                        int Hkv, int T, int Lcap, int vec_per_row) {
   const int lb = blockIdx.x;                  // l*B + b
   const int b = lb % B;
   const int a = min(max(accept_len[b], 0), path_stride);
@@ -43,15 +43,15 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(u32x4_t* __restrict__ k_
   if (!last_workgroup_of(&g_commit_ticket, gridDim.x)) return;
   for (int bb = threadIdx.x; bb < B; bb += 256) {
     const int aa = min(max(accept_len[bb], 0), path_stride);
-    prefix_len[bb] = min(max(prefix_len[bb], 0) + aa, Lcap);
+    prefix_len_out[bb] = min(max(prefix_len[bb], 0) + aa, Lcap);
   }
 }
 
 }  // namespace
 
 extern "C" int kv_commit(void* k_cache, void* v_cache, const void* k_tree, const void* v_tree, const int32_t* path_nodes,
-                         int path_stride, const int32_t* accept_len, int32_t* prefix_len, int NL, int B, int Hkv, int T,
-                         int D, int Lcap, medusa_dtype_t dtype, medusa_stream_t stream_) {
+                         int path_stride, const int32_t* accept_len, int32_t* prefix_len, int32_t* prefix_len_out, int NL,
+                         int B, int Hkv, int T, int D, int Lcap, medusa_dtype_t dtype, medusa_stream_t stream_) {
   if (!k_cache || !v_cache || !k_tree || !v_tree || !path_nodes || !accept_len || !prefix_len) return MEDUSA_EINVAL;
   if (NL < 1 || B < 1 || Hkv < 1 || T < 1 || D < 1 || Lcap < 1 || path_stride < 1) return MEDUSA_EINVAL;
   if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;
@@ -60,8 +60,8 @@ extern "C" int kv_commit(void* k_cache, void* v_cache, const void* k_tree, const
   if ((size_t)NL * B > 0x7fffffffu) return MEDUSA_EUNSUPPORTED;
   hipStream_t stream = (hipStream_t)stream_;
   hipLaunchKernelGGL(kv_commit_kernel, dim3(NL * B), dim3(256), 0, stream, (u32x4_t*)k_cache, (u32x4_t*)v_cache,
-                     (const u32x4_t*)k_tree, (const u32x4_t*)v_tree, path_nodes, path_stride, accept_len, prefix_len, B,
-                     Hkv, T, Lcap, (int)(row_bytes / 16));
+                     (const u32x4_t*)k_tree, (const u32x4_t*)v_tree, path_nodes, path_stride, accept_len, prefix_len,
+                     prefix_len_out ? prefix_len_out : prefix_len, B, Hkv, T, Lcap, (int)(row_bytes / 16));
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;
 }

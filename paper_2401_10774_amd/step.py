@@ -53,6 +53,7 @@ class VerificationStep:
         self.w_lm3 = dev["w_lm"].view(1, V, self.d)
         self.hidden_rows = dev["hidden_tree"].view(B * T, self.d)
         self.prefix_len0 = dev["prefix_len"].clone()
+        self.next_prefix_len = None
         self._plans = {}
 
     def prepare(self) -> None:
@@ -62,6 +63,14 @@ class VerificationStep:
 
     def reset_prefix(self) -> None:
         self.t["prefix_len"].copy_(self.prefix_len0)
+
+    def commit_out_of_place(self) -> torch.Tensor:
+        """Have kv_commit write the advanced lengths to a second array (returned) and leave prefix_len as
+        it is, so that the same step can be enqueued again and again on the same inputs."""
+        if self.next_prefix_len is None:
+            self.next_prefix_len = torch.empty_like(self.t["prefix_len"])
+            self._plans = {}
+        return self.next_prefix_len
 
     def _calls(self, layer: int):
         """The step's library calls with their arguments marshalled once (pointers into layer `layer`)."""
@@ -93,7 +102,9 @@ class VerificationStep:
                                                 self.temperature, self.eps, self.delta, p(a[0]), p(a[1]), p(a[2]),
                                                 p(a[3]), p(a[4]), p(self.ws_accept), nbytes(self.ws_accept))),
             ("kv_commit", L.kv_commit, (p(t["k_cache"]), p(t["v_cache"]), p(t["k_tree"]), p(t["v_tree"]), p(a[2]),
-                                        int(a[2].shape[1]), p(a[0]), p(t["prefix_len"]), self.NL, B, self.Hkv, T,
+                                        int(a[2].shape[1]), p(a[0]), p(t["prefix_len"]),
+                                        None if self.next_prefix_len is None else p(self.next_prefix_len),
+                                        self.NL, B, self.Hkv, T,
                                         self.D, self.Lcap, code)),
         ]
         self._plans[layer] = (pre, post)

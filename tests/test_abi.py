@@ -96,8 +96,8 @@ def test_argument_checks_happen_on_the_host():
     assert L.tree_attention(None, p, p, p, p, p, t.handle, p, 1, 4, 4, 128, 64, 1.0, 1, p, 1 << 30, None) == -1
     assert L.medusa_accept(p, p, t.handle, 1, 100, 5, 1.0, 0.1, 0.1, p, p, p, p, p, p, 1 << 20, None) == -1
     assert L.medusa_accept(p, p, t.handle, 1, 100, 1, 0.0, 0.1, 0.1, p, p, p, p, p, p, 1 << 20, None) == -1
-    assert L.kv_commit(p, p, p, p, p, 3, p, p, 1, 1, 1, 7, 4, 16, 1, None) == -2  # 8-byte rows
-    assert L.kv_commit(p, p, p, None, p, 3, p, p, 1, 1, 1, 7, 64, 16, 1, None) == -1
+    assert L.kv_commit(p, p, p, p, p, 3, p, p, None, 1, 1, 1, 7, 4, 16, 1, None) == -2  # 8-byte rows
+    assert L.kv_commit(p, p, p, None, p, 3, p, p, None, 1, 1, 1, 7, 64, 16, 1, None) == -1
     assert L.medusa_topk_tree(p, None, t.handle, p, 1, 100, 2, p, p, p, p, 1 << 20, None) == -1
     assert L.medusa_topk_tree(p, p, t.handle, p, 1, 100, 1, p, p, p, p, 1 << 20, None) == -1   # fewer heads than levels
     assert L.tree_attention_workspace_bytes(1, 32, 32, 65, 128, 1152) % 256 == 0

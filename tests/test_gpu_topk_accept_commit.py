@@ -174,6 +174,31 @@ def test_kv_commit_bitwise(dtype, NL, B, Hkv, T, D, Lcap):
     assert np.array_equal(d_pl.cpu().numpy(), pl)
 
 
+def test_kv_commit_lengths_to_a_second_array():
+    """Out-of-place form: the cache rows are the same, prefix_len is left alone, the new lengths land
+    in prefix_len_out; a second call on the same inputs writes the same rows again."""
+    NL, B, Hkv, T, D, Lcap, Kp1 = 2, 3, 4, 20, 64, 90, 5
+    rng = np.random.default_rng(96)
+    kc = draw_normal(96, 8, (NL, B, Hkv, Lcap, D), 1.0, "bf16")
+    vc = draw_normal(96, 9, (NL, B, Hkv, Lcap, D), 1.0, "bf16")
+    kt = draw_normal(96, 6, (NL, B, Hkv, T, D), 1.0, "bf16")
+    vt = draw_normal(96, 7, (NL, B, Hkv, T, D), 1.0, "bf16")
+    alen = rng.integers(1, Kp1 + 1, B).astype(np.int32)
+    path = np.full((B, Kp1), -1, np.int32)
+    for b in range(B):
+        path[b, :alen[b]] = np.sort(rng.choice(T, alen[b], replace=False))
+    pl = rng.integers(0, Lcap - Kp1, B).astype(np.int32)
+    d_kc, d_vc, d_pl = to_dev(kc), to_dev(vc), to_dev(pl)
+    d_out = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    for _ in range(2):
+        M.kv_commit(d_kc, d_vc, to_dev(kt), to_dev(vt), to_dev(path), to_dev(alen), d_pl, d_out)
+    torch.cuda.synchronize()
+    pl_ref = pl.copy()
+    O.kv_commit_ref(kc, vc, kt, vt, path, alen, pl_ref)
+    assert np.array_equal(to_host_bits(d_kc), bits(kc)) and np.array_equal(to_host_bits(d_vc), bits(vc))
+    assert np.array_equal(d_pl.cpu().numpy(), pl) and np.array_equal(d_out.cpu().numpy(), pl_ref)
+
+
 def test_kv_commit_never_writes_past_the_capacity():
     NL, B, Hkv, T, D, Lcap = 1, 2, 2, 5, 8, 6
     n = NL * B * Hkv * Lcap * D
