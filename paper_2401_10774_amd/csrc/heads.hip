@@ -155,6 +155,76 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(GemmArgs a) {
   }
 }
 
+__device__ unsigned int g_gemm_ticket[kMaxSplitTiles];
+
+// Tail shared by the MFMA kernels of this file.  On entry every thread holds, for each of its
+// MT x NT accumulator fragments, rows m0 + (wm*MT + t)*16 + 4*(lane/16)..+3 of column
+// n0 + (wn*NT + j)*16 + lane%16.  With a split reduction the partial tiles go to the workspace and
+// only the workgroup that arrives last carries on, with the sum; then the epilogue stores.
+template <int MT, int NT, int EPI, bool SPLIT>
+__device__ __forceinline__ void finish_tile(const GemmArgs& a, floatx4_t (&acc)[MT][NT], int k, int m_tile, int split,
+                                            int n_split, int n0, int m0, int wm, int wn) {
+  const int tid = threadIdx.x, lane = tid & 63, i16 = lane & 15, q4 = lane >> 4;
+  if (SPLIT && n_split > 1) {
+    // partial tile of this split: [fragment][register pair][thread], 8 bytes per thread and store
+    const unsigned int tile = (k * gridDim.x + blockIdx.x) * (gridDim.z / n_split) + m_tile;
+    constexpr int PART = MT * NT * 2 * 256;              // 8-byte words per partial tile
+    uint64_t* part = (uint64_t*)a.ws + (size_t)tile * n_split * PART;
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int rp = 0; rp < 2; ++rp) {
+          const uint64_t v = (uint64_t)__float_as_uint(acc[t][j][2 * rp]) | ((uint64_t)__float_as_uint(acc[t][j][2 * rp + 1]) << 32);
+          store_agent(part + (size_t)split * PART + ((t * NT + j) * 2 + rp) * 256 + tid, v);
+        }
+    if (!last_workgroup_of(&g_gemm_ticket[tile], (unsigned int)n_split)) return;
+    // Sum in split order.  The loads of a group of slots are all issued before the first sum (each is a
+    // round trip to the memory side of the L2, where the other workgroups' stores are visible); splits
+    // past the last one re-read the last one and are not added.
+    constexpr int SLOTS = MT * NT * 2, GROUP = SLOTS >= 32 ? 8 : 4, MAXS = 8;
+#pragma unroll
+    for (int s0 = 0; s0 < SLOTS; s0 += GROUP) {
+      uint64_t v[GROUP][MAXS];
+#pragma unroll
+      for (int g = 0; g < GROUP; ++g)
+#pragma unroll
+        for (int z = 0; z < MAXS; ++z) {
+          const int slot = s0 + g < SLOTS ? s0 + g : SLOTS - 1;
+          v[g][z] = load_agent(part + (size_t)min(z, n_split - 1) * PART + slot * 256 + tid);
+        }
+#pragma unroll
+      for (int g = 0; g < GROUP; ++g) {
+        if (s0 + g >= SLOTS) continue;
+        float lo = 0.f, hi = 0.f;
+#pragma unroll
+        for (int z = 0; z < MAXS; ++z)
+          if (z < n_split) {
+            lo += __uint_as_float((uint32_t)v[g][z]);
+            hi += __uint_as_float((uint32_t)(v[g][z] >> 32));
+          }
+        const int slot = s0 + g, frag = slot >> 1, rp = slot & 1;
+        acc[frag / NT][frag % NT][2 * rp] = lo;
+        acc[frag / NT][frag % NT][2 * rp + 1] = hi;
+      }
+    }
+  }
+
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int n = n0 + (wn * NT + j) * 16 + i16;
+      const int mb = m0 + (wm * MT + t) * 16 + 4 * q4;
+      if (n < a.N) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (mb + r < a.M) epilogue_store<EPI, uint16_t>(a, mb + r, k, n, acc[t][j][r]);
+      }
+    }
+}
+
 // ---------------------------------------------------------------------------------------
 // bf16, M > 4: LDS-staged MFMA GEMM (v_mfma_f32_16x16x32_bf16).
 //
@@ -176,7 +246,6 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(GemmArgs a) {
 // the workgroup that arrives last adds them up in split order (so the result does not depend on
 // which one that is) and runs the epilogue.
 // ---------------------------------------------------------------------------------------
-__device__ unsigned int g_gemm_ticket[kMaxSplitTiles];
 
 template <int WM, int WN, int MT, int NT, int BK, int PD, int EPI, bool SPLIT = false>
 __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
@@ -284,64 +353,161 @@ __global__ __launch_bounds__(256) void gemm_lds_bf16_kernel(GemmArgs a) {
     }
   }
 
-  if (SPLIT && n_split > 1) {
-    // partial tile of this split: [fragment][register pair][thread], 8 bytes per thread and store
-    const unsigned int tile = (k * gridDim.x + blockIdx.x) * (gridDim.z / n_split) + m_tile;
-    constexpr int PART = MT * NT * 2 * 256;              // 8-byte words per partial tile
-    uint64_t* part = (uint64_t*)a.ws + (size_t)tile * n_split * PART;
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-#pragma unroll
-      for (int j = 0; j < NT; ++j)
-#pragma unroll
-        for (int rp = 0; rp < 2; ++rp) {
-          const uint64_t v = (uint64_t)__float_as_uint(acc[t][j][2 * rp]) | ((uint64_t)__float_as_uint(acc[t][j][2 * rp + 1]) << 32);
-          store_agent(part + (size_t)split * PART + ((t * NT + j) * 2 + rp) * 256 + tid, v);
-        }
-    if (!last_workgroup_of(&g_gemm_ticket[tile], (unsigned int)n_split)) return;
-    // Sum in split order.  The loads of a group of slots are all issued before the first sum (each is a
-    // round trip to the memory side of the L2, where the other workgroups' stores are visible); splits
-    // past the last one re-read the last one and are not added.
-    constexpr int SLOTS = MT * NT * 2, GROUP = SLOTS >= 32 ? 8 : 4, MAXS = 8;
-#pragma unroll
-    for (int s0 = 0; s0 < SLOTS; s0 += GROUP) {
-      uint64_t v[GROUP][MAXS];
-#pragma unroll
-      for (int g = 0; g < GROUP; ++g)
-#pragma unroll
-        for (int z = 0; z < MAXS; ++z) {
-          const int slot = s0 + g < SLOTS ? s0 + g : SLOTS - 1;
-          v[g][z] = load_agent(part + (size_t)min(z, n_split - 1) * PART + slot * 256 + tid);
-        }
-#pragma unroll
-      for (int g = 0; g < GROUP; ++g) {
-        if (s0 + g >= SLOTS) continue;
-        float lo = 0.f, hi = 0.f;
-#pragma unroll
-        for (int z = 0; z < MAXS; ++z)
-          if (z < n_split) {
-            lo += __uint_as_float((uint32_t)v[g][z]);
-            hi += __uint_as_float((uint32_t)(v[g][z] >> 32));
-          }
-        const int slot = s0 + g, frag = slot >> 1, rp = slot & 1;
-        acc[frag / NT][frag % NT][2 * rp] = lo;
-        acc[frag / NT][frag % NT][2 * rp + 1] = hi;
-      }
-    }
-  }
+  finish_tile<MT, NT, EPI, SPLIT>(a, acc, k, m_tile, split, n_split, n0, m0, wm, wn);
+}
 
+// ---------------------------------------------------------------------------------------
+// bf16, 4 < M <= ~128 per row block: skinny MFMA GEMM whose wavefronts split the reduction.
+//
+// Workgroup tile BM x BN = 16*MT activation rows x 16*NTW weight rows, reduction in stages of 128
+// elements (256 bytes per row).  The four wavefronts each take one 32-element slice of a stage
+// and the WHOLE tile: every 16-byte LDS chunk is then read by exactly one wavefront, where an
+// arrangement that splits the weight rows over the wavefronts has each of them read all the
+// activation rows (3.6x the LDS reads at MT = 5), and LDS time, not HBM, set the pace of that
+// arrangement from M = 48 upwards.  After the loop the four partial tiles are added through LDS
+// (in wavefront order), wavefront w ending up with the NTW/4 column fragments w*NTW/4.. of all
+// rows: the accumulator layout finish_tile() expects for wavefronts arranged 1 x 4.
+//
+// Loads: thread t fetches, for each of the MT + NTW groups of 16 rows, the 16-byte chunk t%16 of
+// row t/16 of the group: 16 consecutive lanes cover 256 contiguous bytes of a row.  They are
+// held in registers PD stages ahead of their use and written to a double-buffered LDS tile with
+// chunk c of row r at slot c ^ (r%16), which keeps both the row-major stores and the fragment
+// reads (16 rows x 4 chunks per instruction) free of bank conflicts.  One barrier per stage.
+// An odd number of 64-element steps leaves the second half of the last stage empty: wavefronts 2
+// and 3 multiply zeros there.  grid (ceil(N/BN), K, ceil(M/BM)), 256 threads, dynamic LDS 2*(BM+BN)*256.
+// (Reductions split over workgroups stay with the kernel above.)
+// ---------------------------------------------------------------------------------------
+template <int MT, int NTW, int PD, int EPI>
+__global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmArgs a) {
+  constexpr int NT = NTW / 4;                         // column fragments a wavefront owns in the end
+  constexpr int BM = 16 * MT, BN = 16 * NTW;
+  constexpr int LPT = MT + NTW;                       // chunks per thread and stage
+  constexpr int STAGE = (BM + BN) * 256;
+  constexpr bool HM = kHeadMajor<EPI>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_dyn[];
+  unsigned char* lds = lds_dyn;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i16 = lane & 15, q4 = lane >> 4;
+  const int k = blockIdx.y;
+  const int m_tile = blockIdx.z;
+  const int n0 = blockIdx.x * BN, m0 = m_tile * BM;
+  // Byte offsets from the tile's first weight row (< 128 rows x d) and from X fit 32 bits.
+  const unsigned char* Wt = (const unsigned char*)((const uint16_t*)a.W + ((size_t)k * a.N + n0) * a.d);
+  const unsigned char* Xb = (const unsigned char*)a.X;
+  const int r16 = tid >> 4, c16 = tid & 15, half = c16 >> 3;
+  uint32_t goff[LPT];
+#pragma unroll
+  for (int it = 0; it < LPT; ++it)
+    goff[it] = it < MT ? (uint32_t)(x_row_offset<HM>(a, min(m0 + it * 16 + r16, a.M - 1), k) * 2) + (c16 & 7) * 16
+                       : (uint32_t)min((it - MT) * 16 + r16, a.N - 1 - n0) * (uint32_t)a.d * 2u + (c16 & 7) * 16;
+  const int st_off = r16 * 256 + ((c16 ^ r16) << 4);  // (row%16 == r16 for every group of 16 rows)
+
+  const int nk = a.d >> 6;                            // 64-element steps
+  const int stages = (nk + 1) >> 1;
+
+  u32x4_t regs[PD][LPT];
+  auto gload = [&](int stage, u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
+    // this thread's chunk lies in the first or second 64-element step of the stage; past the end
+    // of the reduction the last step is fetched again (and never used)
+    const int e0 = min(2 * stage, nk - 1) * 64, e1 = min(2 * stage + 1, nk - 1) * 64;
+    const uint32_t so_w = (uint32_t)(half ? e1 : e0) * 2u;
+    const uint32_t so_x = (uint32_t)(half ? x_col_offset<HM>(a, e1) : x_col_offset<HM>(a, e0)) * 2u;
+#pragma unroll
+    for (int it = 0; it < LPT; ++it)
+      r[it] = it < MT ? *(const u32x4_t*)(Xb + (goff[it] + so_x)) : *(const u32x4_t*)(Wt + (goff[it] + so_w));
+  };
+  // (activation chunks of a half stage past the end of the reduction are stored as zeros)
+  auto lstore = [&](int buf, int stage, const u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
+    unsigned char* b = lds + buf * STAGE + st_off;
+    const uint32_t keep = (uint32_t) - (int)(2 * stage + half < nk);
+#pragma unroll
+    for (int it = 0; it < LPT; ++it) *(u32x4_t*)(b + it * 4096) = it < MT ? (r[it] & keep) : r[it];
+  };
+  floatx4_t acc[MT][NTW];
 #pragma unroll
   for (int t = 0; t < MT; ++t)
 #pragma unroll
-    for (int j = 0; j < NT; ++j) {
-      const int n = n0 + (wn * NT + j) * 16 + i16;
-      const int mb = m0 + (wm * MT + t) * 16 + 4 * q4;
-      if (n < a.N) {
+    for (int j = 0; j < NTW; ++j) acc[t][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  // fragment of this wavefront's slice: row i16 of a group of 16, chunk wave*4 + q4
+  const int fr_off = i16 * 256 + (((wave * 4 + q4) ^ i16) << 4);
+  bf16x8_t xf[MT], wf[NTW];
+  auto lfrag = [&](int buf) __attribute__((always_inline)) {
+    const unsigned char* b = lds + buf * STAGE + fr_off;
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (mb + r < a.M) epilogue_store<EPI, uint16_t>(a, mb + r, k, n, acc[t][j][r]);
+    for (int t = 0; t < MT; ++t) xf[t] = *(const bf16x8_t*)(b + t * 4096);
+#pragma unroll
+    for (int j = 0; j < NTW; ++j) wf[j] = *(const bf16x8_t*)(b + (MT + j) * 4096);
+  };
+  auto mfma = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < NTW; ++j)
+#pragma unroll
+      for (int t = 0; t < MT; ++t) acc[t][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[t], wf[j], acc[t][j], 0, 0, 0);
+  };
+
+  // Prologue: stages 0..PD-1 requested, stage 0 into LDS.
+#pragma unroll
+  for (int s = 0; s < PD; ++s) gload(s, regs[s]);
+  lstore(0, 0, regs[0]);
+  __syncthreads();
+  // Main loop, unrolled by PD so that the register stage is a compile-time index.  On entry of
+  // stage s its data is in LDS buffer s%2 and register stage s%PD is free.  Instruction order, given
+  // to the scheduler as groups (masks: 0x008 MFMA, 0x020 global load, 0x100 LDS read, 0x200 LDS
+  // store): the fragment reads, then the requests for stage s+PD under the first MFMAs, and the LDS
+  // stores of stage s+1 -- which wait for that stage to arrive -- under the last ones.
+  constexpr int NMF = MT * NTW;
+  for (int s0 = 0; s0 < stages; s0 += PD) {
+#pragma unroll
+    for (int j = 0; j < PD; ++j) {
+      const int s = s0 + j;
+      if (s >= stages) break;
+      const int cur = s & 1;
+      lfrag(cur);
+      gload(s + PD, regs[j]);
+      mfma();
+      lstore(cur ^ 1, s + 1, regs[(j + 1) % PD]);
+      __builtin_amdgcn_sched_group_barrier(0x100, LPT, 0);
+#pragma unroll
+      for (int g = 0; g < LPT; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       }
+      if (NMF > 2 * LPT) __builtin_amdgcn_sched_group_barrier(0x008, NMF - 2 * LPT, 0);
+#pragma unroll
+      for (int g = 0; g < LPT; ++g) {
+        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      }
+      __syncthreads();
     }
+  }
+
+  // Add the four wavefronts' partial tiles, RT groups of 16 rows at a time: each wavefront writes its
+  // fragments (one 16-byte slot per lane), then collects the four partials of the fragments it owns.
+  constexpr int RT = (2 * STAGE) / (4 * NTW * 1024) < MT ? (2 * STAGE) / (4 * NTW * 1024) : MT;
+  static_assert(RT >= 1, "the reduction area must hold one group of rows");
+  floatx4_t fin[MT][NT];
+#pragma unroll
+  for (int t0 = 0; t0 < MT; t0 += RT) {
+    __syncthreads();                                     // the area (stage buffers, or the previous round) is free
+#pragma unroll
+    for (int t = t0; t < t0 + RT && t < MT; ++t)
+#pragma unroll
+      for (int j = 0; j < NTW; ++j)
+        *(floatx4_t*)(lds + ((((t - t0) * 4 + wave) * NTW + j) * 64 + lane) * 16) = acc[t][j];
+    __syncthreads();
+#pragma unroll
+    for (int t = t0; t < t0 + RT && t < MT; ++t)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        floatx4_t sum = *(const floatx4_t*)(lds + ((((t - t0) * 4 + 0) * NTW + wave * NT + j) * 64 + lane) * 16);
+#pragma unroll
+        for (int w = 1; w < 4; ++w) sum += *(const floatx4_t*)(lds + ((((t - t0) * 4 + w) * NTW + wave * NT + j) * 64 + lane) * 16);
+        fin[t][j] = sum;
+      }
+  }
+  finish_tile<MT, NT, EPI, false>(a, fin, k, m_tile, 0, 1, n0, m0, 0, wave);
 }
 
 // Which kernel a bf16 GEMM of M rows goes to, and in what shape.
@@ -410,6 +576,25 @@ int gemv_rows_per_wg(int N, int K) {
   return rows < 8 ? 8 : (rows > 16 ? 16 : (int)rows);
 }
 
+// Register stages of the skinny kernel: three while its MT + NTW chunks per thread and stage leave room.
+constexpr int skinny_depth(int mt, int ntw) { return mt + ntw <= 13 ? 3 : 2; }
+
+// The skinny kernel's LDS tile exceeds the 64 KB a kernel gets by default: raise the limit once per
+// kernel and device.
+template <void (*Kernel)(GemmArgs)>
+int launch_skinny(dim3 grid, size_t lds, hipStream_t stream, const GemmArgs& a) {
+  static bool raised[64] = {};
+  int dev = 0;
+  MEDUSA_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return MEDUSA_EUNSUPPORTED;
+  if (!raised[dev]) {
+    MEDUSA_HIP_TRY(hipFuncSetAttribute((const void*)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));   // MT = NTW = 8
+    raised[dev] = true;
+  }
+  hipLaunchKernelGGL(Kernel, grid, dim3(256), lds, stream, a);
+  return MEDUSA_OK;
+}
+
 template <int EPI>
 int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) {
   GemmArgs a = a_in;
@@ -448,21 +633,27 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
       MEDUSA_LAUNCH_CHECK();
       return MEDUSA_OK;
     }
+    // A split reduction leaves each workgroup only a few steps: there the kernel whose wavefronts split
+    // the weight rows is faster (no sum over the wavefronts at the end; 21 against 24 us at M = 65,
+    // N = d = 4096).  Unsplit, LDS time decides and the kernel whose wavefronts split the reduction wins.
 #define MEDUSA_SKINNY(MT_)                                                                                                     \
   case MT_:                                                                                                                    \
     if (split) {                                                                                                               \
       if (!wide) hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 1, 64, 4, EPI, kCanSplit>), grid, block, 0, stream, a);   \
       else hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 2, 64, 4, EPI, kCanSplit>), grid, block, 0, stream, a);         \
     } else {                                                                                                                   \
-      if (!wide) hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 1, 64, 4, EPI, false>), grid, block, 0, stream, a);       \
-      else hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 2, 64, 4, EPI, false>), grid, block, 0, stream, a);             \
+      if (!wide) rc = launch_skinny<gemm_skinny_bf16_kernel<MT_, 4, skinny_depth(MT_, 4), EPI>>(grid, lds, stream, a);         \
+      else rc = launch_skinny<gemm_skinny_bf16_kernel<MT_, 8, skinny_depth(MT_, 8), EPI>>(grid, lds, stream, a);               \
     }                                                                                                                          \
     break;
+    const size_t lds = (size_t)2 * (plan.mt + (wide ? 8 : 4)) * 4096;
+    int rc = MEDUSA_OK;
     switch (plan.mt) {
       MEDUSA_SKINNY(1) MEDUSA_SKINNY(2) MEDUSA_SKINNY(3) MEDUSA_SKINNY(4) MEDUSA_SKINNY(5) MEDUSA_SKINNY(6)
       MEDUSA_SKINNY(7) MEDUSA_SKINNY(8)
     }
 #undef MEDUSA_SKINNY
+    if (rc != MEDUSA_OK) return rc;
   }
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;

@@ -40,6 +40,15 @@ def test_bf16_odd_sizes(d, V, K):
         run_case("bf16", M_rows, d, V, K, True, 60)
 
 
+# The skinny MFMA kernel walks the reduction in stages of 128 elements: an odd number of 64-element
+# steps leaves half of the last stage empty.  Narrow (64-column) and wide (128-column, from 200
+# tiles) workgroup tiles, few and many row groups, with and without a ragged last tile.
+@pytest.mark.parametrize("M_rows,d,V,K", [(65, 320, 1000, 2), (70, 192, 12800, 2), (128, 64, 300, 1),
+                                          (120, 448, 12900, 2), (33, 704, 25700, 1)])
+def test_bf16_odd_step_counts(M_rows, d, V, K):
+    run_case("bf16", M_rows, d, V, K, False, 80 + M_rows)
+
+
 @pytest.mark.parametrize("M_rows", [1, 3, 4, 10])
 def test_f32_shapes(M_rows):
     err = run_case("f32", M_rows, 256, 1000, 2, True, 70 + M_rows)
