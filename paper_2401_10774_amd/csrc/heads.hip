@@ -180,34 +180,36 @@ __device__ __forceinline__ void finish_tile(const GemmArgs& a, floatx4_t (&acc)[
           store_agent(part + (size_t)split * PART + ((t * NT + j) * 2 + rp) * 256 + tid, v);
         }
     if (!last_workgroup_of(&g_gemm_ticket[tile], (unsigned int)n_split)) return;
-    // Sum in split order.  The loads of a group of slots are all issued before the first sum (each is a
-    // round trip to the memory side of the L2, where the other workgroups' stores are visible); splits
-    // past the last one re-read the last one and are not added.
-    constexpr int SLOTS = MT * NT * 2, GROUP = SLOTS >= 32 ? 8 : 4, MAXS = 8;
+    // Sum in split order.  Every load is a round trip to the memory side of the L2 (where the other
+    // workgroups' stores are visible), so as many as the registers hold are issued before the first
+    // sum: the whole tile of ZB splits at a time, which is all of them for the usual split counts.
+    constexpr int SLOTS = MT * NT * 2, ZB = SLOTS <= 10 ? 8 : (SLOTS <= 20 ? 4 : 2);
+    float lo[SLOTS], hi[SLOTS];
 #pragma unroll
-    for (int s0 = 0; s0 < SLOTS; s0 += GROUP) {
-      uint64_t v[GROUP][MAXS];
+    for (int sl = 0; sl < SLOTS; ++sl) lo[sl] = hi[sl] = 0.f;
+    for (int z0 = 0; z0 < n_split; z0 += ZB) {
+      uint64_t v[ZB][SLOTS];
 #pragma unroll
-      for (int g = 0; g < GROUP; ++g)
+      for (int zz = 0; zz < ZB; ++zz)
+        if (z0 + zz < n_split) {
 #pragma unroll
-        for (int z = 0; z < MAXS; ++z) {
-          const int slot = s0 + g < SLOTS ? s0 + g : SLOTS - 1;
-          v[g][z] = load_agent(part + (size_t)min(z, n_split - 1) * PART + slot * 256 + tid);
+          for (int sl = 0; sl < SLOTS; ++sl) v[zz][sl] = load_agent(part + (size_t)(z0 + zz) * PART + sl * 256 + tid);
         }
 #pragma unroll
-      for (int g = 0; g < GROUP; ++g) {
-        if (s0 + g >= SLOTS) continue;
-        float lo = 0.f, hi = 0.f;
+      for (int zz = 0; zz < ZB; ++zz)
+        if (z0 + zz < n_split) {
 #pragma unroll
-        for (int z = 0; z < MAXS; ++z)
-          if (z < n_split) {
-            lo += __uint_as_float((uint32_t)v[g][z]);
-            hi += __uint_as_float((uint32_t)(v[g][z] >> 32));
+          for (int sl = 0; sl < SLOTS; ++sl) {
+            lo[sl] += __uint_as_float((uint32_t)v[zz][sl]);
+            hi[sl] += __uint_as_float((uint32_t)(v[zz][sl] >> 32));
           }
-        const int slot = s0 + g, frag = slot >> 1, rp = slot & 1;
-        acc[frag / NT][frag % NT][2 * rp] = lo;
-        acc[frag / NT][frag % NT][2 * rp + 1] = hi;
-      }
+        }
+    }
+#pragma unroll
+    for (int sl = 0; sl < SLOTS; ++sl) {
+      const int frag = sl >> 1, rp = sl & 1;
+      acc[frag / NT][frag % NT][2 * rp] = lo[sl];
+      acc[frag / NT][frag % NT][2 * rp + 1] = hi[sl];
     }
   }
 
@@ -513,12 +515,10 @@ __global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmArgs a) {
 // Which kernel a bf16 GEMM of M rows goes to, and in what shape.
 //   M <= 4                         wave-per-row GEMV.
 //   about one 192/128 x 256 tile per CU or more (M > 80)   the large-tile kernel (gemm_big.hip).
-//   otherwise                      the LDS-staged kernel in its skinny arrangement: row blocks of
-//     16*mt <= 128 activation rows (every wavefront sees all rows of its block), 128 weight rows
-//     per workgroup when that alone gives a few hundred workgroups, else 64, and the reduction
-//     split over up to 8 workgroups when even those are too few.  (Measured at M = 65,
-//     N = d = 4096: 64-row tiles x 8 splits 21 us, 128-row tiles x 8 splits 27 us, unsplit 37 us:
-//     the number of workgroups matters more than the activation re-reads.)
+//   otherwise                      a skinny arrangement: row blocks of 16*mt <= 128 activation rows,
+//     128 weight rows per workgroup when that alone gives 200 workgroups (and mt <= 5), else 64;
+//     unsplit: the kernel whose wavefronts split the reduction; with under 128 tiles and a workspace:
+//     the kernel whose wavefronts split the weight rows, its reduction split over 2-8 workgroups.
 //   M > 80 and at least 200 tiles of 128 x 128: those tiles, wavefronts 2 x 2, unsplit (at M = 356
 //     and 1040 the skinny arrangement was up to 1.5x faster below that tile count and up to 1.6x
 //     slower above it; splitting the 128 x 128 kernel's reduction never paid for its 64 KB partials).
@@ -548,14 +548,19 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
   }
   p.kind = GemmPlan::SKINNY;
   p.mt = ceil_div(ceil_div(M, p.m_blocks), 16);
-  p.wide = (long)ceil_div(N, 128) * K * p.m_blocks >= 200;  // measured at V = 32000, M = 65: 52 us wide, 63 us narrow
+  p.wide = p.mt <= 5 && (long)ceil_div(N, 128) * K * p.m_blocks >= 200;   // (128-column tiles exist for up to 80 rows)
   if (!have_ws) return p;
+  // Split the reduction only when the unsplit kernel would leave most of the chip idle (under 128
+  // tiles): into the largest power of two of workgroups per tile that leaves each at least 16 steps
+  // and the launch at most ~640 workgroups.  Measured at M = 65 (us, splits 1/2/4/8):
+  // N = 4096, d = 4096: 25/24/18/19;  N = 4096, d = 11008: 67/54/36/35;  N = 5120, d = 13824: 83/65/57/54;
+  // N = 11008, d = 4096: 32/37/36/45;  N = 13824, d = 5120: 41/48/53/63.
   const long tiles = (long)ceil_div(N, p.wide ? 128 : 64) * K * p.m_blocks;
-  if (tiles >= 384 || tiles > kMaxSplitTiles) return p;
-  long s = 512 / tiles;
-  const long by_steps = (d / 64) / 8;                       // at least 8 reduction steps per split
-  s = s < by_steps ? s : by_steps;
-  p.ksplit = (int)(s < 1 ? 1 : (s > 8 ? 8 : s));
+  if (tiles >= 128) return p;
+  long cap = 640 / tiles;
+  const long by_steps = (d / 64) / 16;
+  cap = cap < by_steps ? cap : by_steps;
+  while (p.ksplit * 2 <= cap && p.ksplit < 8) p.ksplit *= 2;
   return p;
 }
 // Workspace for the fp32 partial tiles of a split reduction (0 if this shape is not split).
@@ -642,8 +647,8 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
       if (!wide) hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 1, 64, 4, EPI, kCanSplit>), grid, block, 0, stream, a);   \
       else hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 2, 64, 4, EPI, kCanSplit>), grid, block, 0, stream, a);         \
     } else {                                                                                                                   \
-      if (!wide) rc = launch_skinny<gemm_skinny_bf16_kernel<MT_, 4, skinny_depth(MT_, 4), EPI>>(grid, lds, stream, a);         \
-      else rc = launch_skinny<gemm_skinny_bf16_kernel<MT_, 8, skinny_depth(MT_, 8), EPI>>(grid, lds, stream, a);               \
+      if (!wide) rc = launch_skinny<gemm_skinny_bf16_kernel<MT_, 4, skinny_depth(MT_, 4), EPI>>(grid, lds, stream, a);  \
+      else rc = launch_skinny<gemm_skinny_bf16_kernel<(MT_ <= 5 ? MT_ : 5), 8, skinny_depth(MT_, 8), EPI>>(grid, lds, stream, a); \
     }                                                                                                                          \
     break;
     const size_t lds = (size_t)2 * (plan.mt + (wide ? 8 : 4)) * 4096;
