@@ -139,18 +139,50 @@ __device__ __forceinline__ void accept_finalize(int b, const float* __restrict__
   __shared__ float s_m[MEDUSA_MAX_TREE_TOKENS], s_lnS[MEDUSA_MAX_TREE_TOKENS], s_H[MEDUSA_MAX_TREE_TOKENS];
   __shared__ uint64_t s_pass[2];
   __shared__ uint32_t s_best[2];
+  __shared__ uint64_t s_anc[MEDUSA_MAX_TREE_TOKENS][2];
+  __shared__ int32_t s_tok[MEDUSA_MAX_TREE_TOKENS];
   const int t = threadIdx.x;
   const int T = tree->T, K = tree->K;
   const int lane = t & 63, wave = t >> 6;
+  // Everything this thread will need from memory is requested up front, so that the workgroup pays
+  // one round trip, not one per phase: its node's tree-table entries, its token, and all partials.
+  int par = 0, tok = -1, dep = 0;
+  uint64_t anc0 = 0, anc1 = 0;
   if (t < T) {
+    par = tree->parent[t];
+    dep = tree->depth[t];
+    anc0 = tree->anc_mask[t][0];
+    anc1 = tree->anc_mask[t][1];
+    tok = tree_tokens[(size_t)b * T + t];
     const RowPart* p = part + ((size_t)b * T + t) * kAccMaxChunks;
-    uint64_t key = load_agent(&p[0].key);
-    float m = load_agent(&p[0].m), S = load_agent(&p[0].S), U = load_agent(&p[0].U);
-    for (int c = 1; c < chunks; ++c) {
-      const uint64_t k2 = load_agent(&p[c].key);
-      key = k2 > key ? k2 : key;
-      if (TYPICAL) stats_merge(m, S, U, load_agent(&p[c].m), load_agent(&p[c].S), load_agent(&p[c].U));
+    uint64_t keys[kAccMaxChunks];
+    float pm[kAccMaxChunks], pS[kAccMaxChunks], pU[kAccMaxChunks];
+#pragma unroll
+    for (int c = 0; c < kAccMaxChunks; ++c)
+      if (c < chunks) {
+        keys[c] = load_agent(&p[c].key);
+        if (TYPICAL) {
+          pm[c] = load_agent(&p[c].m);
+          pS[c] = load_agent(&p[c].S);
+          pU[c] = load_agent(&p[c].U);
+        }
+      }
+    uint64_t key = keys[0];
+    float m = 0.f, S = 0.f, U = 0.f;
+    if (TYPICAL) {
+      m = pm[0];
+      S = pS[0];
+      U = pU[0];
     }
+#pragma unroll
+    for (int c = 1; c < kAccMaxChunks; ++c)
+      if (c < chunks) {
+        key = keys[c] > key ? keys[c] : key;
+        if (TYPICAL) stats_merge(m, S, U, pm[c], pS[c], pU[c]);
+      }
+    s_anc[t][0] = anc0;
+    s_anc[t][1] = anc1;
+    s_tok[t] = tok;
     s_arg[t] = (int32_t)rank_key_id(key);
     if (TYPICAL) {
       // statistics are in log2 units: ln S stays ln S, the entropy is ln S - ln 2 * U / S
@@ -164,8 +196,6 @@ __device__ __forceinline__ void accept_finalize(int b, const float* __restrict__
   bool pass = false;
   if (t == 0) pass = true;                                   // the root is accepted unconditionally
   else if (t < T) {
-    const int par = tree->parent[t];
-    const int tok = tree_tokens[(size_t)b * T + t];
     if (!TYPICAL) {
       pass = tok == s_arg[par];
     } else if (tok >= 0 && tok < V) {
@@ -180,8 +210,8 @@ __device__ __forceinline__ void accept_finalize(int b, const float* __restrict__
   __syncthreads();
   const uint64_t fail0 = ~s_pass[0], fail1 = ~s_pass[1];
   uint32_t score = 0;
-  if (t < T && (tree->anc_mask[t][0] & fail0) == 0 && (tree->anc_mask[t][1] & fail1) == 0)
-    score = ((uint32_t)(tree->depth[t] + 1) << 8) | (uint32_t)(255 - t);   // deeper first, then lower index
+  if (t < T && (anc0 & fail0) == 0 && (anc1 & fail1) == 0)
+    score = ((uint32_t)(dep + 1) << 8) | (uint32_t)(255 - t);   // deeper first, then lower index
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) score = max(score, (uint32_t)__shfl_xor((int)score, o, kWave));
   if (lane == 0 && wave < 2) s_best[wave] = score;
@@ -201,14 +231,14 @@ __device__ __forceinline__ void accept_finalize(int b, const float* __restrict__
     if (t < alen) {
       int seen = 0;
       for (int u = 0; u < T; ++u) {
-        if ((tree->anc_mask[best][u >> 6] >> (u & 63)) & 1ull) {
+        if ((s_anc[best][u >> 6] >> (u & 63)) & 1ull) {
           if (seen == t) { node = u; break; }
           ++seen;
         }
       }
     }
     path_nodes[(size_t)b * (K + 1) + t] = node;
-    accepted_tokens[(size_t)b * (K + 1) + t] = node >= 0 ? tree_tokens[(size_t)b * T + node] : -1;
+    accepted_tokens[(size_t)b * (K + 1) + t] = node >= 0 ? s_tok[node] : -1;
   }
 }
 

@@ -1,8 +1,9 @@
 // kv_commit (Fig. 1 of the Medusa paper: the accepted prefix is the next step's context):
 // append the accepted path's tree K/V rows to every layer of the cache, then grow prefix_len.
 // Pure index arithmetic and 16-byte copies: bit-exact by construction.  One launch: every
-// workgroup reads the old prefix_len before it takes a ticket, and the workgroup that draws the
-// last ticket writes the new lengths (in place, or to a second array) once all others are done.
+// workgroup reads the old prefix_len.  In place, each takes a ticket afterwards and the workgroup
+// that draws the last one writes the new lengths, once all others are done with the old ones;
+// with a second array for the new lengths nobody has to wait: workgroup 0 writes them.
 #include "common.hpp"
 
 namespace {
@@ -18,29 +19,44 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(u32x4_t* __restrict__ k_
                                                         const int32_t* __restrict__ path_nodes, int path_stride,
                                                         const int32_t* __restrict__ accept_len,
                                                         const int32_t* prefix_len, int32_t* prefix_len_out, int B,
-                                                        int Hkv, int T, int Lcap, int vec_per_row) {
+                                                        int Hkv, int T, int Lcap, int vec_per_row, int in_place) {
   const int lb = blockIdx.x;                  // l*B + b
   const int b = lb % B;
   const int a = min(max(accept_len[b], 0), path_stride);
   const int L = prefix_len[b];
-  const int per_head = a * vec_per_row;       // 16-byte chunks per head and tensor
-  const int total = 2 * Hkv * per_head;
-  for (int i = threadIdx.x; i < total; i += 256) {
-    const int which = i >= Hkv * per_head;
-    int rem = i - which * Hkv * per_head;
-    const int h = rem / per_head;
-    rem -= h * per_head;
-    const int j = rem / vec_per_row, c = rem - j * vec_per_row;
-    const int node = path_nodes[(size_t)b * path_stride + j];
-    const int dst = L + j;
-    if (node < 0 || node >= T || dst < 0 || dst >= Lcap) continue;
-    const size_t lbh = (size_t)lb * Hkv + h;
-    const size_t src_i = (lbh * T + node) * vec_per_row + c;
-    const size_t dst_i = (lbh * Lcap + dst) * vec_per_row + c;
-    if (which) v_cache[dst_i] = v_tree[src_i];
-    else k_cache[dst_i] = k_tree[src_i];
+  // Work item i: path slot j = i / per_slot, then tensor (K, V), head, 16-byte chunk.  A thread's path
+  // node does not depend on accept_len, so the three small loads go out together; four items per
+  // thread and round, so that their row loads do too; the rounds end at the first unaccepted slot.
+  const int per_head = vec_per_row, per_slot = 2 * Hkv * per_head;
+  const int total = path_stride * per_slot;
+  for (int base = 0; base < total; base += 4 * 256) {
+    if (base / per_slot >= a) break;
+    size_t src_i[4], dst_i[4];
+    bool ok[4], which[4];
+    u32x4_t val[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = base + u * 256 + threadIdx.x;
+      const int j = min(i / per_slot, path_stride - 1);
+      int rem = i - j * per_slot;
+      which[u] = rem >= Hkv * per_head;
+      rem -= which[u] * Hkv * per_head;
+      const int h = rem / per_head, c = rem - h * per_head;
+      const int node = path_nodes[(size_t)b * path_stride + j];
+      const int dst = L + j;
+      ok[u] = i < total && j < a && node >= 0 && node < T && dst >= 0 && dst < Lcap;
+      const size_t lbh = (size_t)lb * Hkv + h;
+      src_i[u] = (lbh * T + node) * vec_per_row + c;
+      dst_i[u] = (lbh * Lcap + dst) * vec_per_row + c;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (ok[u]) val[u] = which[u] ? v_tree[src_i[u]] : k_tree[src_i[u]];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (ok[u]) (which[u] ? v_cache : k_cache)[dst_i[u]] = val[u];
   }
-  if (!last_workgroup_of(&g_commit_ticket, gridDim.x)) return;
+  if (in_place ? !last_workgroup_of(&g_commit_ticket, gridDim.x) : blockIdx.x != 0) return;
   for (int bb = threadIdx.x; bb < B; bb += 256) {
     const int aa = min(max(accept_len[bb], 0), path_stride);
     prefix_len_out[bb] = min(max(prefix_len[bb], 0) + aa, Lcap);
@@ -61,7 +77,8 @@ extern "C" int kv_commit(void* k_cache, void* v_cache, const void* k_tree, const
   hipStream_t stream = (hipStream_t)stream_;
   hipLaunchKernelGGL(kv_commit_kernel, dim3(NL * B), dim3(256), 0, stream, (u32x4_t*)k_cache, (u32x4_t*)v_cache,
                      (const u32x4_t*)k_tree, (const u32x4_t*)v_tree, path_nodes, path_stride, accept_len, prefix_len,
-                     prefix_len_out ? prefix_len_out : prefix_len, B, Hkv, T, Lcap, (int)(row_bytes / 16));
+                     prefix_len_out ? prefix_len_out : prefix_len, B, Hkv, T, Lcap, (int)(row_bytes / 16),
+                     (int)(!prefix_len_out || prefix_len_out == prefix_len));
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;
 }

@@ -56,11 +56,10 @@ __global__ __launch_bounds__(256) void topk_tree_kernel(const float* __restrict_
                                                         uint64_t* __restrict__ part, const TreeTables* __restrict__ tree,
                                                         const int32_t* __restrict__ prefix_len,
                                                         int32_t* __restrict__ topk_ids, int32_t* __restrict__ tree_tokens,
-                                                        int32_t* __restrict__ position_ids) {
+                                                        int32_t* __restrict__ position_ids, int K) {
   __shared__ uint64_t cand[4][S];
   __shared__ int32_t flat[1 + MEDUSA_MAX_HEADS * kMaxS];
-  const int K = tree->K;
-  const int chunks = gridDim.x;
+  const int chunks = gridDim.x;                     // (K = tree->K comes as an argument: the row decode below needs it at once)
   const int row = blockIdx.y;                       // b*(K+1) + h
   const int b = row / (K + 1), h = row - b * (K + 1);
   const float* src = h == 0 ? lm_logits + (size_t)b * V : medusa_logits + ((size_t)b * K_heads + (h - 1)) * V;
@@ -112,43 +111,66 @@ __global__ __launch_bounds__(256) void topk_tree_kernel(const float* __restrict_
 
   // ---- the sequence's last workgroup merges the chunk winners and fills the tree ------------
   if (!last_workgroup_of(&g_topk_ticket[b], (unsigned)(chunks * (K + 1)))) return;
+  // Everything needed from memory is requested before the first use: the tree-table entries of this
+  // thread's node, the prefix length, and the chunk winners of the rows this wavefront merges
+  // (row hh goes to wavefront hh % 4), so that the merge costs one round trip, not one per row.
   const int Smax = tree->S, T = tree->T;
-  if (wave == 0) {
-    for (int hh = 0; hh <= K; ++hh) {
-      const int want = hh == 0 ? 1 : tree->topk_per_head[hh - 1];
-      const uint64_t* p = part + ((size_t)b * (K + 1) + hh) * kMaxChunks * S;
-      constexpr int PER_LANE = (kMaxChunks * S + 63) / 64;
-      uint64_t c[PER_LANE];
+  const int L = prefix_len[b];
+  constexpr int TPT = (MEDUSA_MAX_TREE_TOKENS + 255) / 256;          // tree nodes per thread
+  int my_src[TPT], my_depth[TPT];
 #pragma unroll
-      for (int j = 0; j < PER_LANE; ++j) c[j] = j * 64 + lane < chunks * S ? load_agent(p + j * 64 + lane) : 0;
-      for (int r = 0; r < want; ++r) {
-        uint64_t mx = c[0];
+  for (int u = 0; u < TPT; ++u) {
+    const int t = threadIdx.x + u * 256;
+    my_src[u] = t < T ? tree->token_src[t] : 0;
+    my_depth[u] = t < T ? tree->depth[t] : 0;
+  }
+  constexpr int PER_LANE = (kMaxChunks * S + 63) / 64;
+  constexpr int RPW = (MEDUSA_MAX_HEADS + 1 + 3) / 4;                // rows per wavefront
+  uint64_t c[RPW][PER_LANE];
+  int want[RPW], base[RPW];
 #pragma unroll
-        for (int j = 1; j < PER_LANE; ++j) mx = c[j] > mx ? c[j] : mx;
-        const uint64_t best = wave_max_u64(mx);
-        bool done = false;                            // keys are unique: exactly one slot matches
+  for (int q = 0; q < RPW; ++q) {
+    const int hh = wave + 4 * q;
+    want[q] = hh > K ? 0 : (hh == 0 ? 1 : tree->topk_per_head[hh - 1]);
+    base[q] = hh > K || hh == 0 ? 0 : tree->head_base[hh - 1];
+    const uint64_t* p = part + ((size_t)b * (K + 1) + min(hh, K)) * kMaxChunks * S;
 #pragma unroll
-        for (int j = 0; j < PER_LANE; ++j) {
-          if (!done && c[j] == best) { c[j] = 0; done = true; }
-        }
-        if (lane == 0) {
-          const int32_t id = (int32_t)rank_key_id(best);
-          if (hh == 0) flat[0] = id;
-          else {
-            flat[tree->head_base[hh - 1] + r] = id;
-            topk_ids[((size_t)b * K + (hh - 1)) * Smax + r] = id;
-          }
+    for (int j = 0; j < PER_LANE; ++j) c[q][j] = hh <= K && j * 64 + lane < chunks * S ? load_agent(p + j * 64 + lane) : 0;
+  }
+#pragma unroll
+  for (int q = 0; q < RPW; ++q) {
+    const int hh = wave + 4 * q;
+    if (hh > K) break;
+    for (int r = 0; r < want[q]; ++r) {
+      uint64_t mx = c[q][0];
+#pragma unroll
+      for (int j = 1; j < PER_LANE; ++j) mx = c[q][j] > mx ? c[q][j] : mx;
+      const uint64_t best = wave_max_u64(mx);
+      bool done = false;                              // keys are unique: exactly one slot matches
+#pragma unroll
+      for (int j = 0; j < PER_LANE; ++j) {
+        if (!done && c[q][j] == best) { c[q][j] = 0; done = true; }
+      }
+      if (lane == 0) {
+        const int32_t id = (int32_t)rank_key_id(best);
+        if (hh == 0) flat[0] = id;
+        else {
+          flat[base[q] + r] = id;
+          topk_ids[((size_t)b * K + (hh - 1)) * Smax + r] = id;
         }
       }
-      if (hh > 0 && lane == 0)
-        for (int r = want; r < Smax; ++r) topk_ids[((size_t)b * K + (hh - 1)) * Smax + r] = -1;
     }
+    if (hh > 0 && lane == 0)
+      for (int r = want[q]; r < Smax; ++r) topk_ids[((size_t)b * K + (hh - 1)) * Smax + r] = -1;
   }
   __syncthreads();
-  const int L = prefix_len[b];
-  for (int t = threadIdx.x; t < T; t += 256) {
-    tree_tokens[(size_t)b * T + t] = flat[tree->token_src[t]];
-    position_ids[(size_t)b * T + t] = L + tree->depth[t];
+#pragma unroll
+  for (int u = 0; u < TPT; ++u) {
+    const int t = threadIdx.x + u * 256;
+    if (t < T) {
+      tree_tokens[(size_t)b * T + t] = flat[my_src[u]];
+      position_ids[(size_t)b * T + t] = L + my_depth[u];
+    }
   }
 }
 
@@ -181,7 +203,7 @@ extern "C" int medusa_topk_tree(const float* medusa_logits, const float* lm_logi
   const int Sc = S <= 1 ? 1 : (S <= 2 ? 2 : (S <= 4 ? 4 : (S <= 8 ? 8 : 16)));
 #define MEDUSA_TOPK(S_)                                                                                         \
   hipLaunchKernelGGL(topk_tree_kernel<S_>, grid, block, 0, stream, medusa_logits, lm_logits, V, K_heads, part, \
-                     tree->dev, prefix_len, topk_ids, tree_tokens, position_ids)
+                     tree->dev, prefix_len, topk_ids, tree_tokens, position_ids, K)
   switch (Sc) {
     case 1: MEDUSA_TOPK(1); break;
     case 2: MEDUSA_TOPK(2); break;
