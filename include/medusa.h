@@ -248,6 +248,17 @@ int tree_rope(void* q, void* k, const int32_t* position_ids, int B, int Hq, int 
               medusa_dtype_t dtype, medusa_stream_t stream);
 
 /* ----------------------------------------------------------------------------------
+ * Tuning knob (no counterpart in the paper).  The MFMA kernels of medusa_heads and tree_linear
+ * for 5..80 rows come in two forms: one is faster when the weight matrix is still in the GPU's
+ * last-level cache from the previous call (an LM head of up to 256 MB that is re-read every step,
+ * with only non-temporal streams in between), the other when it comes from HBM.  Matrices of up to
+ * `bytes` bytes are taken to be cache-resident.  Default 256 MiB; 0 = always assume cold weights
+ * (e.g. when a whole backbone streams through between two calls).  Process-wide, not thread-safe.
+ * Results are within the same tolerance either way (the summation order differs).
+ * -------------------------------------------------------------------------------- */
+int medusa_set_cache_resident_bytes(size_t bytes);
+
+/* ----------------------------------------------------------------------------------
  * Benchmark hook (no counterpart in the paper): while a pair of hipEvent_t handles is set,
  * every medusa_heads call with w1 != NULL records `start` right before and `stop` right after
  * its vocabulary-projection kernel (the W2 stream, the largest single read of the step) on the

@@ -13,6 +13,7 @@ from .binding import (
     medusa_accept,
     medusa_accept_workspace_bytes,
     medusa_heads,
+    medusa_set_cache_resident_bytes,
     medusa_topk_tree,
     tree_attention,
     tree_attention_workspace_bytes,
@@ -23,6 +24,6 @@ from .binding import (
 
 __all__ = [
     "MedusaError", "MedusaTree", "kv_commit", "lib", "library_path", "medusa_accept",
-    "medusa_accept_workspace_bytes", "medusa_heads", "medusa_topk_tree", "tree_attention",
+    "medusa_accept_workspace_bytes", "medusa_heads", "medusa_set_cache_resident_bytes", "medusa_topk_tree", "tree_attention",
     "tree_attention_workspace_bytes", "tree_linear", "tree_linear_workspace_bytes", "tree_rope",
 ]

@@ -27,6 +27,7 @@ EXPORTED_SYMBOLS = (
     "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "medusa_accept_workspace_bytes",
     "medusa_accept", "kv_commit", "tree_linear_workspace_bytes", "tree_linear", "tree_rope",
     "medusa_profile_set_events",
+    "medusa_set_cache_resident_bytes",
 )
 
 
@@ -73,6 +74,7 @@ def lib() -> ctypes.CDLL:
         L.tree_linear.argtypes = [c_void_p] * 4 + [c_int] * 7 + [c_void_p, c_size_t, c_void_p]
         L.tree_rope.argtypes = [c_void_p] * 3 + [c_int] * 5 + [c_float, c_int, c_void_p]
         L.medusa_profile_set_events.argtypes = [c_void_p, c_void_p]
+        L.medusa_set_cache_resident_bytes.argtypes = [ctypes.c_size_t]
         for name in EXPORTED_SYMBOLS:
             fn = getattr(L, name)
             if fn.restype is ctypes.c_int or fn.restype is None:
@@ -365,6 +367,12 @@ def tree_linear(x: torch.Tensor, w: torch.Tensor, B: int, T: int, mul: Optional[
                              0 if workspace is None else workspace.numel() * workspace.element_size(),
                              _stream(stream)), "tree_linear")
     return y
+
+
+def medusa_set_cache_resident_bytes(nbytes: int) -> None:
+    """Weight matrices of up to `nbytes` are taken to stay in the last-level cache between calls
+    (default 256 MiB; 0 = always cold).  Selects between two forms of the 5..80-row MFMA kernels."""
+    _check(lib().medusa_set_cache_resident_bytes(int(nbytes)), "medusa_set_cache_resident_bytes")
 
 
 def tree_rope(q: torch.Tensor, k: torch.Tensor, position_ids: torch.Tensor, theta: float = 10000.0, stream=None) -> None:

@@ -512,6 +512,180 @@ __global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmArgs a) {
   finish_tile<MT, NT, EPI, false>(a, fin, k, m_tile, 0, 1, n0, m0, 0, wave);
 }
 
+// ---------------------------------------------------------------------------------------
+// bf16, 4 < M <= 80, 128-column tiles: the skinny kernel above with the weights fetched in 1 KB runs.
+//
+// Cold weights stream from HBM at 4.4 TB/s when a workgroup asks for 256 bytes of each of its 128
+// rows at a time, at 5.3 TB/s for 1 KB of 32 rows (measured with a plain read kernel).  So the
+// reduction advances in super-stages of 512 elements, and within one the tile's four groups of 32
+// weight rows take turns: a sub-stage is 32 rows x 1 KB of weights, one wavefront instruction per
+// row.  The activation rows of a super-stage (16*MT x 1 KB) sit in a single LDS slab; each
+// wavefront copies the fragments of its 128-element slice into registers at the first sub-stage
+// and keeps them for all four, which frees the slab for the next super-stage's rows: they arrive
+// in three pieces, stored during sub-stages 1 to 3.  Everything else -- wavefronts split the
+// reduction, swizzled unpadded LDS rows (chunk c of row r in slot c ^ (r%16) of its 256-byte
+// group), PD register stages, one barrier per sub-stage, sum over the wavefronts at the end --
+// is as above.  grid (ceil(N/128), K, ceil(M/BM)), 256 threads, dynamic LDS (MT*16 + 64) KB.
+// ---------------------------------------------------------------------------------------
+template <int MT, int PD, int EPI>
+__global__ __launch_bounds__(256) void gemm_runs_bf16_kernel(GemmArgs a) {
+  constexpr int NTW = 8, NT = 2, NG = 4;               // column fragments per tile / per wavefront in the end, column groups
+  constexpr int BM = 16 * MT, BN = 128;
+  constexpr int XQ = MT * 4;                           // activation chunks per thread and super-stage
+  constexpr int XC = (XQ + 2) / 3;                     // ... per piece (three pieces)
+  constexpr int WC = 8;                                // weight chunks per thread and sub-stage
+  constexpr int LPT = WC + XC;
+  constexpr int SLAB = BM * 1024, WBUF = 32 * 1024;
+  constexpr bool HM = kHeadMajor<EPI>;
+  static_assert(PD == 2 || PD == 4, "the loop is unrolled by the four column groups");
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_dyn[];
+  unsigned char* lds = lds_dyn;                        // [slab][weight buffer 0][weight buffer 1]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i16 = lane & 15, q4 = lane >> 4;
+  const int k = blockIdx.y;
+  const int m_tile = blockIdx.z;
+  const int n0 = blockIdx.x * BN, m0 = m_tile * BM;
+  const unsigned char* Wt = (const unsigned char*)((const uint16_t*)a.W + ((size_t)k * a.N + n0) * a.d);
+  const unsigned char* Xb = (const unsigned char*)a.X;
+  const int c64 = lane;                                // this thread's 16-byte chunk of a 1 KB run
+  const int n_super = (a.d + 511) >> 9;
+  const int c_last = ((a.d - (n_super - 1) * 512) >> 3) - 1;   // last valid chunk of the last super-stage
+
+  // Byte offsets of the rows this thread fetches (from the tile's first weight row; from X).
+  const int w_last = a.N - 1 - n0;                     // last weight row of the matrix, relative to the tile
+  const uint32_t w_pitch = (uint32_t)a.d * 2u;
+  uint32_t xoff[XQ];                                   // activation row q*4 + wave
+#pragma unroll
+  for (int q = 0; q < XQ; ++q) xoff[q] = (uint32_t)(x_row_offset<HM>(a, min(m0 + q * 4 + wave, a.M - 1), k) * 2);
+  // LDS offset of this thread's chunk within a 1 KB row whose index is r (mod 16): rows q*4 + wave
+  // and it*4 + wave have r%16 = (4*(q%4) + wave), so the slot depends on q%4 only
+  auto slot_of = [&](int r) { return ((c64 & ~15) | ((c64 ^ r) & 15)) << 4; };
+
+  u32x4_t regs[PD][LPT];
+  // Requests of sub-stage u = 4*S + g: the weights of column group g, super-stage S, and -- for
+  // g = 2, 3, 0 -- piece 0, 1, 2 of the activation rows of super-stage S+1, S+1, S.
+  auto gload = [&](int S, int g, u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
+    const int Sw = min(S, n_super - 1);
+    const int cw = Sw == n_super - 1 ? min(c64, c_last) : c64;
+    const uint32_t so_w = (uint32_t)(Sw * 1024 + cw * 16);
+#pragma unroll
+    for (int it = 0; it < WC; ++it) r[it] = *(const u32x4_t*)(Wt + ((uint32_t)min(g * 32 + it * 4 + wave, w_last) * w_pitch + so_w));
+    if (g != 1) {
+      const int p = g == 0 ? 2 : g - 2;
+      const int Sx = min(g == 0 ? S : S + 1, n_super - 1);
+      const int cx = Sx == n_super - 1 ? min(c64, c_last) : c64;
+      const uint32_t so_x = (uint32_t)(x_col_offset<HM>(a, Sx * 512 + (cx & ~7) * 8) * 2) + (cx & 7) * 16;
+#pragma unroll
+      for (int i = 0; i < XC; ++i) {
+        const int q = p * XC + i < XQ ? p * XC + i : XQ - 1;
+        r[WC + i] = *(const u32x4_t*)(Xb + (xoff[q] + so_x));
+      }
+    }
+  };
+  // ... and their stores: weights to buffer u%2, the activation piece to the slab (zeros beyond d)
+  auto lstore = [&](int S, int g, const u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
+    unsigned char* wb = lds + SLAB + (g & 1) * WBUF + wave * 1024;
+#pragma unroll
+    for (int it = 0; it < WC; ++it) *(u32x4_t*)(wb + it * 4096 + slot_of(it * 4 + wave)) = r[it];
+    if (g != 1) {
+      const int p = g == 0 ? 2 : g - 2;
+      const int Sx = g == 0 ? S : S + 1;
+      const uint32_t keep = (uint32_t) - (int)(Sx < n_super - 1 || (Sx == n_super - 1 && c64 <= c_last));
+#pragma unroll
+      for (int i = 0; i < XC; ++i) {
+        const int q = p * XC + i < XQ ? p * XC + i : XQ - 1;
+        *(u32x4_t*)(lds + (q * 4 + wave) * 1024 + slot_of(q * 4 + wave)) = r[WC + i] & keep;
+      }
+    }
+  };
+  floatx4_t acc[MT][NTW];
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int j = 0; j < NTW; ++j) acc[t][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+  // fragment reads: row i16 of a group of 16, chunks wave*16 + ks*4 + q4 (this wavefront's 128 elements)
+  int fr_off[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    const int c = wave * 16 + ks * 4 + q4;
+    fr_off[ks] = i16 * 1024 + (((c & ~15) | ((c ^ i16) & 15)) << 4);
+  }
+  bf16x8_t xf[MT][4], wf[NT][4];
+
+  // Prologue: the activation rows of super-stage 0 and the weights of sub-stage 0 into LDS,
+  // sub-stages 1..PD-1 requested.
+  {
+    const int cx = n_super == 1 ? min(c64, c_last) : c64;
+    const uint32_t so_x = (uint32_t)(x_col_offset<HM>(a, (cx & ~7) * 8) * 2) + (cx & 7) * 16;
+    const uint32_t keep = (uint32_t) - (int)(n_super > 1 || c64 <= c_last);
+    u32x4_t x0[XQ];
+#pragma unroll
+    for (int q = 0; q < XQ; ++q) x0[q] = *(const u32x4_t*)(Xb + (xoff[q] + so_x));
+    gload(0, 0, regs[0]);
+#pragma unroll
+    for (int q = 0; q < XQ; ++q) *(u32x4_t*)(lds + (q * 4 + wave) * 1024 + slot_of(q * 4 + wave)) = x0[q] & keep;
+    lstore(0, 0, regs[0]);
+  }
+#pragma unroll
+  for (int u = 1; u < PD; ++u) gload(u / NG, u % NG, regs[u]);
+  __syncthreads();
+
+  constexpr int NMF = MT * NT * 4;
+  for (int S = 0; S < n_super; ++S) {
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      // On entry of sub-stage u = 4*S + g its weights are in buffer g%2 and register stage u%PD is free
+      // (its contents, sub-stage u, were stored during the previous sub-stage).
+      if (g == 0) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) xf[t][ks] = *(const bf16x8_t*)(lds + t * 16384 + fr_off[ks]);
+      }
+      const unsigned char* wb = lds + SLAB + (g & 1) * WBUF;
+#pragma unroll
+      for (int f = 0; f < NT; ++f)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) wf[f][ks] = *(const bf16x8_t*)(wb + f * 16384 + fr_off[ks]);
+      gload(S + (g + PD) / NG, (g + PD) % NG, regs[g % PD]);     // sub-stage u + PD
+#pragma unroll
+      for (int f = 0; f < NT; ++f)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+          for (int t = 0; t < MT; ++t)
+            acc[t][g * NT + f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[t][ks], wf[f][ks], acc[t][g * NT + f], 0, 0, 0);
+      lstore(S + (g + 1) / NG, (g + 1) % NG, regs[(g + 1) % PD]);
+      __syncthreads();
+    }
+  }
+
+  // Add the four wavefronts' partial tiles, RT groups of 16 rows at a time (as in the kernel above).
+  constexpr int RT = (SLAB + 2 * WBUF) / (4 * NTW * 1024) < MT ? (SLAB + 2 * WBUF) / (4 * NTW * 1024) : MT;
+  floatx4_t fin[MT][NT];
+#pragma unroll
+  for (int t0 = 0; t0 < MT; t0 += RT) {
+    __syncthreads();
+#pragma unroll
+    for (int t = t0; t < t0 + RT && t < MT; ++t)
+#pragma unroll
+      for (int j = 0; j < NTW; ++j)
+        *(floatx4_t*)(lds + ((((t - t0) * 4 + wave) * NTW + j) * 64 + lane) * 16) = acc[t][j];
+    __syncthreads();
+#pragma unroll
+    for (int t = t0; t < t0 + RT && t < MT; ++t)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        floatx4_t sum = *(const floatx4_t*)(lds + ((((t - t0) * 4 + 0) * NTW + wave * NT + j) * 64 + lane) * 16);
+#pragma unroll
+        for (int w = 1; w < 4; ++w) sum += *(const floatx4_t*)(lds + ((((t - t0) * 4 + w) * NTW + wave * NT + j) * 64 + lane) * 16);
+        fin[t][j] = sum;
+      }
+  }
+  finish_tile<MT, NT, EPI, false>(a, fin, k, m_tile, 0, 1, n0, m0, 0, wave);
+}
+
 // Which kernel a bf16 GEMM of M rows goes to, and in what shape.
 //   M <= 4                         wave-per-row GEMV.
 //   about one 192/128 x 256 tile per CU or more (M > 80)   the large-tile kernel (gemm_big.hip).
@@ -525,10 +699,13 @@ __global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmArgs a) {
 struct GemmPlan {
   enum { GEMV, SKINNY, SQUARE, BIG } kind;
   bool wide;
+  bool runs;            // 128-column skinny tiles: the kernel that fetches the weights in 1 KB runs
   int mt, m_blocks, ksplit;
 };
+// Weight matrices up to this many bytes are taken to stay in the last-level cache between calls.
+size_t g_llc_bytes = (size_t)256 << 20;
 GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) {
-  GemmPlan p = {GemmPlan::GEMV, false, 1, 1, 1};
+  GemmPlan p = {GemmPlan::GEMV, false, false, 1, 1, 1};
   if (M <= 4) return p;
   if (M > 80 && !wide_offsets) {                            // (the large-tile kernel addresses with 32-bit element offsets)
     const bool tall = ceil_div(M, 192) * 192 <= ceil_div(M, 128) * 128;
@@ -549,6 +726,9 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
   p.kind = GemmPlan::SKINNY;
   p.mt = ceil_div(ceil_div(M, p.m_blocks), 16);
   p.wide = p.mt <= 5 && (long)ceil_div(N, 128) * K * p.m_blocks >= 200;   // (128-column tiles exist for up to 80 rows)
+  // Cold weights want long runs per row (15-19 % faster at M = 8..64, 10 % at 65..80); weights that
+  // the last-level cache holds want the short-stage kernel (3-8 % faster there).
+  p.runs = p.wide && (size_t)K * N * d * sizeof(uint16_t) > g_llc_bytes;
   if (!have_ws) return p;
   // Split the reduction only when the unsplit kernel would leave most of the chip idle (under 128
   // tiles): into the largest power of two of workgroups per tile that leaves each at least 16 steps
@@ -593,7 +773,7 @@ int launch_skinny(dim3 grid, size_t lds, hipStream_t stream, const GemmArgs& a) 
   MEDUSA_HIP_TRY(hipGetDevice(&dev));
   if (dev < 0 || dev >= 64) return MEDUSA_EUNSUPPORTED;
   if (!raised[dev]) {
-    MEDUSA_HIP_TRY(hipFuncSetAttribute((const void*)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));   // MT = NTW = 8
+    MEDUSA_HIP_TRY(hipFuncSetAttribute((const void*)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024));   // the largest tile of these kernels
     raised[dev] = true;
   }
   hipLaunchKernelGGL(Kernel, grid, dim3(256), lds, stream, a);
@@ -648,6 +828,7 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
       else hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 2, 64, 4, EPI, kCanSplit>), grid, block, 0, stream, a);         \
     } else {                                                                                                                   \
       if (!wide) rc = launch_skinny<gemm_skinny_bf16_kernel<MT_, 4, skinny_depth(MT_, 4), EPI>>(grid, lds, stream, a);  \
+      else if (plan.runs) rc = launch_skinny<gemm_runs_bf16_kernel<(MT_ <= 5 ? MT_ : 5), (MT_ <= 2 ? 4 : 2), EPI>>(grid, (size_t)(plan.mt * 16 + 64) * 1024, stream, a); \
       else rc = launch_skinny<gemm_skinny_bf16_kernel<(MT_ <= 5 ? MT_ : 5), 8, skinny_depth(MT_, 8), EPI>>(grid, lds, stream, a); \
     }                                                                                                                          \
     break;
@@ -751,6 +932,11 @@ extern "C" int tree_linear(const void* x, const void* w, const void* mul, void* 
     a.ws = workspace;
   hipStream_t stream = (hipStream_t)stream_;
   return mul ? launch_gemm<EPI_GATED>(a, dtype, stream) : launch_gemm<EPI_PLAIN>(a, dtype, stream);
+}
+
+extern "C" int medusa_set_cache_resident_bytes(size_t bytes) {
+  g_llc_bytes = bytes;
+  return MEDUSA_OK;
 }
 
 extern "C" int medusa_profile_set_events(void* start, void* stop) {

@@ -60,6 +60,18 @@ def test_linear_bf16_large_tile_kernel():
     linear_case("bf16", 4, 89, 192, 25600, 0, 0, False, 423)          # 356 rows: two 192-row tiles
 
 
+def test_linear_bf16_long_run_kernel():
+    # 200 tiles of 128 columns at up to 80 rows, weights declared cold: the kernel that fetches 1 KB
+    # runs, with the gated epilogue and with head-major activations on both sides
+    M.medusa_set_cache_resident_bytes(0)
+    try:
+        linear_case("bf16", 1, 65, 192, 25600, 0, 0, True, 430)
+        linear_case("bf16", 2, 33, 256, 25600, 2, 200, False, 431)
+        linear_case("bf16", 1, 10, 1024, 25610, 8, 0, True, 432)
+    finally:
+        M.medusa_set_cache_resident_bytes(256 << 20)
+
+
 def test_linear_f32():
     linear_case("f32", 1, 10, 256, 96, 0, 0, False, 410)
     linear_case("f32", 2, 10, 256, 128, 4, 2, True, 411)

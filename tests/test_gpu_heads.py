@@ -49,6 +49,22 @@ def test_bf16_odd_step_counts(M_rows, d, V, K):
     run_case("bf16", M_rows, d, V, K, False, 80 + M_rows)
 
 
+# The 128-column skinny tiles have a second kernel for weights that come from HBM rather than from
+# the last-level cache (1 KB runs per weight row, super-stages of 512 elements).  The library picks
+# it for weight matrices above a size threshold; with the threshold at zero the same shapes as
+# above -- row groups 1..5, ragged last tile, one to several super-stages, partial last one -- run
+# through it.
+@pytest.mark.parametrize("M_rows,d,V,K", [(70, 192, 12800, 2), (120, 448, 12900, 2), (33, 704, 25700, 1),
+                                          (5, 512, 25600, 1), (17, 1024, 6400, 4), (48, 1600, 12803, 2),
+                                          (64, 64, 25600, 1), (80, 2560, 25601, 1)])
+def test_bf16_long_run_kernel(M_rows, d, V, K):
+    M.medusa_set_cache_resident_bytes(0)
+    try:
+        run_case("bf16", M_rows, d, V, K, False, 90 + M_rows)
+    finally:
+        M.medusa_set_cache_resident_bytes(256 << 20)
+
+
 @pytest.mark.parametrize("M_rows", [1, 3, 4, 10])
 def test_f32_shapes(M_rows):
     err = run_case("f32", M_rows, 256, 1000, 2, True, 70 + M_rows)
