@@ -3,21 +3,23 @@
 // (ancestors and itself).  The tree mask is one 128-bit word per query row.
 //
 // bf16 path: split-K flash-decoding on 16x16x32 bf16 MFMA.
-//   * One workgroup = one (sequence, KV head, block of up to 80 query rows, split of the key
+//   * One workgroup = one (sequence, KV head, block of up to 96 query rows, split of the key
 //     range).  All G = Hq/Hkv query heads that share the KV head are handled together: their
 //     G*T rows are contiguous in q and out.
 //   * Keys are numbered prefix first, tree after (key L+u is tree node u), and processed in
 //     64-key blocks; a split owns a contiguous run of blocks, computed from prefix_len[b] on
 //     the device.  K and V tiles are fetched with full-line 16-byte loads one block ahead of
-//     their use (registers), then parked in swizzled LDS tiles; K of block i+1 and V of block i
-//     are written between the two barriers of block i, so single tiles suffice and two
-//     workgroups fit on a CU to cover each other's latencies.
-//   * Scores are formed transposed, S^T = K Q^T: wavefront w owns keys 16w..16w+15 of the block
-//     for all query rows, so each lane owns one query column per tile and the row maximum needs
-//     two cross-lane steps plus one exchange of 4 x rows floats through LDS.  The probabilities
-//     go to LDS as bf16 [query][key]; in the second product O^T = V^T P^T wavefront w owns a
-//     quarter of the head dimension for all query rows, so the output accumulators are never
-//     merged across wavefronts.  Two barriers per 64 keys.
+//     their use (registers), then parked in swizzled, double-buffered LDS tiles: one barrier
+//     per block.
+//   * A wavefront owns 16 query rows and, for them, all keys of a block and the whole head
+//     dimension.  Scores are formed transposed, S^T = K Q^T, so each lane owns one query column:
+//     the row maximum and sum take two cross-lane steps, and the probabilities go from the
+//     accumulators straight into the second product O^T = V^T P^T as its B operand -- nothing
+//     of the soft-max passes through LDS and no wavefront waits for another inside a block.
+//     (An earlier version gave each wavefront 16 keys of the block for all rows in the first
+//     product and a quarter of the head dimension in the second: fewer LDS reads, but the maxima
+//     and the probabilities crossed LDS behind two more barriers; 20/48/78/140 us against
+//     18/40/42/122 us now at the four bf16 benchmark shapes.)
 //   * The tree mask is the 128-bit ancestor word of the lane's query node shifted to the block's
 //     key range; keys past the valid range are redirected to a valid row and masked, so stale or
 //     poisoned cache rows are never used.
@@ -131,12 +133,6 @@ __global__ __launch_bounds__(256) void tree_attn_plain_kernel(AttnArgs a) {
   }
 }
 
-// ---------------------------------------------------------------------------------------
-// MFMA split-K kernel, bf16.  grid (n_splits, Hkv*row_blocks, B), 256 threads.
-// Operand layout of v_mfma_f32_16x16x32_bf16 (A: 16 x 32, B: 32 x 16, C: 16 x 16): lane l
-// holds row (A) / column (B) l%16 and reduction elements 8*(l/16)..+7; it receives column
-// l%16 and rows 4*(l/16)..+3 of C.
-// ---------------------------------------------------------------------------------------
 typedef short short4_t __attribute__((ext_vector_type(4)));
 
 // Four bf16 of a transposed tile: within each group of 16 lanes, lane j of the group receives
@@ -147,30 +143,33 @@ __device__ __forceinline__ short4_t lds_read_tr16(const unsigned char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4_t*)p);
 }
 
-template <int D, int MT>
-__global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
+// ---------------------------------------------------------------------------------------
+// MFMA split-K kernel, bf16.  grid (n_splits, Hkv*row_blocks, B), 64*NW threads.
+// Operand layout of v_mfma_f32_16x16x32_bf16 (A: 16 x 32, B: 32 x 16, C: 16 x 16): lane l
+// holds row (A) / column (B) l%16 and reduction elements 8*(l/16)..+7; it receives column
+// l%16 and rows 4*(l/16)..+3 of C.
+// Wavefront w owns the MTW tiles of 16 query rows w*MTW.. of the workgroup's row block and, for
+// them, ALL 64 keys of a block and the whole head dimension: the row maximum and
+// sum need two cross-lane steps and no LDS, the probabilities go from the accumulators of
+// S^T = K Q^T straight into the B operand of O^T = V^T P^T (lane l%16 = query row in both; the
+// reduction slots of a 32-key step are keys 4*(l/16)..+3 of its two 16-key tiles, and the V
+// fragment is read transposed in the same order), and the only barrier of a 64-key block is the
+// one that publishes the next K and V tiles (double-buffered in LDS, fetched one block ahead into
+// registers by all wavefronts together).
+// ---------------------------------------------------------------------------------------
+template <int D, int MTW, int NW>
+__global__ __launch_bounds__(64 * NW, (NW + 3) / 4) void tree_attn_rows_kernel(AttnArgs a) {
   constexpr int KS = D / 32;                    // reduction steps of K Q^T
-  constexpr int DPW = D / 64;                   // 16-wide output tiles of the head dimension per wavefront
-  // LDS tiles are unpadded; the 16-byte chunk c of row r is stored at chunk slot c ^ swz(r), chosen
-  // per tile so that its reads are bank-conflict free (a 64-lane 16-byte read is served in four
-  // groups of 16 lanes that are not consecutive lanes, an 8-byte read in groups of 16 consecutive
-  // lanes; padded pitches leave both kinds of read two-way conflicted):
-  //   K, read as MFMA operands (16 rows x 4 chunks per instruction): swz = r & 15 (256-byte rows) or
-  //     (r >> 1) & 7 (128-byte rows);
-  //   V, read 8 bytes per lane transposed (4 rows x 32 bytes per 16 lanes): swz = 2 (r & 7), resp.
-  //     2 ((r >> 1) & 3);
-  //   P (128-byte rows, MFMA-operand reads, 8-byte writes): swz = (r >> 1) & 7.
-  constexpr int PITCH = D * 2;                  // bytes per row of the K and V tiles
+  constexpr int DT = D / 16;                    // 16-wide tiles of the head dimension
+  constexpr int NTH = 64 * NW;
+  constexpr int PITCH = D * 2;                  // bytes per row of the K and V tiles (unpadded, swizzled as above)
   constexpr int TENSOR_BYTES = kBlkKeys * PITCH;
-  constexpr int PPITCH = kBlkKeys * 2;          // bytes per row of the probability tile
   constexpr int CPR = D / 8;                    // 16-byte chunks per K/V row
-  constexpr int LPT = kBlkKeys * CPR / 256;     // chunks per thread per block and tensor
-  __shared__ __attribute__((aligned(16))) unsigned char s_k[TENSOR_BYTES];
-  __shared__ __attribute__((aligned(16))) unsigned char s_v[TENSOR_BYTES];
-  __shared__ __attribute__((aligned(16))) unsigned char s_p[16 * MT * PPITCH];
-  __shared__ __attribute__((aligned(16))) float s_max[16 * MT][4];   // block maximum per query row and wavefront
-  __shared__ float s_sum[4][16 * MT];
-  __shared__ uint64_t s_anc[16 * MT][2];        // ancestor mask of every query row of this workgroup
+  constexpr int CHUNKS = kBlkKeys * CPR;        // per block and tensor
+  constexpr int LPT = (CHUNKS + NTH - 1) / NTH; // chunks per thread per block and tensor
+  constexpr int ROWS = 16 * MTW * NW;           // query rows of a workgroup
+  __shared__ __attribute__((aligned(16))) unsigned char s_kv[2][2][TENSOR_BYTES];   // [buffer][K, V]
+  __shared__ uint64_t s_anc[ROWS][2];           // ancestor mask of every query row of this workgroup
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, q4 = lane >> 4;
@@ -184,7 +183,7 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
   const int bps = ceil_div(nblk, a.n_splits);
   const int blk_lo = min(split * bps, nblk), blk_hi = min(nblk, blk_lo + bps);
   const int n_iter = blk_hi - blk_lo;
-  const int row0 = rb * 16 * MT;
+  const int row0 = rb * ROWS + wave * 16 * MTW;          // first query row of this wavefront
 
   const uint16_t* qg = (const uint16_t*)a.q + ((size_t)b * a.Hq + (size_t)kvh * a.G) * T * D;
   const uint16_t* kc = (const uint16_t*)a.k_cache + ((size_t)b * a.Hkv + kvh) * a.Lcap * D;
@@ -192,35 +191,33 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
   const uint16_t* kt = (const uint16_t*)a.k_tree + ((size_t)b * a.Hkv + kvh) * T * D;
   const uint16_t* vt = (const uint16_t*)a.v_tree + ((size_t)b * a.Hkv + kvh) * T * D;
 
-  if (tid < 16 * MT) {
-    const int tq = min(row0 + tid, R - 1) % T;
-    s_anc[tid][0] = a.tree->anc_mask[tq][0];
-    s_anc[tid][1] = a.tree->anc_mask[tq][1];
+  for (int r = tid; r < ROWS; r += NTH) {
+    const int tq = min(rb * ROWS + r, R - 1) % T;
+    s_anc[r][0] = a.tree->anc_mask[tq][0];
+    s_anc[r][1] = a.tree->anc_mask[tq][1];
   }
   // Q^T fragments (B operand of K Q^T): column = query row, reduction = head dimension.
-  bf16x8_t qf[MT][KS];
+  bf16x8_t qf[MTW][KS];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
+  for (int mt = 0; mt < MTW; ++mt) {
     const int r = min(row0 + 16 * mt + i16, R - 1);
 #pragma unroll
     for (int c = 0; c < KS; ++c) qf[mt][c] = *(const bf16x8_t*)(qg + (size_t)r * D + 32 * c + 8 * q4);
   }
 
-  // This thread's chunks of a K (or V) block: row in the block, element offset, LDS offset.
+  // This thread's chunks of a K (or V) block (chunk ids past the block repeat the last chunk).
   auto swz_k = [](int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); };
   auto swz_v = [](int r) { return D == 128 ? 2 * (r & 7) : 2 * ((r >> 1) & 3); };
   int ch_row[LPT], ch_off[LPT], ch_dst_k[LPT], ch_dst_v[LPT];
 #pragma unroll
   for (int it = 0; it < LPT; ++it) {
-    const int id = it * 256 + tid;
+    const int id = min(it * NTH + tid, CHUNKS - 1);
     ch_row[it] = id / CPR;
     const int chunk = id - ch_row[it] * CPR;
     ch_off[it] = ch_row[it] * D + chunk * 8;
     ch_dst_k[it] = ch_row[it] * PITCH + ((chunk ^ swz_k(ch_row[it])) << 4);
     ch_dst_v[it] = ch_row[it] * PITCH + ((chunk ^ swz_v(ch_row[it])) << 4);
   }
-  // One tensor's rows of block `iter` of this split (index clamped into the split's range;
-  // the redundant reloads past the end are never used).
   auto gload = [&](int iter, const uint16_t* cache, const uint16_t* tree_rows, u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
     const int key0 = (blk_lo + min(iter, n_iter - 1)) * kBlkKeys;
     if (key0 + kBlkKeys <= L) {                  // the common case: the whole block lies in the prefix
@@ -242,133 +239,129 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
     for (int it = 0; it < LPT; ++it) *(u32x4_t*)(tile + dst[it]) = r[it];
   };
 
-  floatx4_t o[MT][DPW];
-  float m_run[MT], l_run[MT];
+  floatx4_t o[MTW][DT];
+  float m_run[MTW], l_run[MTW];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
+  for (int mt = 0; mt < MTW; ++mt) {
     m_run[mt] = -INFINITY;
     l_run[mt] = 0.f;
 #pragma unroll
-    for (int dd = 0; dd < DPW; ++dd) o[mt][dd] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    for (int dd = 0; dd < DT; ++dd) o[mt][dd] = floatx4_t{0.f, 0.f, 0.f, 0.f};
   }
   const float sc = a.scale * 1.4426950408889634f;        // scores are kept in log2 units
-  const int kswz = swz_k(i16);                           // (a wavefront's 16-key tile starts at a multiple of 16)
-  const int kf_off = (16 * wave + i16) * PITCH;
-  const int pswz = (i16 >> 1) & 7;
-  const int p_wr_off = i16 * PPITCH + (((2 * wave + (q4 >> 1)) ^ pswz) << 4) + 8 * (q4 & 1);
-  const int p_rd_off = i16 * PPITCH;
-  // transposed V read: lane r of a 16-lane group addresses V[8*q4 + r/4 (+4)][16*dd' + 4*(r%4) .. +3]
-  const int v_row = 8 * q4 + (i16 >> 2);
-  const int v_chunk0 = 2 * (wave * DPW) + ((i16 & 3) >> 1), v_half = 8 * (i16 & 1);
+  const int kswz = swz_k(i16);
+  const int kf_off = i16 * PITCH;
+  // transposed V read: lane r of a 16-lane group addresses V[4*q4 + r/4 (+16)][16*dd + 4*(r%4) .. +3]
+  const int v_row = 4 * q4 + (i16 >> 2);
+  const int v_chunk0 = (i16 & 3) >> 1, v_half = 8 * (i16 & 1);
 
   u32x4_t kreg[LPT], vreg[LPT];
   if (n_iter > 0) {
     gload(0, kc, kt, kreg);
     gload(0, vc, vt, vreg);
-    lstore(s_k, ch_dst_k, kreg);
+    lstore(s_kv[0][0], ch_dst_k, kreg);
+    lstore(s_kv[0][1], ch_dst_v, vreg);
     gload(1, kc, kt, kreg);
+    gload(1, vc, vt, vreg);
   }
   __syncthreads();
 
   for (int i = 0; i < n_iter; ++i) {
-    // here: K of block i is in LDS, K of block i+1 and V of block i are in registers (or in flight)
+    // here: K and V of block i are in LDS buffer i%2, those of block i+1 in registers (or in flight)
+    const unsigned char* s_k = s_kv[i & 1][0];
+    const unsigned char* s_v = s_kv[i & 1][1];
     const int key0 = (blk_lo + i) * kBlkKeys;
-    // ---- S^T for this wavefront's 16 keys, all query tiles ----
-    bf16x8_t kf[KS];
-#pragma unroll
-    for (int c = 0; c < KS; ++c) kf[c] = *(const bf16x8_t*)(s_k + kf_off + (((4 * c + q4) ^ kswz) << 4));
-    floatx4_t sv[MT];
     const bool all_visible = key0 + kBlkKeys <= L;
     const int sh = L - key0;                              // position of tree node 0 inside the block
+    // ---- S^T = K Q^T: four tiles of 16 keys, this wavefront's query tiles ----
+    floatx4_t sv[MTW][4];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      floatx4_t s = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    for (int kt4 = 0; kt4 < 4; ++kt4) {
+      bf16x8_t kf[KS];
 #pragma unroll
-      for (int c = 0; c < KS; ++c) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[c], qf[mt][c], s, 0, 0, 0);
-      s *= sc;
+      for (int c = 0; c < KS; ++c) kf[c] = *(const bf16x8_t*)(s_k + 16 * kt4 * PITCH + kf_off + (((4 * c + q4) ^ kswz) << 4));
+#pragma unroll
+      for (int mt = 0; mt < MTW; ++mt) {
+        floatx4_t acc = floatx4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < KS; ++c) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[c], qf[mt][c], acc, 0, 0, 0);
+        sv[mt][kt4] = acc * sc;
+      }
+    }
+    // the next block's tiles go to the other buffer (free since the barrier of block i-1); then
+    // the requests for the block after it
+    lstore(s_kv[(i & 1) ^ 1][0], ch_dst_k, kreg);
+    lstore(s_kv[(i & 1) ^ 1][1], ch_dst_v, vreg);
+    gload(i + 2, kc, kt, kreg);
+    gload(i + 2, vc, vt, vreg);
+    // ---- mask, online soft-max, probabilities as the B operand of the second product ----
+    bf16x8_t pf[MTW][2];
+#pragma unroll
+    for (int mt = 0; mt < MTW; ++mt) {
       if (!all_visible) {
         // keys key0 .. key0+63: prefix keys are visible to all, tree key L+u iff ancestor bit u
-        const uint64_t lo = s_anc[16 * mt + i16][0], hi = s_anc[16 * mt + i16][1];
+        const int row = wave * 16 * MTW + 16 * mt + i16;
+        const uint64_t lo = s_anc[row][0], hi = s_anc[row][1];
         uint64_t tree_bits;
         if (sh >= 0) tree_bits = lo << sh;
         else if (sh > -64) tree_bits = (lo >> (-sh)) | (hi << (64 + sh));
         else tree_bits = hi >> (-sh - 64);
         const uint64_t vis = tree_bits | (sh > 0 ? (1ull << sh) - 1ull : 0ull);
-        const uint32_t my = (uint32_t)(vis >> (16 * wave + 4 * q4));
 #pragma unroll
-        for (int r = 0; r < 4; ++r) s[r] = (my >> r) & 1u ? s[r] : -INFINITY;
+        for (int kt4 = 0; kt4 < 4; ++kt4) {
+          const uint32_t my = (uint32_t)(vis >> (16 * kt4 + 4 * q4));
+#pragma unroll
+          for (int r = 0; r < 4; ++r) sv[mt][kt4][r] = (my >> r) & 1u ? sv[mt][kt4][r] : -INFINITY;
+        }
       }
-      sv[mt] = s;
-      float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-      mx = rows_max(mx);
-      if (q4 == 0) s_max[16 * mt + i16][wave] = mx;
-    }
-    __syncthreads();        // A: block maxima are visible; every wavefront has left block i-1 and the K tile
-    // ---- online soft-max update, probabilities to LDS ----
+      float mx = -INFINITY;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int c = 16 * mt + i16;
-      const floatx4_t m4 = *(const floatx4_t*)s_max[c];
-      const float mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
+      for (int kt4 = 0; kt4 < 4; ++kt4)
+        mx = fmaxf(mx, fmaxf(fmaxf(sv[mt][kt4][0], sv[mt][kt4][1]), fmaxf(sv[mt][kt4][2], sv[mt][kt4][3])));
+      mx = rows_max(mx);
       const float m_new = fmaxf(m_run[mt], mx);
       const float m_safe = m_new == -INFINITY ? 0.f : m_new;
       const float alpha = __builtin_amdgcn_exp2f(m_run[mt] - m_safe);
-      const float p0 = __builtin_amdgcn_exp2f(sv[mt][0] - m_safe), p1 = __builtin_amdgcn_exp2f(sv[mt][1] - m_safe);
-      const float p2 = __builtin_amdgcn_exp2f(sv[mt][2] - m_safe), p3 = __builtin_amdgcn_exp2f(sv[mt][3] - m_safe);
-      l_run[mt] = l_run[mt] * alpha + ((p0 + p1) + (p2 + p3));
+      float psum = 0.f;
+      uint32_t pk[4][2];
+#pragma unroll
+      for (int kt4 = 0; kt4 < 4; ++kt4) {
+        const float p0 = __builtin_amdgcn_exp2f(sv[mt][kt4][0] - m_safe), p1 = __builtin_amdgcn_exp2f(sv[mt][kt4][1] - m_safe);
+        const float p2 = __builtin_amdgcn_exp2f(sv[mt][kt4][2] - m_safe), p3 = __builtin_amdgcn_exp2f(sv[mt][kt4][3] - m_safe);
+        psum += (p0 + p1) + (p2 + p3);
+        pk[kt4][0] = pack_bf16x2(p0, p1);
+        pk[kt4][1] = pack_bf16x2(p2, p3);
+      }
+      l_run[mt] = l_run[mt] * alpha + psum;
       m_run[mt] = m_new;
       // after the first blocks the running maximum rarely moves: skip the rescale when no row of
       // this tile needs it (alpha is exactly 1 then)
       if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-        for (int dd = 0; dd < DPW; ++dd) o[mt][dd] *= alpha;
+        for (int dd = 0; dd < DT; ++dd) o[mt][dd] *= alpha;
       }
-      u32x2_t w;
-      w.x = pack_bf16x2(p0, p1);
-      w.y = pack_bf16x2(p2, p3);
-      *(u32x2_t*)(s_p + 16 * mt * PPITCH + p_wr_off) = w;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const u32x4_t w = {pk[2 * ks][0], pk[2 * ks][1], pk[2 * ks + 1][0], pk[2 * ks + 1][1]};
+        pf[mt][ks] = __builtin_bit_cast(bf16x8_t, w);
+      }
     }
-    // tiles: K of the next block (the K tile is free since barrier A), V of this block (the V tile
-    // was last read in block i-1, which every wavefront left before barrier A); then start the
-    // loads that will be parked one block from now
-    lstore(s_k, ch_dst_k, kreg);
-    lstore(s_v, ch_dst_v, vreg);
-    gload(i + 2, kc, kt, kreg);
-    gload(i + 1, vc, vt, vreg);
-    __syncthreads();        // B: probabilities, the V tile and the next K tile are visible
-    // ---- O^T += V^T P^T for this wavefront's slice of the head dimension ----
+    // ---- O^T += V^T P^T: reduction slots of step ks = keys 32*ks + 4*q4..+3 and 32*ks + 16 + 4*q4..+3 ----
 #pragma unroll
-    for (int ks = 0; ks < kBlkKeys / 32; ++ks) {
-      bf16x8_t pf[MT];
+    for (int dd = 0; dd < DT; ++dd) {
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        pf[mt] = *(const bf16x8_t*)(s_p + 16 * mt * PPITCH + p_rd_off + (((4 * ks + q4) ^ pswz) << 4));
-#pragma unroll
-      for (int dd = 0; dd < DPW; ++dd) {
-        const int r0 = 32 * ks + v_row, r1 = r0 + 4;
+      for (int ks = 0; ks < 2; ++ks) {
+        const int r0 = 32 * ks + v_row, r1 = r0 + 16;
         const short4_t v0 = lds_read_tr16(s_v + r0 * PITCH + (((v_chunk0 + 2 * dd) ^ swz_v(r0)) << 4) + v_half);
         const short4_t v1 = lds_read_tr16(s_v + r1 * PITCH + (((v_chunk0 + 2 * dd) ^ swz_v(r1)) << 4) + v_half);
         typedef short short8_t __attribute__((ext_vector_type(8)));
         const short8_t v8 = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
         const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, v8);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) o[mt][dd] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[mt], o[mt][dd], 0, 0, 0);
+        for (int mt = 0; mt < MTW; ++mt) o[mt][dd] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[mt][ks], o[mt][dd], 0, 0, 0);
       }
     }
-  }
-
-  // ---- totals of the soft-max denominators: over this lane's key slots, lanes, wavefronts ----
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    float l = l_run[mt];
-    l = rows_sum(l);
-    if (q4 == 0) s_sum[wave][16 * mt + i16] = l;
-  }
-  __syncthreads();
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    const int c = 16 * mt + i16;
-    l_run[mt] = (s_sum[0][c] + s_sum[1][c]) + (s_sum[2][c] + s_sum[3][c]);
+    __syncthreads();        // the next block's tiles are visible; every wavefront has left this block's
   }
 
   // ---- write: final output (single split) or the split's partial ----------------------------
@@ -376,28 +369,29 @@ __global__ __launch_bounds__(256, 2) void tree_attn_mfma_kernel(AttnArgs a) {
   typedef float float4v_t __attribute__((ext_vector_type(4)));
   uint16_t* og = (uint16_t*)a.out + ((size_t)b * a.Hq + (size_t)kvh * a.G) * T * D;
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
+  for (int mt = 0; mt < MTW; ++mt) {
+    const float l = rows_sum(l_run[mt]);                  // over this lane's key slots and its three partner lanes
     const int r = row0 + 16 * mt + i16;
     if (r >= R) continue;
-    const float inv = l_run[mt] > 0.f ? 1.0f / l_run[mt] : 0.f;
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
     if (a.n_splits == 1) {
 #pragma unroll
-      for (int dd = 0; dd < DPW; ++dd) {
+      for (int dd = 0; dd < DT; ++dd) {
         u32x2_t w;
         w.x = pack_bf16x2(o[mt][dd][0] * inv, o[mt][dd][1] * inv);
         w.y = pack_bf16x2(o[mt][dd][2] * inv, o[mt][dd][3] * inv);
-        *(u32x2_t*)(og + (size_t)r * D + 16 * (wave * DPW + dd) + 4 * q4) = w;
+        *(u32x2_t*)(og + (size_t)r * D + 16 * dd + 4 * q4) = w;
       }
     } else {
       const size_t unit = ((size_t)b * a.Hkv + kvh) * a.n_splits + split;
       uint64_t* prow = a.ws_o + (unit * R + r) * (D / 4);
 #pragma unroll
-      for (int dd = 0; dd < DPW; ++dd) {
+      for (int dd = 0; dd < DT; ++dd) {
         const float4v_t f = {o[mt][dd][0] * inv, o[mt][dd][1] * inv, o[mt][dd][2] * inv, o[mt][dd][3] * inv};
-        prow[4 * (wave * DPW + dd) + q4] = __builtin_bit_cast(uint64_t, __builtin_convertvector(f, half4_t));
+        prow[4 * dd + q4] = __builtin_bit_cast(uint64_t, __builtin_convertvector(f, half4_t));
       }
-      if (wave == 0 && q4 == 0) {
-        const f32x2_t ml = {m_run[mt], l_run[mt]};
+      if (q4 == 0) {
+        const f32x2_t ml = {m_run[mt], l};
         a.ws_ml[unit * R + r] = __builtin_bit_cast(uint64_t, ml);
       }
     }
@@ -438,20 +432,30 @@ __global__ __launch_bounds__(256) void tree_attn_combine_kernel(AttnArgs a) {
 }
 
 struct Plan {
-  int mt, row_blocks, n_splits;
+  int nw, row_blocks, n_splits;
 };
 
+// One tile of 16 query rows per wavefront, up to six wavefronts per workgroup; more rows are cut
+// into row blocks (which re-read K and V, from L2 when they run side by side).  Two tiles per
+// wavefront halve the LDS reads per row but measured slower (the per-block chain of a wavefront
+// doubles and one workgroup per CU has nothing to cover it with: 162 against 138 us at B = 16,
+// G = 4).
 Plan make_plan(int B, int Hq, int Hkv, int T, int Lcap) {
   Plan p;
   const int R = (Hq / Hkv) * T;
   const int tiles = ceil_div(R, 16);
-  p.mt = tiles >= 5 ? 5 : tiles;
-  p.row_blocks = ceil_div(tiles, p.mt);
+  p.row_blocks = ceil_div(tiles, 6);
+  p.nw = ceil_div(tiles, p.row_blocks);
+  p.row_blocks = ceil_div(tiles, p.nw);
   const int blocks = ceil_div(Lcap + T, kBlkKeys);
   const int base = B * Hkv * p.row_blocks;
-  // two workgroups fit on a CU: aim at ~2 x 256 of them, but keep at least four key blocks per
-  // split: each split costs a partial write and read of about 80 keys' worth of bytes
-  int want = 512 / base;
+  // One workgroup runs per CU.  A single sequence has splits of equal length: one round of at most
+  // 256 workgroups (8192 keys, 32 heads: 8 splits 39.5 us, 6 41.6, 10 53.6, 16 47.3).  A batch is
+  // ragged (the host does not know the lengths): about twice as many workgroups even out the long
+  // sequences (B = 4, 40 heads: 1/2/3/4 splits 50/47/43/47 us; B = 16, 8 KV heads x 3 row blocks:
+  // 138/122/123).  At least four key blocks per split: each split costs a partial write and read
+  // of about 80 keys' worth of bytes.
+  int want = B == 1 ? 256 / base : ceil_div(448, base);
   const int cap = blocks / 4 > 1 ? blocks / 4 : 1;
   want = want < 1 ? 1 : (want > cap ? cap : want);
   p.n_splits = ceil_div(blocks, ceil_div(blocks, want));
@@ -460,14 +464,14 @@ Plan make_plan(int B, int Hq, int Hkv, int T, int Lcap) {
 
 template <int D>
 int launch_mfma(const AttnArgs& a, const Plan& p, hipStream_t stream) {
-  const dim3 grid(a.n_splits, a.Hkv * a.row_blocks, a.B), block(256);
-  switch (p.mt) {
-    case 1: hipLaunchKernelGGL((tree_attn_mfma_kernel<D, 1>), grid, block, 0, stream, a); break;
-    case 2: hipLaunchKernelGGL((tree_attn_mfma_kernel<D, 2>), grid, block, 0, stream, a); break;
-    case 3: hipLaunchKernelGGL((tree_attn_mfma_kernel<D, 3>), grid, block, 0, stream, a); break;
-    case 4: hipLaunchKernelGGL((tree_attn_mfma_kernel<D, 4>), grid, block, 0, stream, a); break;
-    default: hipLaunchKernelGGL((tree_attn_mfma_kernel<D, 5>), grid, block, 0, stream, a); break;
+  const dim3 grid(a.n_splits, a.Hkv * a.row_blocks, a.B), block(64 * p.nw);
+#define MEDUSA_ATTN(NW_) \
+  case NW_: hipLaunchKernelGGL((tree_attn_rows_kernel<D, 1, NW_>), grid, block, 0, stream, a); break
+  switch (p.nw) {
+    MEDUSA_ATTN(1); MEDUSA_ATTN(2); MEDUSA_ATTN(3); MEDUSA_ATTN(4); MEDUSA_ATTN(5); MEDUSA_ATTN(6);
+    default: return MEDUSA_EUNSUPPORTED;
   }
+#undef MEDUSA_ATTN
   MEDUSA_LAUNCH_CHECK();
   if (a.n_splits > 1) {
     hipLaunchKernelGGL((tree_attn_combine_kernel<D>), dim3(ceil_div(a.R * (D / 4), 256), a.Hkv, a.B), dim3(256), 0,
