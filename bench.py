@@ -219,7 +219,8 @@ def bench_block(args, cfg):
     rnd = lambda *shape, std=1.0: (torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32) * std).to(dt)
     sets = []
     for _ in range(n_sets):
-        sets.append(dict(wq=rnd(Hq * D, h, std=h ** -0.5), wk=rnd(Hkv * D, h, std=h ** -0.5), wv=rnd(Hkv * D, h, std=h ** -0.5),
+        wqkv = rnd((Hq + 2 * Hkv) * D, h, std=h ** -0.5)     # one allocation: the block fuses the three projections at B = 1
+        sets.append(dict(wq=wqkv[:Hq * D], wk=wqkv[Hq * D:(Hq + Hkv) * D], wv=wqkv[(Hq + Hkv) * D:],
                          wu=rnd(inter, Hq * D, std=h ** -0.5), wg=rnd(inter, Hq * D, std=h ** -0.5),
                          wd=rnd(h, inter, std=inter ** -0.5), kc=rnd(B, Hkv, cfg.Lcap, D), vc=rnd(B, Hkv, cfg.Lcap, D)))
     x = rnd(B * T, h)
@@ -253,10 +254,12 @@ def bench_block(args, cfg):
     total = w_bytes + act_bytes + kv_bytes
     flops = 2.0 * M_rows * (Hq * D * h + 2 * Hkv * D * h + 2 * inter * Hq * D + h * inter) + 4.0 * B * Hq * T * (mean_L + T) * D
     if args.breakdown:
-        names = ["X W_Q", "X W_K", "X W_V", "rotary", "QK^T, PV", "X W_u", "X W_g", "X W_d"]
         stream = torch.cuda.current_stream().cuda_stream
         plans = [blk._calls(x, w["wq"], w["wk"], w["wv"], w["wu"], w["wg"], w["wd"], w["kc"], w["vc"], pl, pos, scale)
                  for w in sets]
+        names = ["X W_Q", "X W_K", "X W_V", "rotary", "QK^T, PV", "X W_u", "X W_g", "X W_d"]
+        if len(plans[0]) == 6:
+            names = ["X W_QKV"] + names[3:]
         for j, name in enumerate(names):
             for i in range(5):
                 _, fn, a = plans[i % n_sets][j]

@@ -2,7 +2,11 @@
 X W_Q, X W_K, X W_V (tree_linear), rotary embedding at the tree positions (tree_rope), Q K^T and
 P V against the cache (tree_attention), X W_u, X W_g, X W_d (tree_linear).  Buffers are allocated
 once and the calls' arguments are marshalled once per set of operands; ``run`` only launches
-kernels.  Argument marshalling only -- every operator runs in the HIP library."""
+kernels.  Argument marshalling only -- every operator runs in the HIP library.
+
+With one sequence, and W_Q, W_K, W_V handed in as consecutive row blocks of one allocation (views
+of a [(Hq + 2 Hkv) D, h] tensor), the three projections are one tree_linear call: its head-major
+output [1, Hq + 2 Hkv, T, D] is q, k and v back to back."""
 from __future__ import annotations
 
 import torch
@@ -17,12 +21,17 @@ class SimplifiedBlock:
         self.h, self.Hq, self.Hkv, self.D, self.inter, self.Lcap, self.theta = h, Hq, Hkv, D, inter, Lcap, theta
         T = tree.T
         mk = lambda *shape: torch.empty(shape, dtype=dtype, device=device)
-        self.q, self.k, self.v = mk(B, Hq, T, D), mk(B, Hkv, T, D), mk(B, Hkv, T, D)
+        if B == 1:
+            self.qkv = mk(1, Hq + 2 * Hkv, T, D)
+            self.q, self.k, self.v = self.qkv[:, :Hq], self.qkv[:, Hq:Hq + Hkv], self.qkv[:, Hq + Hkv:]
+        else:
+            self.qkv = None
+            self.q, self.k, self.v = mk(B, Hq, T, D), mk(B, Hkv, T, D), mk(B, Hkv, T, D)
         self.attn = mk(B, Hq, T, D)
         self.up, self.act, self.out = mk(B * T, inter), mk(B * T, inter), mk(B * T, h)
         self.ws = _b._scratch(_b.tree_attention_workspace_bytes(B, Hq, Hkv, T, D, Lcap), device)
         need = max(_b.tree_linear_workspace_bytes(B, T, d_in, d_out, dtype)
-                   for d_in, d_out in ((h, Hq * D), (h, Hkv * D), (Hq * D, inter), (inter, h)))
+                   for d_in, d_out in ((h, Hq * D), (h, Hkv * D), (h, (Hq + 2 * Hkv) * D), (Hq * D, inter), (inter, h)))
         self.ws_lin = _b._scratch(need, device)
         self._plans = {}
 
@@ -46,10 +55,15 @@ class SimplifiedBlock:
         lin = lambda xin, w, mul, y, d_in, d_out, xh, yh: (
             "tree_linear", L.tree_linear, (p(xin), p(w), None if mul is None else p(mul), p(y), B, T, d_in, d_out, xh, yh,
                                            code, p(self.ws_lin), nb(self.ws_lin)))
-        plan = [
-            lin(x, wq, None, self.q, h, Hq * D, 0, Hq),
-            lin(x, wk, None, self.k, h, Hkv * D, 0, Hkv),
-            lin(x, wv, None, self.v, h, Hkv * D, 0, Hkv),
+        nbytes = lambda t: t.numel() * t.element_size()
+        fused = (self.qkv is not None and wk.data_ptr() == wq.data_ptr() + nbytes(wq)
+                 and wv.data_ptr() == wk.data_ptr() + nbytes(wk))
+        if fused:
+            qkv_calls = [lin(x, wq, None, self.qkv, h, (Hq + 2 * Hkv) * D, 0, Hq + 2 * Hkv)]
+        else:
+            qkv_calls = [lin(x, wq, None, self.q, h, Hq * D, 0, Hq), lin(x, wk, None, self.k, h, Hkv * D, 0, Hkv),
+                         lin(x, wv, None, self.v, h, Hkv * D, 0, Hkv)]
+        plan = qkv_calls + [
             ("tree_rope", L.tree_rope, (p(self.q), p(self.k), p(position_ids), B, Hq, Hkv, T, D, float(self.theta), code)),
             ("tree_attention", L.tree_attention, (p(self.q), p(self.k), p(self.v), p(k_cache), p(v_cache), p(prefix_len),
                                                   self.tree.handle, p(self.attn), B, Hq, Hkv, D, self.Lcap, float(scale),

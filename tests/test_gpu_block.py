@@ -102,7 +102,7 @@ def test_rope(dtype, D, maxpos):
         assert err <= TOL[dtype], f"tree_rope rel err {err}"
 
 
-def block_case(dtype, branching, B, h, Hq, Hkv, D, inter, Lcap, prefix, seed):
+def block_case(dtype, branching, B, h, Hq, Hkv, D, inter, Lcap, prefix, seed, adjacent_qkv=False):
     tree_o = O.tree_cartesian(branching)
     tree_g = M.MedusaTree(branching=branching)
     T = tree_o.T
@@ -116,8 +116,14 @@ def block_case(dtype, branching, B, h, Hq, Hkv, D, inter, Lcap, prefix, seed):
     pos = (pl[:, None] + np.asarray(tree_o.depth, np.int32)[None, :]).astype(np.int32)
     scale, theta = 1.0 / math.sqrt(D), 10000.0
     blk = SimplifiedBlock(tree_g, B, h, Hq, Hkv, D, inter, Lcap, torch.bfloat16 if dtype == "bf16" else torch.float32)
-    out = blk.run(to_dev(x), *(to_dev(ws[n]) for n in ("wq", "wk", "wv", "wu", "wg", "wd")), to_dev(kc), to_dev(vc),
+    dw = {n: to_dev(ws[n]) for n in ("wq", "wk", "wv", "wu", "wg", "wd")}
+    if adjacent_qkv:      # W_Q, W_K, W_V as consecutive row blocks of one allocation: one projection call at B = 1
+        wqkv = torch.cat([dw["wq"], dw["wk"], dw["wv"]], dim=0)
+        dw["wq"], dw["wk"], dw["wv"] = wqkv[:Hq * D], wqkv[Hq * D:(Hq + Hkv) * D], wqkv[(Hq + Hkv) * D:]
+    out = blk.run(to_dev(x), *(dw[n] for n in ("wq", "wk", "wv", "wu", "wg", "wd")), to_dev(kc), to_dev(vc),
                   to_dev(pl), to_dev(pos), scale)
+    if adjacent_qkv and B == 1:
+        assert len(blk._plans) == 1 and len(next(iter(blk._plans.values()))) == 6      # the fused form did run
     torch.cuda.synchronize()
     ref = O.simplified_block_ref(x, ws["wq"], ws["wk"], ws["wv"], ws["wu"], ws["wg"], ws["wd"], kc, vc, pl, pos, tree_o,
                                  Hq, Hkv, scale, theta, dtype)
@@ -152,3 +158,8 @@ def test_block_bf16_gqa_ragged():
 
 def test_block_bf16_head_dim_128():
     block_case("bf16", (2, 2, 1), 1, 512, 4, 4, 128, 768, 400, [300], 602)
+
+
+def test_block_bf16_fused_qkv_projection():
+    block_case("bf16", (4, 3, 2, 1), 1, 512, 8, 2, 64, 1024, 300, [200], 603, adjacent_qkv=True)
+    block_case("bf16", (2, 2, 1), 1, 512, 4, 4, 128, 768, 400, [300], 604, adjacent_qkv=True)
