@@ -304,9 +304,10 @@ def bench_speed_model(args, cfg):
     gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
     rnd = lambda *shp, std=1.0: (torch.randn(shp, generator=gen, device="cuda", dtype=torch.float32) * std).to(dt)
     n_sets = 6
-    wsets = [dict(wq=rnd(Hq * D, h, std=h ** -0.5), wk=rnd(Hkv * D, h, std=h ** -0.5), wv=rnd(Hkv * D, h, std=h ** -0.5),
+    qkv = [rnd((Hq + 2 * Hkv) * D, h, std=h ** -0.5) for _ in range(n_sets)]      # one allocation per set (fused at batch 1)
+    wsets = [dict(wq=qkv[i][:Hq * D], wk=qkv[i][Hq * D:(Hq + Hkv) * D], wv=qkv[i][(Hq + Hkv) * D:],
                   wu=rnd(inter, Hq * D, std=h ** -0.5), wg=rnd(inter, Hq * D, std=h ** -0.5), wd=rnd(h, inter, std=inter ** -0.5))
-             for _ in range(n_sets)]
+             for i in range(n_sets)]
     qs = [1, 16, 32, 48, 64, 80, 96, 112]
     acc = synthetic_accuracy_table(5, 10)
     trees = {q: (M.MedusaTree(nodes=[]) if q == 1 else M.MedusaTree(accuracy=acc, n_nodes=q - 1)) for q in qs}

@@ -729,14 +729,23 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
   // Cold weights want long runs per row (15-19 % faster at M = 8..64, 10 % at 65..80); weights that
   // the last-level cache holds want the short-stage kernel (3-8 % faster there).
   p.runs = p.wide && (size_t)K * N * d * sizeof(uint16_t) > g_llc_bytes;
-  if (!have_ws) return p;
-  // Split the reduction only when the unsplit kernel would leave most of the chip idle (under 128
+  // Split the reduction only when the unsplit kernel would leave most of the chip idle (under 160
   // tiles): into the largest power of two of workgroups per tile that leaves each at least 16 steps
   // and the launch at most ~640 workgroups.  Measured at M = 65 (us, splits 1/2/4/8):
   // N = 4096, d = 4096: 25/24/18/19;  N = 4096, d = 11008: 67/54/36/35;  N = 5120, d = 13824: 83/65/57/54;
-  // N = 11008, d = 4096: 32/37/36/45;  N = 13824, d = 5120: 41/48/53/63.
+  // N = 11008, d = 4096: 32/37/36/45;  N = 13824, d = 5120: 41/48/53/63;  and with two or three row
+  // blocks at N = d = 4096 (splits 1/2/4): M = 192 (128 tiles) 30/28/27, M = 260 (192 tiles) 31/38/42.
   const long tiles = (long)ceil_div(N, p.wide ? 128 : 64) * K * p.m_blocks;
-  if (tiles >= 128) return p;
+  if (!have_ws || tiles >= 160) {
+    // Unsplit.  With seven or eight row groups per workgroup the kernel runs out of registers for its
+    // prefetch: one more row block then, if the launch stays within one workgroup per CU (M = 256,
+    // N = d = 4096: 38 -> 31 us; N = 4096, d = 11008: 91 -> 75; but N = 11008, d = 4096: 78 -> 91).
+    if (!p.wide && p.mt >= 7 && tiles / p.m_blocks * (p.m_blocks + 1) <= 256) {
+      p.m_blocks += 1;
+      p.mt = ceil_div(ceil_div(M, p.m_blocks), 16);
+    }
+    return p;
+  }
   long cap = 640 / tiles;
   const long by_steps = (d / 64) / 16;
   cap = cap < by_steps ? cap : by_steps;
