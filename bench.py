@@ -223,6 +223,8 @@ def bench_block(args, cfg):
         sets.append(dict(wq=wqkv[:Hq * D], wk=wqkv[Hq * D:(Hq + Hkv) * D], wv=wqkv[(Hq + Hkv) * D:],
                          wu=rnd(inter, Hq * D, std=h ** -0.5), wg=rnd(inter, Hq * D, std=h ** -0.5),
                          wd=rnd(h, inter, std=inter ** -0.5), kc=rnd(B, Hkv, cfg.Lcap, D), vc=rnd(B, Hkv, cfg.Lcap, D)))
+        # bf16: gate and up in one call over interleaved weights (the separate matrices are then not read)
+        sets[-1]["wgu"] = M.interleave_gate_up(sets[-1]["wg"], sets[-1]["wu"]) if dt == torch.bfloat16 else None
     x = rnd(B * T, h)
     pl = torch.randint(cfg.L_min, cfg.L_max + 1, (B,), generator=gen, device="cuda", dtype=torch.int32)
     depth = torch.from_numpy(tree.depth).to(device="cuda", dtype=torch.int32)
@@ -232,7 +234,7 @@ def bench_block(args, cfg):
 
     def run(i):
         w = sets[i % n_sets]
-        blk.run(x, w["wq"], w["wk"], w["wv"], w["wu"], w["wg"], w["wd"], w["kc"], w["vc"], pl, pos, scale)
+        blk.run(x, w["wq"], w["wk"], w["wv"], w["wu"], w["wg"], w["wd"], w["kc"], w["vc"], pl, pos, scale, w["wgu"])
 
     K, W = args.steps, args.warmup
     for i in range(W):
@@ -249,17 +251,19 @@ def bench_block(args, cfg):
     M_rows = B * T
     w_bytes = (Hq * D * h + 2 * Hkv * D * h + 2 * inter * Hq * D + h * inter) * es
     act_bytes = (3 * M_rows * h + 2 * M_rows * (Hq + 2 * Hkv) * D + 2 * M_rows * Hq * D + 3 * M_rows * Hq * D
-                 + 4 * M_rows * inter + M_rows * h) * es
+                 + (2 if dt == torch.bfloat16 and M_rows <= 80 else 4) * M_rows * inter + M_rows * h) * es   # (fused gate/up: no `up` round trip)
     kv_bytes = int(2 * B * Hkv * mean_L * D * es)
     total = w_bytes + act_bytes + kv_bytes
     flops = 2.0 * M_rows * (Hq * D * h + 2 * Hkv * D * h + 2 * inter * Hq * D + h * inter) + 4.0 * B * Hq * T * (mean_L + T) * D
     if args.breakdown:
         stream = torch.cuda.current_stream().cuda_stream
-        plans = [blk._calls(x, w["wq"], w["wk"], w["wv"], w["wu"], w["wg"], w["wd"], w["kc"], w["vc"], pl, pos, scale)
+        plans = [blk._calls(x, w["wq"], w["wk"], w["wv"], w["wu"], w["wg"], w["wd"], w["kc"], w["vc"], pl, pos, scale, w["wgu"])
                  for w in sets]
-        names = ["X W_Q", "X W_K", "X W_V", "rotary", "QK^T, PV", "X W_u", "X W_g", "X W_d"]
-        if len(plans[0]) == 6:
-            names = ["X W_QKV"] + names[3:]
+        names = [{"tree_rope": "rotary", "tree_attention": "QK^T, PV", "tree_linear_swiglu": "X W_u, W_g"}.get(c[0], c[0])
+                 for c in plans[0]]
+        lin_names = (["X W_QKV"] if names.index("rotary") == 1 else ["X W_Q", "X W_K", "X W_V"]) + (
+            ["X W_d"] if "X W_u, W_g" in names else ["X W_u", "X W_g", "X W_d"])
+        names = [lin_names.pop(0) if nm == "tree_linear" else nm for nm in names]
         for j, name in enumerate(names):
             for i in range(5):
                 _, fn, a = plans[i % n_sets][j]
@@ -308,6 +312,8 @@ def bench_speed_model(args, cfg):
     wsets = [dict(wq=qkv[i][:Hq * D], wk=qkv[i][Hq * D:(Hq + Hkv) * D], wv=qkv[i][(Hq + Hkv) * D:],
                   wu=rnd(inter, Hq * D, std=h ** -0.5), wg=rnd(inter, Hq * D, std=h ** -0.5), wd=rnd(h, inter, std=inter ** -0.5))
              for i in range(n_sets)]
+    for w in wsets:
+        w["wgu"] = M.interleave_gate_up(w["wg"], w["wu"])
     qs = [1, 16, 32, 48, 64, 80, 96, 112]
     acc = synthetic_accuracy_table(5, 10)
     trees = {q: (M.MedusaTree(nodes=[]) if q == 1 else M.MedusaTree(accuracy=acc, n_nodes=q - 1)) for q in qs}
@@ -330,7 +336,8 @@ def bench_speed_model(args, cfg):
             def run(i):
                 w = wsets[i % n_sets]
                 kc, vc = caches[i % len(caches)]
-                blk.run(x, w["wq"], w["wk"], w["wv"], w["wu"], w["wg"], w["wd"], kc, vc, pl, pos, scale)
+                blk.run(x, w["wq"], w["wk"], w["wv"], w["wu"], w["wg"], w["wd"], kc, vc, pl, pos, scale,
+                        w["wgu"] if B * T > 4 else None)      # (plain decoding keeps the wave-per-row kernels; the block falls back to two calls above 80 rows)
 
             for i in range(12):
                 run(i)

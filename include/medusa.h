@@ -247,6 +247,19 @@ int tree_linear(const void* x, const void* w, const void* mul, void* y, int B, i
 int tree_rope(void* q, void* k, const int32_t* position_ids, int B, int Hq, int Hkv, int T, int D, float theta,
               medusa_dtype_t dtype, medusa_stream_t stream);
 
+/* Gate and up projections of the gated feed-forward in one pass (App. G, operator table, rows
+ * X W_g and X W_u): y = SiLU(x w_g^T) * (x w_u^T), rounded once, with no intermediate in memory.
+ *   x     [B*T, d_in] token-major, or head-major [B, x_heads, T, d_in/x_heads] when x_heads > 0
+ *   w_gu  [2*d_out, d_in]: the rows of w_g and w_u interleaved in blocks of 16 -- rows 32b..32b+15
+ *         are rows 16b..16b+15 of w_g, rows 32b+16..32b+31 the same rows of w_u (a layout the caller
+ *         prepares once per weight pair)
+ *   y     [B*T, d_out] token-major, or head-major [B, y_heads, T, d_out/y_heads] when y_heads > 0
+ * All device pointers, caller-owned.  bf16 only (MEDUSA_EUNSUPPORTED for fp32: two tree_linear calls
+ * do the same there); d_in a multiple of 64, d_out a multiple of 16, B*T <= 4096.  Tuned for the
+ * tree-token range of rows (5..80 per launch block); correct for any row count. */
+int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int B, int T, int d_in, int d_out, int x_heads,
+                       int y_heads, medusa_dtype_t dtype, medusa_stream_t stream);
+
 /* ----------------------------------------------------------------------------------
  * Tuning knob (no counterpart in the paper).  The MFMA kernels of medusa_heads and tree_linear
  * for 5..80 rows come in two forms: one is faster when the weight matrix is still in the GPU's

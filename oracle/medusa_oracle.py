@@ -395,6 +395,14 @@ def tree_linear_ref(x, w, dtype: str, mul=None):
     return round_to_storage(y, dtype)
 
 
+def tree_swiglu_ref(x, w_gate, w_up, dtype: str):
+    """The gated feed-forward's inner product of App. G's operator table (X W_g and X W_u), combined
+    as the Llama family does: SiLU(x w_gate^T) * (x w_up^T), with no rounding of either projection
+    on the way; result [M, d_out] rounded once to the storage dtype."""
+    xv = widen(x)
+    return round_to_storage(silu(xv @ widen(w_gate).T) * (xv @ widen(w_up).T), dtype)
+
+
 def rope_ref(x, position_ids, theta: float, dtype: str):
     """Rotary position embedding at the tree's positional indices (Sec. 2.1.2: the indices follow
     the tree structure, i.e. position = prefix length + depth of the node; they are an input

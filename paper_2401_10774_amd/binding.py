@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = (
     "medusa_tree_create_optimized", "medusa_tree_destroy",
     "medusa_tree_query", "medusa_tree_tables", "medusa_heads", "medusa_topk_tree_workspace_bytes",
     "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "medusa_accept_workspace_bytes",
-    "medusa_accept", "kv_commit", "tree_linear_workspace_bytes", "tree_linear", "tree_rope",
+    "medusa_accept", "kv_commit", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_swiglu", "tree_rope",
     "medusa_profile_set_events",
     "medusa_set_cache_resident_bytes",
 )
@@ -72,6 +72,7 @@ def lib() -> ctypes.CDLL:
         L.tree_linear_workspace_bytes.restype = c_size_t
         L.tree_linear_workspace_bytes.argtypes = [c_int] * 5
         L.tree_linear.argtypes = [c_void_p] * 4 + [c_int] * 7 + [c_void_p, c_size_t, c_void_p]
+        L.tree_linear_swiglu.argtypes = [c_void_p] * 3 + [c_int] * 7 + [c_void_p]
         L.tree_rope.argtypes = [c_void_p] * 3 + [c_int] * 5 + [c_float, c_int, c_void_p]
         L.medusa_profile_set_events.argtypes = [c_void_p, c_void_p]
         L.medusa_set_cache_resident_bytes.argtypes = [ctypes.c_size_t]
@@ -366,6 +367,40 @@ def tree_linear(x: torch.Tensor, w: torch.Tensor, B: int, T: int, mul: Optional[
                              None if workspace is None else workspace.data_ptr(),
                              0 if workspace is None else workspace.numel() * workspace.element_size(),
                              _stream(stream)), "tree_linear")
+    return y
+
+
+def interleave_gate_up(w_gate: torch.Tensor, w_up: torch.Tensor) -> torch.Tensor:
+    """The weight layout tree_linear_swiglu reads: blocks of 16 gate rows followed by the same 16 rows
+    of the up projection.  [d_out, d_in] x 2 -> [2*d_out, d_in]; d_out a multiple of 16."""
+    d_out, d_in = w_gate.shape
+    if w_up.shape != w_gate.shape or d_out % 16 != 0:
+        raise MedusaError("gate and up weights must have the same shape, rows a multiple of 16")
+    return torch.stack((w_gate.view(d_out // 16, 16, d_in), w_up.view(d_out // 16, 16, d_in)), dim=1).reshape(2 * d_out, d_in).contiguous()
+
+
+def tree_linear_swiglu(x: torch.Tensor, w_gu: torch.Tensor, B: int, T: int, y: Optional[torch.Tensor] = None,
+                       y_heads: int = 0, stream=None) -> torch.Tensor:
+    """y = SiLU(x w_g^T) * (x w_u^T) in one pass; w_gu = interleave_gate_up(w_g, w_u).  x token-major
+    [B*T, d_in] or head-major [B, H, T, Dh]; y token-major [B*T, d_out] or head-major."""
+    code = _dtype_code(x)
+    d_out, d_in = w_gu.shape[0] // 2, w_gu.shape[1]
+    _dev(w_gu, "w_gu", dtype=x.dtype, shape=(2 * d_out, d_in))
+    x_heads = 0
+    if x.dim() == 4:
+        if x.shape[0] != B or x.shape[2] != T or x.shape[1] * x.shape[3] != d_in:
+            raise MedusaError("head-major x must be [B, H, T, d_in/H]")
+        x_heads = int(x.shape[1])
+        _dev(x, "x", dtype=x.dtype)
+    else:
+        _dev(x, "x", dtype=x.dtype, shape=(B * T, d_in))
+    if y is None:
+        y = torch.empty((B, y_heads, T, d_out // y_heads) if y_heads > 0 else (B * T, d_out), dtype=x.dtype, device=x.device)
+    _dev(y, "y", dtype=x.dtype)
+    if y.numel() != B * T * d_out:
+        raise MedusaError("y has the wrong number of elements")
+    _check(lib().tree_linear_swiglu(x.data_ptr(), w_gu.data_ptr(), y.data_ptr(), B, T, d_in, d_out, x_heads, y_heads, code,
+                                    _stream(stream)), "tree_linear_swiglu")
     return y
 
 

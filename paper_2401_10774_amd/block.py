@@ -6,7 +6,9 @@ kernels.  Argument marshalling only -- every operator runs in the HIP library.
 
 With one sequence, and W_Q, W_K, W_V handed in as consecutive row blocks of one allocation (views
 of a [(Hq + 2 Hkv) D, h] tensor), the three projections are one tree_linear call: its head-major
-output [1, Hq + 2 Hkv, T, D] is q, k and v back to back."""
+output [1, Hq + 2 Hkv, T, D] is q, k and v back to back.  With ``w_gu`` (binding.interleave_gate_up
+of W_g and W_u) given and at most 80 tree tokens in all, X W_u and X W_g are one
+tree_linear_swiglu call and ``self.up`` is not produced."""
 from __future__ import annotations
 
 import torch
@@ -35,8 +37,9 @@ class SimplifiedBlock:
         self.ws_lin = _b._scratch(need, device)
         self._plans = {}
 
-    def _calls(self, x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale):
-        key = tuple(t.data_ptr() for t in (x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids)) + (scale,)
+    def _calls(self, x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale, w_gu=None):
+        key = tuple(t.data_ptr() for t in (x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids)) + (
+            scale, None if w_gu is None else w_gu.data_ptr())
         plan = self._plans.get(key)
         if plan is not None:
             return plan
@@ -68,19 +71,24 @@ class SimplifiedBlock:
             ("tree_attention", L.tree_attention, (p(self.q), p(self.k), p(self.v), p(k_cache), p(v_cache), p(prefix_len),
                                                   self.tree.handle, p(self.attn), B, Hq, Hkv, D, self.Lcap, float(scale),
                                                   code, p(self.ws), nb(self.ws))),
-            lin(self.attn, wu, None, self.up, Hq * D, inter, Hq, 0),
-            lin(self.attn, wg, self.up, self.act, Hq * D, inter, Hq, 0),
-            lin(self.act, wd, None, self.out, inter, h, 0, 0),
         ]
+        if w_gu is not None and B * T <= 80:       # (one row block of the fused kernel; beyond, two calls are faster)
+            _b._dev(w_gu, "w_gu", dtype=dt, shape=(2 * inter, Hq * D))
+            plan.append(("tree_linear_swiglu", L.tree_linear_swiglu, (p(self.attn), p(w_gu), p(self.act), B, T, Hq * D, inter,
+                                                                      Hq, 0, code)))
+        else:
+            plan += [lin(self.attn, wu, None, self.up, Hq * D, inter, Hq, 0),
+                     lin(self.attn, wg, self.up, self.act, Hq * D, inter, Hq, 0)]
+        plan.append(lin(self.act, wd, None, self.out, inter, h, 0, 0))
         self._plans[key] = plan
         return plan
 
-    def run(self, x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale: float):
+    def run(self, x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale: float, w_gu=None):
         """x [B*T, h]; weights out x in; k_cache, v_cache [B, Hkv, Lcap, D] of one layer.  Enqueues the
         block on the current stream and returns its output [B*T, h]; intermediates stay in
         self.q/k/v/attn/up/act."""
         stream = torch.cuda.current_stream().cuda_stream
-        for name, fn, args in self._calls(x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale):
+        for name, fn, args in self._calls(x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale, w_gu):
             rc = fn(*args, stream)
             if rc != 0:
                 _b._check(rc, name)

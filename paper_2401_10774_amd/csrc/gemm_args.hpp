@@ -7,7 +7,10 @@
 //            EPI_RESID   dtype  out[m][k][n] = SiLU(acc) + hidden[m][n]   (residual block of a head)
 //            EPI_PLAIN   dtype  out(m, n)    = acc                        (backbone linear layers)
 //            EPI_GATED   dtype  out(m, n)    = SiLU(acc) * mul[m][n]      (gate projection times up projection)
-enum { EPI_LOGITS = 0, EPI_RESID = 1, EPI_PLAIN = 2, EPI_GATED = 3 };
+//            EPI_SWIGLU  dtype  out(m, c)    = SiLU(acc(m, gate row of c)) * acc(m, up row of c): W holds gate and up
+//                               rows interleaved in blocks of 16 (rows 32b..32b+15 gate, 32b+16..32b+31 up, of
+//                               output columns 16b..16b+15); out has N/2 columns.  128-column skinny tiles only.
+enum { EPI_LOGITS = 0, EPI_RESID = 1, EPI_PLAIN = 2, EPI_GATED = 3, EPI_SWIGLU = 4 };
 
 // acc[m][n] = sum_j W[k][n][j] * X(m, k, j)
 // X is either row-major with strides (x_dh == 0): X[m*xs_m + k*xs_k + j], or head-major
@@ -34,7 +37,7 @@ struct GemmArgs {
 // The head-major forms exist only for the epilogues tree_linear uses (HM): the kernels of
 // medusa_heads are compiled without them.
 template <int EPI>
-constexpr bool kHeadMajor = EPI == 2 || EPI == 3;      // EPI_PLAIN, EPI_GATED
+constexpr bool kHeadMajor = EPI == 2 || EPI == 3 || EPI == 4;      // EPI_PLAIN, EPI_GATED, EPI_SWIGLU
 
 template <bool HM>
 __device__ __forceinline__ size_t x_row_offset(const GemmArgs& a, int m, int k) {

@@ -213,6 +213,26 @@ __device__ __forceinline__ void finish_tile(const GemmArgs& a, floatx4_t (&acc)[
     }
   }
 
+  if constexpr (EPI == EPI_SWIGLU) {
+    // the wavefront's two fragments are the gate rows and the up rows of output columns 16b..16b+15
+    static_assert(NT == 2, "gate and up fragments side by side");
+    const int n = (n0 >> 1) + wn * 16 + i16, n_out = a.N >> 1;
+    if (n >= n_out) return;
+    const size_t col = out_col_offset<true>(a, n);
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+      const int mb = m0 + (wm * MT + t) * 16 + 4 * q4;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (mb + r >= a.M) continue;
+        const float g = acc[t][0][r], u = acc[t][1][r];
+        const float v = g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g)) * u;
+        const size_t row = a.y_dh == 0 ? (size_t)(mb + r) * n_out : out_row_offset<true>(a, mb + r, k);
+        store_from_float<uint16_t>((uint16_t*)a.out + row + col, v);
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int t = 0; t < MT; ++t)
 #pragma unroll
@@ -941,6 +961,58 @@ extern "C" int tree_linear(const void* x, const void* w, const void* mul, void* 
     a.ws = workspace;
   hipStream_t stream = (hipStream_t)stream_;
   return mul ? launch_gemm<EPI_GATED>(a, dtype, stream) : launch_gemm<EPI_PLAIN>(a, dtype, stream);
+}
+
+// Gate and up projections of the gated feed-forward in one pass over both weight matrices (App. G,
+// operator table: X W_g and X W_u; the product SiLU(X W_g) * (X W_u) is what X W_d consumes).
+extern "C" int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int B, int T, int d_in, int d_out, int x_heads,
+                                  int y_heads, medusa_dtype_t dtype, medusa_stream_t stream_) {
+  if (!x || !w_gu || !y) return MEDUSA_EINVAL;
+  if (B < 1 || T < 1 || d_in < 1 || d_out < 1 || x_heads < 0 || y_heads < 0) return MEDUSA_EINVAL;
+  if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;
+  if (dtype != MEDUSA_BF16) return MEDUSA_EUNSUPPORTED;            // (fp32 callers use two tree_linear calls)
+  const long M = (long)B * T;
+  if (M > 4096 || d_in > 65536 || d_out > (1 << 24)) return MEDUSA_EUNSUPPORTED;
+  if (d_in % 64 != 0 || d_out % 16 != 0) return MEDUSA_EUNSUPPORTED;
+  if (x_heads > 0 && (d_in % x_heads != 0 || (d_in / x_heads) % 64 != 0)) return MEDUSA_EUNSUPPORTED;
+  if (y_heads > 0 && d_out % y_heads != 0) return MEDUSA_EINVAL;
+  GemmArgs a = {};
+  a.W = w_gu;
+  a.X = x;
+  a.out = y;
+  a.M = (int)M;
+  a.N = 2 * d_out;
+  a.d = d_in;
+  a.K = 1;
+  a.xs_m = d_in;
+  a.ksplit = 1;
+  if (x_heads > 0) {
+    a.x_T = T;
+    a.x_heads = x_heads;
+    a.x_dh = d_in / x_heads;
+  }
+  if (y_heads > 0) {
+    a.y_T = T;
+    a.y_heads = y_heads;
+    a.y_dh = d_out / y_heads;
+  }
+  // 128-column tiles (gate and up fragments of a column block side by side in a wavefront), row blocks
+  // of at most 80 rows, never split: tuned for the tree-token range, correct for any M
+  const int m_blocks = ceil_div(a.M, 80), mt = ceil_div(ceil_div(a.M, m_blocks), 16);
+  const dim3 grid(ceil_div(a.N, 128), 1, m_blocks);
+  const bool runs = (size_t)a.N * a.d * sizeof(uint16_t) > g_llc_bytes;
+  hipStream_t stream = (hipStream_t)stream_;
+  int rc = MEDUSA_OK;
+#define MEDUSA_SWIGLU(MT_)                                                                                                \
+  case MT_:                                                                                                               \
+    if (runs) rc = launch_skinny<gemm_runs_bf16_kernel<MT_, (MT_ <= 2 ? 4 : 2), EPI_SWIGLU>>(grid, (size_t)(MT_ * 16 + 64) * 1024, stream, a); \
+    else rc = launch_skinny<gemm_skinny_bf16_kernel<MT_, 8, skinny_depth(MT_, 8), EPI_SWIGLU>>(grid, (size_t)2 * (MT_ + 8) * 4096, stream, a); \
+    break;
+  switch (mt) { MEDUSA_SWIGLU(1) MEDUSA_SWIGLU(2) MEDUSA_SWIGLU(3) MEDUSA_SWIGLU(4) MEDUSA_SWIGLU(5) default: return MEDUSA_EUNSUPPORTED; }
+#undef MEDUSA_SWIGLU
+  if (rc != MEDUSA_OK) return rc;
+  MEDUSA_LAUNCH_CHECK();
+  return MEDUSA_OK;
 }
 
 extern "C" int medusa_set_cache_resident_bytes(size_t bytes) {

@@ -72,6 +72,54 @@ def test_linear_bf16_long_run_kernel():
         M.medusa_set_cache_resident_bytes(256 << 20)
 
 
+def interleave16(wg, wu):
+    """Blocks of 16 gate rows followed by the same 16 up rows (numpy, independent of the library's helper)."""
+    n, d = wg.shape
+    out = np.empty((2 * n, d), wg.dtype)
+    for b in range(n // 16):
+        out[32 * b:32 * b + 16] = wg[16 * b:16 * b + 16]
+        out[32 * b + 16:32 * b + 32] = wu[16 * b:16 * b + 16]
+    return out
+
+
+@pytest.mark.parametrize("B,T,d_in,d_out,x_heads,y_heads,cold", [
+    (1, 65, 512, 384, 0, 0, False), (1, 65, 512, 384, 4, 0, True), (2, 50, 256, 1008, 0, 3, False),
+    (1, 5, 192, 64, 0, 0, False), (1, 1, 128, 48, 0, 0, False), (4, 89, 320, 400, 0, 0, True), (1, 33, 1024, 2064, 8, 0, True)])
+def test_linear_swiglu_bf16(B, T, d_in, d_out, x_heads, y_heads, cold):
+    seed = 700 + B * T
+    M_rows = B * T
+    x = draw_normal(seed, 0, (M_rows, d_in), 1.0, "bf16")
+    wg = draw_normal(seed, 1, (d_out, d_in), 1.0 / math.sqrt(d_in), "bf16")
+    wu = draw_normal(seed, 2, (d_out, d_in), 1.0 / math.sqrt(d_in), "bf16")
+    xd = to_dev(x)
+    if x_heads:
+        xd = to_dev(np.ascontiguousarray(x.reshape(B, T, x_heads, d_in // x_heads).transpose(0, 2, 1, 3)))
+    w_gu = to_dev(interleave16(wg, wu))
+    assert torch.equal(w_gu, M.interleave_gate_up(to_dev(wg), to_dev(wu)))
+    M.medusa_set_cache_resident_bytes(0 if cold else 256 << 20)
+    try:
+        y = M.tree_linear_swiglu(xd, w_gu, B, T, y_heads=y_heads)
+        torch.cuda.synchronize()
+    finally:
+        M.medusa_set_cache_resident_bytes(256 << 20)
+    got = to_host_f64(y)
+    if y_heads:
+        got = got.transpose(0, 2, 1, 3).reshape(M_rows, d_out)
+    ref = O.tree_swiglu_ref(x, wg, wu, "bf16")
+    err = row_rel_err(got, ref)
+    assert err <= TOL["bf16"], f"tree_linear_swiglu rel err {err}"
+
+
+def test_linear_swiglu_rejects_what_it_does_not_cover():
+    x = torch.zeros((4, 128), dtype=torch.float32, device="cuda")
+    w = torch.zeros((64, 128), dtype=torch.float32, device="cuda")
+    with pytest.raises(M.MedusaError):
+        M.tree_linear_swiglu(x, w, 1, 4)                                # fp32
+    xb, wb = x.bfloat16(), torch.zeros((40, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(M.MedusaError):
+        M.tree_linear_swiglu(xb, wb, 1, 4)                              # 20 output columns: not a multiple of 16
+
+
 def test_linear_f32():
     linear_case("f32", 1, 10, 256, 96, 0, 0, False, 410)
     linear_case("f32", 2, 10, 256, 128, 4, 2, True, 411)
@@ -102,7 +150,7 @@ def test_rope(dtype, D, maxpos):
         assert err <= TOL[dtype], f"tree_rope rel err {err}"
 
 
-def block_case(dtype, branching, B, h, Hq, Hkv, D, inter, Lcap, prefix, seed, adjacent_qkv=False):
+def block_case(dtype, branching, B, h, Hq, Hkv, D, inter, Lcap, prefix, seed, adjacent_qkv=False, fused_gate_up=False):
     tree_o = O.tree_cartesian(branching)
     tree_g = M.MedusaTree(branching=branching)
     T = tree_o.T
@@ -120,10 +168,11 @@ def block_case(dtype, branching, B, h, Hq, Hkv, D, inter, Lcap, prefix, seed, ad
     if adjacent_qkv:      # W_Q, W_K, W_V as consecutive row blocks of one allocation: one projection call at B = 1
         wqkv = torch.cat([dw["wq"], dw["wk"], dw["wv"]], dim=0)
         dw["wq"], dw["wk"], dw["wv"] = wqkv[:Hq * D], wqkv[Hq * D:(Hq + Hkv) * D], wqkv[(Hq + Hkv) * D:]
+    w_gu = M.interleave_gate_up(dw["wg"], dw["wu"]) if fused_gate_up else None
     out = blk.run(to_dev(x), *(dw[n] for n in ("wq", "wk", "wv", "wu", "wg", "wd")), to_dev(kc), to_dev(vc),
-                  to_dev(pl), to_dev(pos), scale)
+                  to_dev(pl), to_dev(pos), scale, w_gu)
     if adjacent_qkv and B == 1:
-        assert len(blk._plans) == 1 and len(next(iter(blk._plans.values()))) == 6      # the fused form did run
+        assert len(blk._plans) == 1 and len(next(iter(blk._plans.values()))) == (5 if fused_gate_up else 6)   # the fused form did run
     torch.cuda.synchronize()
     ref = O.simplified_block_ref(x, ws["wq"], ws["wk"], ws["wv"], ws["wu"], ws["wg"], ws["wd"], kc, vc, pl, pos, tree_o,
                                  Hq, Hkv, scale, theta, dtype)
@@ -131,7 +180,8 @@ def block_case(dtype, branching, B, h, Hq, Hkv, D, inter, Lcap, prefix, seed, ad
     # end to end every intermediate inherits the rounding differences of its predecessors: a few
     # storage roundings deep, so the bound is the per-operator tolerance times the chain length
     depth = {"q": 2, "k": 2, "v": 1, "attn": 3, "up": 4, "act": 5, "out": 6}
-    for name in ("q", "k", "v", "attn", "up", "act", "out"):
+    names = [n for n in ("q", "k", "v", "attn", "up", "act", "out") if not (fused_gate_up and n == "up")]   # no `up` in memory when fused
+    for name in names:
         err = row_rel_err(to_host_f64(got[name]), ref[name])
         assert err <= TOL[dtype] * depth[name], f"{name}: rel err {err}"
     # stage-wise, from the GPU's own inputs: each operator alone meets the per-operator tolerance
@@ -139,10 +189,13 @@ def block_case(dtype, branching, B, h, Hq, Hkv, D, inter, Lcap, prefix, seed, ad
     a_tok = O.from_heads(g64["attn"])
     checks = {
         "attn": (O.round_to_storage(O.tree_attention_ref(g64["q"], g64["k"], g64["v"], kc, vc, pl, tree_o, scale), dtype), g64["attn"]),
-        "up": (O.tree_linear_ref(a_tok, ws["wu"], dtype), g64["up"]),
-        "act": (O.tree_linear_ref(a_tok, ws["wg"], dtype, mul=g64["up"]), g64["act"]),
         "out": (O.tree_linear_ref(g64["act"], ws["wd"], dtype), g64["out"]),
     }
+    if fused_gate_up:
+        checks["act"] = (O.tree_swiglu_ref(a_tok, ws["wg"], ws["wu"], dtype), g64["act"])
+    else:
+        checks["up"] = (O.tree_linear_ref(a_tok, ws["wu"], dtype), g64["up"])
+        checks["act"] = (O.tree_linear_ref(a_tok, ws["wg"], dtype, mul=g64["up"]), g64["act"])
     for name, (want, have) in checks.items():
         err = row_rel_err(have, want)
         assert err <= TOL[dtype], f"{name} (stage-wise): rel err {err}"
@@ -158,6 +211,11 @@ def test_block_bf16_gqa_ragged():
 
 def test_block_bf16_head_dim_128():
     block_case("bf16", (2, 2, 1), 1, 512, 4, 4, 128, 768, 400, [300], 602)
+
+
+def test_block_bf16_fused_gate_and_up():
+    block_case("bf16", (3, 2, 1), 2, 512, 8, 2, 64, 1024, 700, [600, 37], 605, fused_gate_up=True)       # 2 x 16 rows
+    block_case("bf16", (2, 2, 1), 1, 512, 4, 4, 128, 768, 400, [300], 606, adjacent_qkv=True, fused_gate_up=True)
 
 
 def test_block_bf16_fused_qkv_projection():

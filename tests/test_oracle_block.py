@@ -36,6 +36,30 @@ def test_gated_linear_closed_forms():
     assert np.all(got[1] == 0.0)                                                   # token 1 sees only zeros
 
 
+def test_swiglu_brute_force_and_special_cases():
+    # independent loops with math.exp; a swapped gate and up, a missing SiLU or a transposed weight fail
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((4, 6)).astype(np.float32)
+    wg = rng.standard_normal((5, 6)).astype(np.float32)
+    wu = rng.standard_normal((5, 6)).astype(np.float32)
+    got = O.tree_swiglu_ref(x, wg, wu, "f32")
+    assert got.shape == (4, 5)
+    for m in range(4):
+        for n in range(5):
+            g = sum(float(x[m, j]) * float(wg[n, j]) for j in range(6))
+            u = sum(float(x[m, j]) * float(wu[n, j]) for j in range(6))
+            want = g / (1.0 + math.exp(-g)) * u
+            assert abs(got[m, n] - want) <= 1e-6 * max(1.0, abs(want))
+    # zero gate rows give zero whatever the up rows are; a large gate passes the up projection times the gate
+    e = np.eye(2, dtype=np.float32)
+    assert np.all(O.tree_swiglu_ref(e, np.zeros((3, 2), np.float32), np.ones((3, 2), np.float32), "f32") == 0.0)
+    big = O.tree_swiglu_ref(e, np.full((1, 2), 50.0, np.float32), np.full((1, 2), 3.0, np.float32), "f32")
+    assert np.allclose(big, 150.0, rtol=1e-6)
+    # it is the two-operator form without the intermediate rounding: equal to it in fp32 up to that rounding
+    two_step = O.tree_linear_ref(x, wg, "f32", mul=O.tree_linear_ref(x, wu, "f32"))
+    assert np.allclose(got, two_step, rtol=1e-5, atol=1e-6)
+
+
 def _rope_complex(x, pos, theta):
     """Independent statement: the pair (x[j], x[j + D/2]) is the complex number x[j] + i x[j + D/2],
     multiplied by exp(i * pos * theta**(-2j/D))."""
