@@ -53,11 +53,14 @@ __device__ __forceinline__ void row_stats(const float* __restrict__ logits, int 
   // soft-max statistics in log2 units: t = z * log2(e), m = max t, S = sum 2^(t-m), U = sum (t-m) 2^(t-m)
   float m = -INFINITY, S = 0.f, U = 0.f;
   const float k2 = inv_temp * 1.4426950408889634f;
-  auto visit = [&](float x, int i) {
+  auto visit_max = [&](float x, int i) {
     if (x > best || best_i < 0) {
       best = x;
       best_i = i;
     }
+  };
+  auto visit = [&](float x, int i) {
+    visit_max(x, i);
     if (TYPICAL) {
       const float t = x * k2;
       if (t > m) {                       // new running maximum: rescale what has been summed
@@ -76,18 +79,46 @@ __device__ __forceinline__ void row_stats(const float* __restrict__ logits, int 
     const int per = ceil_div(V >> 2, chunks);
     const int lo = blockIdx.x * per, hi = min(V >> 2, lo + per);
     const floatx4_t* src4 = (const floatx4_t*)src;
-    // eight independent 16-byte loads in flight per thread before the (branchy) visits consume them
+    // eight independent 16-byte loads in flight per thread before the visits consume them
     constexpr int NB = 8;
     for (int i0 = lo + threadIdx.x; i0 < hi; i0 += NB * 256) {
       floatx4_t v[NB];
 #pragma unroll
       for (int u = 0; u < NB; ++u) v[u] = src4[min(i0 + u * 256, hi - 1)];
+      float bm = -INFINITY;
 #pragma unroll
       for (int u = 0; u < NB; ++u) {
         const int i = i0 + u * 256;
         if (i < hi) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) visit(v[u][e], 4 * i + e);
+          for (int e = 0; e < 4; ++e) {
+            visit_max(v[u][e], 4 * i + e);
+            if (TYPICAL) {
+              v[u][e] *= k2;
+              bm = fmaxf(bm, v[u][e]);
+            }
+          }
+        }
+      }
+      if (TYPICAL) {
+        // the batch's maximum first, one rescale of the running sums for all 32 values, then
+        // branch-free accumulation: one exp2 per value instead of a divergent branch with one on each side
+        if (bm > m) {
+          const float c = S > 0.f ? __builtin_amdgcn_exp2f(m - bm) : 0.f;
+          U = S > 0.f ? c * (U + (m - bm) * S) : 0.f;
+          S = c * S;
+          m = bm;
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+          if (i0 + u * 256 < hi) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float d = v[u][e] - m, p = __builtin_amdgcn_exp2f(d);
+              S += p;
+              U = fmaf(d, p, U);
+            }
+          }
         }
       }
     }
