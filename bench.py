@@ -342,14 +342,18 @@ def bench_speed_model(args, cfg):
             for i in range(12):
                 run(i)
             torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            n = 60
-            e0.record()
-            for i in range(n):
-                run(i)
-            e1.record()
-            torch.cuda.synchronize()
-            lat[q] = e0.elapsed_time(e1) / n * 1e-3
+            # three timed groups of 20 blocks, the median group counts (a stray stall of the box,
+            # seen once as a 4x outlier of one point, would otherwise bend the curve)
+            groups = []
+            for g in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(20):
+                    run(20 * g + i)
+                e1.record()
+                torch.cuda.synchronize()
+                groups.append(e0.elapsed_time(e1) / 20 * 1e-3)
+            lat[q] = sorted(groups)[1]
             del blk
         rows = S.simulate_speedup(lambda q: lat[q], qs)
         roof = S.simulate_speedup(lambda q: S.roofline_latency(shape, B, q, s_len, 2.5e15, 8e12), qs)

@@ -95,5 +95,6 @@ inline size_t x_extent(const GemmArgs& a) {
 }
 
 // Large-M bf16 GEMM (own translation unit: it is compiled with its own code-generation options).
-// Requires every element offset into W and X below 2^31.  Returns a medusa status code.
-int launch_gemm_big(const GemmArgs& a, int epi, hipStream_t stream);
+// Requires every element offset into W and X below 2^31.  Tiles of 192 (tall) or 128 activation rows
+// x 256 weight rows.  Returns a medusa status code.
+int launch_gemm_big(const GemmArgs& a, int epi, bool tall, hipStream_t stream);

@@ -224,15 +224,14 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
 }
 
 template <int EPI>
-int launch(const GemmArgs& a_in, hipStream_t stream) {
+int launch(const GemmArgs& a_in, bool tall, hipStream_t stream) {
   GemmArgs a = a_in;
   // 16-byte epilogue accesses need 8-column runs that are contiguous and aligned in the output and
   // in the tensor the epilogue reads
   const size_t align = (size_t)a.out | (size_t)(EPI == EPI_RESID || EPI == EPI_GATED ? a.hidden : nullptr);
   a.vec_epilogue = a.N % 8 == 0 && align % 16 == 0 && (a.y_dh == 0 || a.y_dh % 8 == 0) ? 1 : 0;
-  // 192 x 256 or 128 x 256 tile, whichever pads M less (ties to the larger)
+  // 192 x 256 or 128 x 256 tile, as the caller planned
   const int n_tiles = ceil_div(a.N, 256);
-  const bool tall = ceil_div(a.M, 192) * 192 <= ceil_div(a.M, 128) * 128;
   const int m_tiles = ceil_div(a.M, tall ? 192 : 128);
   const dim3 grid(8 * ceil_div(n_tiles, 8) * m_tiles, a.K), block(256);
   if (tall) hipLaunchKernelGGL((gemm_big_bf16_kernel<6, 8, EPI>), grid, block, 0, stream, a, m_tiles, n_tiles);
@@ -243,14 +242,14 @@ int launch(const GemmArgs& a_in, hipStream_t stream) {
 
 }  // namespace
 
-int launch_gemm_big(const GemmArgs& a, int epi, hipStream_t stream) {
+int launch_gemm_big(const GemmArgs& a, int epi, bool tall, hipStream_t stream) {
   if (a.d % 64 != 0 || a.d < 64) return MEDUSA_EUNSUPPORTED;
   if ((size_t)a.N * a.d >= ((size_t)1 << 31) || x_extent(a) >= ((size_t)1 << 31)) return MEDUSA_EUNSUPPORTED;
   switch (epi) {
-    case EPI_LOGITS: return launch<EPI_LOGITS>(a, stream);
-    case EPI_RESID: return launch<EPI_RESID>(a, stream);
-    case EPI_PLAIN: return launch<EPI_PLAIN>(a, stream);
-    case EPI_GATED: return launch<EPI_GATED>(a, stream);
+    case EPI_LOGITS: return launch<EPI_LOGITS>(a, tall, stream);
+    case EPI_RESID: return launch<EPI_RESID>(a, tall, stream);
+    case EPI_PLAIN: return launch<EPI_PLAIN>(a, tall, stream);
+    case EPI_GATED: return launch<EPI_GATED>(a, tall, stream);
   }
   return MEDUSA_EINVAL;
 }

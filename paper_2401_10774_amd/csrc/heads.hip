@@ -707,15 +707,17 @@ __global__ __launch_bounds__(256) void gemm_runs_bf16_kernel(GemmArgs a) {
 }
 
 // Which kernel a bf16 GEMM of M rows goes to, and in what shape.
-//   M <= 4                         wave-per-row GEMV.
-//   about one 192/128 x 256 tile per CU or more (M > 80)   the large-tile kernel (gemm_big.hip).
-//   otherwise                      a skinny arrangement: row blocks of 16*mt <= 128 activation rows,
-//     128 weight rows per workgroup when that alone gives 200 workgroups (and mt <= 5), else 64;
-//     unsplit: the kernel whose wavefronts split the reduction; with under 128 tiles and a workspace:
-//     the kernel whose wavefronts split the weight rows, its reduction split over 2-8 workgroups.
-//   M > 80 and at least 200 tiles of 128 x 128: those tiles, wavefronts 2 x 2, unsplit (at M = 356
-//     and 1040 the skinny arrangement was up to 1.5x faster below that tile count and up to 1.6x
-//     slower above it; splitting the 128 x 128 kernel's reduction never paid for its 64 KB partials).
+//   M <= 4     wave-per-row GEMV.
+//   M > 80     128 x 128 tiles (wavefronts 2 x 2, unsplit) or the large-tile kernel (gemm_big.hip)
+//              with 128 or 192 x 256 tiles, whichever a small cost model prices lowest (below); if
+//              none of them has enough tiles, as for fewer rows:
+//   otherwise  a skinny arrangement: row blocks of 16*mt <= 128 activation rows, 128 weight rows per
+//              workgroup when that alone gives 200 workgroups (and mt <= 5), else 64; unsplit: the
+//              kernel whose wavefronts split the reduction; with under 160 tiles and a workspace:
+//              the kernel whose wavefronts split the weight rows, its reduction split over 2-8
+//              workgroups (at M = 356 and 1040 the skinny arrangement was up to 1.5x faster than
+//              128 x 128 tiles below 200 of those and up to 1.6x slower above; splitting the
+//              128 x 128 kernel's reduction never paid for its 64 KB partials).
 struct GemmPlan {
   enum { GEMV, SKINNY, SQUARE, BIG } kind;
   bool wide;
@@ -727,21 +729,53 @@ size_t g_llc_bytes = (size_t)256 << 20;
 GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) {
   GemmPlan p = {GemmPlan::GEMV, false, false, 1, 1, 1};
   if (M <= 4) return p;
-  if (M > 80 && !wide_offsets) {                            // (the large-tile kernel addresses with 32-bit element offsets)
-    const bool tall = ceil_div(M, 192) * 192 <= ceil_div(M, 128) * 128;
-    if ((long)ceil_div(M, tall ? 192 : 128) * ceil_div(N, 256) * K >= 200) {
+  p.m_blocks = ceil_div(M, 128);
+  if (M > 80) {
+    // Three arrangements compete above 80 rows: 128 x 128 tiles (two workgroups share a CU) and
+    // the large-tile kernel with 128 or 192 rows x 256 (one workgroup per CU).  What decides is
+    // how evenly the tiles fill 256 CUs, so each candidate is priced with its measured time per
+    // round of tiles (us at d = 4096, 7B shapes; the large tiles also wait for the weights'
+    // first trip from HBM) and the cheapest one runs:
+    //   128 x 128: 65 / 88 / 140 / 150 us for up to 1 / 2 / 3 / 4 tiles per CU, then 37.5 per tile,
+    //              plus 0.3 x (weight bytes at 6 TB/s) per tile and CU;
+    //   128 x 256: 68 per round of 256 tiles, 192 x 256: 88, plus 0.6 x (weight bytes at 6 TB/s).
+    // 128 x 128 tiles need 200 of them, or a skinny launch that would exceed one workgroup per CU;
+    // the large tiles need 120 (below that the skinny kernels win: M = 512, N = d = 4096 runs 42 us
+    // skinny, 61 us large-tile).
+    const double scale = d / 4096.0, w_us = (double)K * N * d * 2.0 / 6.0e6;
+    const int mt_skinny = ceil_div(ceil_div(M, p.m_blocks), 16);
+    const bool skinny_wide = mt_skinny <= 5 && (long)ceil_div(N, 128) * K * p.m_blocks >= 200;
+    const long skinny_tiles = (long)ceil_div(N, skinny_wide ? 128 : 64) * K * p.m_blocks;
+    const long sq_tiles = (long)ceil_div(N, 128) * p.m_blocks * K;
+    double best = 1e30;
+    int pick = GemmPlan::SKINNY;
+    bool tall = false;
+    if (sq_tiles >= 200 || skinny_tiles > 256) {
+      const long n = (sq_tiles + 255) / 256;
+      static const double t_sq[5] = {0., 65., 88., 140., 150.};
+      best = (n <= 4 ? t_sq[n] : 37.5 * n) * scale + 0.3 * w_us * n;
+      pick = GemmPlan::SQUARE;
+    }
+    if (!wide_offsets) {                                    // (the large-tile kernel addresses with 32-bit element offsets)
+      for (int r = 128; r <= 192; r += 64) {
+        const long tiles = (long)ceil_div(M, r) * ceil_div(N, 256) * K;
+        if (tiles < 120) continue;
+        const double t = (r == 128 ? 68.0 : 88.0) * scale * (double)((tiles + 255) / 256) + 0.6 * w_us;
+        if (t < best) { best = t; pick = GemmPlan::BIG; tall = r == 192; }
+      }
+    }
+    if (pick == GemmPlan::BIG) {
       p.kind = GemmPlan::BIG;
+      p.wide = tall;                                        // (for this kind: 192-row tiles)
       return p;
     }
-  }
-  p.m_blocks = ceil_div(M, 128);
-  if (M > 80 && (long)ceil_div(N, 128) * p.m_blocks * K >= 200) {
-    // enough 128 x 128 tiles to fill the chip: wavefronts 2 x 2 (half the LDS reads per MFMA of the
-    // skinny arrangement), never split
-    p.kind = GemmPlan::SQUARE;
-    p.wide = true;
-    p.mt = 4;
-    return p;
+    if (pick == GemmPlan::SQUARE) {
+      // wavefronts 2 x 2 (half the LDS reads per MFMA of the skinny arrangement), never split
+      p.kind = GemmPlan::SQUARE;
+      p.wide = true;
+      p.mt = 4;
+      return p;
+    }
   }
   p.kind = GemmPlan::SKINNY;
   p.mt = ceil_div(ceil_div(M, p.m_blocks), 16);
@@ -834,7 +868,7 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
   } else {
     const bool wide_offsets = (size_t)a.N * a.d >= ((size_t)1 << 31) || x_extent(a) >= ((size_t)1 << 31);
     const GemmPlan plan = plan_gemm(a.M, a.N, a.d, a.K, a.ws != nullptr, wide_offsets);
-    if (plan.kind == GemmPlan::BIG) return launch_gemm_big(a, EPI, stream);
+    if (plan.kind == GemmPlan::BIG) return launch_gemm_big(a, EPI, plan.wide, stream);
     const bool wide = plan.wide;
     a.ksplit = plan.ksplit;
     // split reductions exist for the epilogues tree_linear uses (medusa_heads passes no workspace)
