@@ -779,6 +779,20 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
   }
   p.kind = GemmPlan::SKINNY;
   p.mt = ceil_div(ceil_div(M, p.m_blocks), 16);
+  // More than 80 rows per block over a short reduction and a narrow output (the d x d projections):
+  // rather than splitting the reduction of a few fat tiles, cut the rows into more blocks until
+  // the unsplit launch has about one workgroup per CU; the blocks of a weight tile run side by side
+  // and share its trip from HBM.  N = d = 4096 (us, one/two blocks against four): M = 128 23 -> 18,
+  // M = 192 26 -> 21, M = 256 32 -> 24.5; N = d = 5120, M = 128: 38 -> 32.  Long reductions lose
+  // (d = 11008, M = 128: 50 -> 54), fewer rows gain nothing (M = 64: 16 -> 15.4).
+  if (p.mt >= 6 && d <= 6144) {
+    const long per_block = (long)ceil_div(N, 64) * K;
+    if (per_block * p.m_blocks < 160) {
+      const int want = (int)((256 + per_block - 1) / per_block), most = ceil_div(M, 32);
+      p.m_blocks = want < most ? want : most;
+      p.mt = ceil_div(ceil_div(M, p.m_blocks), 16);
+    }
+  }
   p.wide = p.mt <= 5 && (long)ceil_div(N, 128) * K * p.m_blocks >= 200;   // (128-column tiles exist for up to 80 rows)
   // Cold weights want long runs per row (15-19 % faster at M = 8..64, 10 % at 65..80); weights that
   // the last-level cache holds want the short-stage kernel (3-8 % faster there).
