@@ -272,6 +272,19 @@ int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int B, int T, i
 int medusa_set_cache_resident_bytes(size_t bytes);
 
 /* ----------------------------------------------------------------------------------
+ * Diagnostic (no counterpart in the paper; host only, touches no GPU): which kernel arrangement
+ * the library would launch for a bf16 product of M activation rows with K weight matrices of
+ * N rows x d columns (medusa_heads, tree_linear), with or without a workspace.
+ * plan6 (host, 6 ints, written): [0] kind: 0 wave-per-row GEMV, 1 skinny MFMA tiles, 2 128 x 128
+ * tiles, 3 large tiles;  [1] kind 1: 128 (else 64) weight rows per workgroup, kind 3: 192 (else 128)
+ * activation rows per tile;  [2] kind 1: the long-run kernel for cold weights;  [3] kind 1/2: groups
+ * of 16 activation rows per row block (1..8);  [4] row blocks;  [5] workgroups that share one tile's
+ * reduction (1 = unsplit; > 1 only with a workspace).
+ * Returns MEDUSA_EINVAL for a null pointer or a non-positive size.
+ * -------------------------------------------------------------------------------- */
+int medusa_gemm_plan(int M, int N, int d, int K, int have_workspace, int* plan6);
+
+/* ----------------------------------------------------------------------------------
  * Benchmark hook (no counterpart in the paper): while a pair of hipEvent_t handles is set,
  * every medusa_heads call with w1 != NULL records `start` right before and `stop` right after
  * its vocabulary-projection kernel (the W2 stream, the largest single read of the step) on the

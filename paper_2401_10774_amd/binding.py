@@ -27,7 +27,7 @@ EXPORTED_SYMBOLS = (
     "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "medusa_accept_workspace_bytes",
     "medusa_accept", "kv_commit", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_swiglu", "tree_rope",
     "medusa_profile_set_events",
-    "medusa_set_cache_resident_bytes",
+    "medusa_set_cache_resident_bytes", "medusa_gemm_plan",
 )
 
 
@@ -76,6 +76,7 @@ def lib() -> ctypes.CDLL:
         L.tree_rope.argtypes = [c_void_p] * 3 + [c_int] * 5 + [c_float, c_int, c_void_p]
         L.medusa_profile_set_events.argtypes = [c_void_p, c_void_p]
         L.medusa_set_cache_resident_bytes.argtypes = [ctypes.c_size_t]
+        L.medusa_gemm_plan.argtypes = [c_int] * 5 + [ctypes.POINTER(c_int)]
         for name in EXPORTED_SYMBOLS:
             fn = getattr(L, name)
             if fn.restype is ctypes.c_int or fn.restype is None:
@@ -408,6 +409,15 @@ def medusa_set_cache_resident_bytes(nbytes: int) -> None:
     """Weight matrices of up to `nbytes` are taken to stay in the last-level cache between calls
     (default 256 MiB; 0 = always cold).  Selects between two forms of the 5..80-row MFMA kernels."""
     _check(lib().medusa_set_cache_resident_bytes(int(nbytes)), "medusa_set_cache_resident_bytes")
+
+
+def medusa_gemm_plan(M: int, N: int, d: int, K: int = 1, have_workspace: bool = True) -> dict:
+    """Which kernel arrangement a bf16 product of M rows with K matrices of N x d would get
+    (host-side diagnostic, no GPU work)."""
+    out = (ctypes.c_int * 6)()
+    _check(lib().medusa_gemm_plan(int(M), int(N), int(d), int(K), int(bool(have_workspace)), out), "medusa_gemm_plan")
+    kinds = ("gemv", "skinny", "square", "big")
+    return {"kind": kinds[out[0]], "wide": bool(out[1]), "runs": bool(out[2]), "mt": out[3], "m_blocks": out[4], "ksplit": out[5]}
 
 
 def tree_rope(q: torch.Tensor, k: torch.Tensor, position_ids: torch.Tensor, theta: float = 10000.0, stream=None) -> None:

@@ -914,6 +914,7 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
     switch (plan.mt) {
       MEDUSA_SKINNY(1) MEDUSA_SKINNY(2) MEDUSA_SKINNY(3) MEDUSA_SKINNY(4) MEDUSA_SKINNY(5) MEDUSA_SKINNY(6)
       MEDUSA_SKINNY(7) MEDUSA_SKINNY(8)
+      default: return MEDUSA_EUNSUPPORTED;                  // (no plan asks for more than 128 rows per block)
     }
 #undef MEDUSA_SKINNY
     if (rc != MEDUSA_OK) return rc;
@@ -1060,6 +1061,14 @@ extern "C" int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int 
 #undef MEDUSA_SWIGLU
   if (rc != MEDUSA_OK) return rc;
   MEDUSA_LAUNCH_CHECK();
+  return MEDUSA_OK;
+}
+
+extern "C" int medusa_gemm_plan(int M, int N, int d, int K, int have_workspace, int* plan6) {
+  if (!plan6 || M < 1 || N < 1 || d < 1 || K < 1) return MEDUSA_EINVAL;
+  const bool wide_offsets = (size_t)N * d >= ((size_t)1 << 31) || (size_t)M * d + (size_t)K * d + d >= ((size_t)1 << 31);
+  const GemmPlan p = plan_gemm(M, N, d, K, have_workspace != 0, wide_offsets);
+  plan6[0] = (int)p.kind; plan6[1] = p.wide; plan6[2] = p.runs; plan6[3] = p.mt; plan6[4] = p.m_blocks; plan6[5] = p.ksplit;
   return MEDUSA_OK;
 }
 

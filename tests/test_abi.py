@@ -110,3 +110,41 @@ def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(M.MedusaError, match="device memory"):
         M.medusa_heads(torch.zeros(1, 64), None, torch.zeros(1, 10, 64))
+
+
+def test_gemm_plans_are_launchable():
+    """Host logic of the GEMM planning: over a grid of shapes every plan names an arrangement the
+    launch code has a kernel for, its row blocks cover all rows, and a split reduction appears
+    only with a workspace and is matched by a workspace size."""
+    import paper_2401_10774_amd as M
+    L = M.lib()
+    shapes = [(4096, 4096), (11008, 4096), (4096, 11008), (12288, 4096), (22016, 4096), (32000, 4096),
+              (1024, 4096), (5120, 5120), (13824, 5120), (5120, 13824), (32000, 5120), (192, 64), (64, 128)]
+    for N, d in shapes:
+        for K in (1, 5):
+            for rows in (1, 4, 5, 16, 17, 64, 65, 80, 81, 96, 128, 129, 192, 256, 356, 512, 640, 768, 1040, 2080, 3584):
+                for ws in (False, True):
+                    p = M.medusa_gemm_plan(rows, N, d, K, ws)
+                    what = f"M={rows} N={N} d={d} K={K} ws={ws}: {p}"
+                    if rows <= 4:
+                        assert p["kind"] == "gemv", what
+                        continue
+                    assert p["kind"] in ("skinny", "square", "big"), what
+                    if p["kind"] == "big":
+                        assert rows > 80, what
+                        continue
+                    if p["kind"] == "square":       # 128 x 128 tiles
+                        assert rows > 80 and p["ksplit"] == 1 and p["m_blocks"] * 128 >= rows, what
+                        continue
+                    assert 1 <= p["mt"] <= 8 and p["m_blocks"] >= 1, what
+                    assert p["m_blocks"] * p["mt"] * 16 >= rows, what
+                    assert p["ksplit"] in (1, 2, 4, 8), what
+                    assert ws or p["ksplit"] == 1, what
+                    assert not p["wide"] or p["mt"] <= 5, what
+                    assert not p["runs"] or p["wide"], what
+                    if p["ksplit"] > 1:
+                        assert (d // 64) // p["ksplit"] >= 1, what
+                        if K == 1:
+                            assert L.tree_linear_workspace_bytes(1, rows, d, N, 1) > 0, what
+    with pytest.raises(M.MedusaError):
+        M.medusa_gemm_plan(0, 64, 64)
