@@ -126,6 +126,7 @@ def main():
     L = M.lib()
     K, W = args.steps, args.warmup
     step.commit_out_of_place()   # every timed step sees the same prefix lengths; no reset between steps
+    plant_accepted_paths(step, tensors, tree, cfg)
     for i in range(W):
         step.run(i % cfg.NL)
     torch.cuda.synchronize()
@@ -197,6 +198,36 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, x)
     print(json.dumps(out), flush=True)
+
+
+def plant_accepted_paths(step, tensors, tree, cfg):
+    """Input preparation, before any timing.  Random hidden states accept nothing beyond the root,
+    which would leave acceptance and kv_commit their minimum work.  The paper's steps emit about
+    three tokens (Sec. 3; 0.477 log2(64) = 2.86 in the appendix's model), so per sequence one tree
+    path of 1..3 nodes below the root (two at batch 1; seeded) is made acceptable: the hidden
+    state of each node on it is replaced by 40x the LM-head row of the path's next token, whose
+    logit (about 65) then towers over the rest (about N(0, 1)).  The row norm (about 51) stays close
+    to that of the random rows (64).  The tree tokens come from one untimed step on these inputs."""
+    import numpy as np
+    import torch
+
+    step.run(0)
+    torch.cuda.synchronize()
+    tok = step.tree_tokens.view(cfg.B, tree.T).cpu().numpy()
+    rng = np.random.default_rng(cfg.seed)
+    rows, toks = [], []
+    for b in range(cfg.B):
+        dep = 2 if cfg.B == 1 else int(rng.integers(1, min(3, tree.K) + 1))
+        at_depth = np.flatnonzero(tree.depth == dep)
+        n = int(at_depth[rng.integers(len(at_depth))])
+        while n > 0:
+            rows.append(b * tree.T + int(tree.parent[n]))
+            toks.append(int(tok[b, n]))
+            n = int(tree.parent[n])
+    hidden = tensors["hidden_tree"].view(cfg.B * tree.T, cfg.d)
+    w = tensors["w_lm"][torch.tensor(toks, device="cuda")].float() * 40.0
+    hidden[torch.tensor(rows, device="cuda")] = w.to(hidden.dtype)
+    torch.cuda.synchronize()
 
 
 def bench_block(args, cfg):

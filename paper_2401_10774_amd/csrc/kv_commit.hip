@@ -1,9 +1,10 @@
 // kv_commit (Fig. 1 of the Medusa paper: the accepted prefix is the next step's context):
 // append the accepted path's tree K/V rows to every layer of the cache, then grow prefix_len.
-// Pure index arithmetic and 16-byte copies: bit-exact by construction.  One launch: every
-// workgroup reads the old prefix_len.  In place, each takes a ticket afterwards and the workgroup
-// that draws the last one writes the new lengths, once all others are done with the old ones;
-// with a second array for the new lengths nobody has to wait: workgroup 0 writes them.
+// Pure index arithmetic and 16-byte copies: bit-exact by construction.  One launch, one workgroup
+// per (layer, sequence, path slot), so that a long accepted path costs no more time than a short
+// one.  Every workgroup reads the old prefix_len.  In place, each takes a ticket afterwards and
+// the workgroup that draws the last one writes the new lengths, once all others are done with the
+// old ones; with a second array for the new lengths nobody has to wait: workgroup (0, 0) writes them.
 #include "common.hpp"
 
 namespace {
@@ -12,8 +13,8 @@ namespace {
 // on a GPU: calls that overlap on different streams would race.
 __device__ unsigned int g_commit_ticket;
 
-// grid (NL*B), 256 threads.  One workgroup moves the <= K+1 accepted rows of all KV heads of one
-// (layer, sequence), K and V.  Few, fat workgroups keep the number of tickets small.
+// grid (NL*B, path_stride), 256 threads.  One workgroup moves one accepted row (path slot) of all KV
+// heads of one (layer, sequence), K and V; workgroups of slots beyond accept_len have nothing to move.
 __global__ __launch_bounds__(256) void kv_commit_kernel(u32x4_t* __restrict__ k_cache, u32x4_t* __restrict__ v_cache,
                                                         const u32x4_t* __restrict__ k_tree, const u32x4_t* __restrict__ v_tree,
                                                         const int32_t* __restrict__ path_nodes, int path_stride,
@@ -21,42 +22,42 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(u32x4_t* __restrict__ k_
                                                         const int32_t* prefix_len, int32_t* prefix_len_out, int B,
                                                         int Hkv, int T, int Lcap, int vec_per_row, int in_place) {
   const int lb = blockIdx.x;                  // l*B + b
+  const int j = blockIdx.y;                   // path slot
   const int b = lb % B;
+  // the three small loads do not depend on each other: they go out together
   const int a = min(max(accept_len[b], 0), path_stride);
   const int L = prefix_len[b];
-  // Work item i: path slot j = i / per_slot, then tensor (K, V), head, 16-byte chunk.  A thread's path
-  // node does not depend on accept_len, so the three small loads go out together; four items per
-  // thread and round, so that their row loads do too; the rounds end at the first unaccepted slot.
-  const int per_head = vec_per_row, per_slot = 2 * Hkv * per_head;
-  const int total = path_stride * per_slot;
-  for (int base = 0; base < total; base += 4 * 256) {
-    if (base / per_slot >= a) break;
-    size_t src_i[4], dst_i[4];
-    bool ok[4], which[4];
-    u32x4_t val[4];
+  const int node = path_nodes[(size_t)b * path_stride + j];
+  const int dst = L + j;
+  if (j < a && node >= 0 && node < T && dst >= 0 && dst < Lcap) {
+    // Work item i: tensor (K, V), head, 16-byte chunk.  Four items per thread and round, so that
+    // their row loads are in flight together.
+    const int per_head = vec_per_row, total = 2 * Hkv * per_head;
+    for (int base = 0; base < total; base += 4 * 256) {
+      size_t src_i[4], dst_i[4];
+      bool ok[4], which[4];
+      u32x4_t val[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int i = base + u * 256 + threadIdx.x;
-      const int j = min(i / per_slot, path_stride - 1);
-      int rem = i - j * per_slot;
-      which[u] = rem >= Hkv * per_head;
-      rem -= which[u] * Hkv * per_head;
-      const int h = rem / per_head, c = rem - h * per_head;
-      const int node = path_nodes[(size_t)b * path_stride + j];
-      const int dst = L + j;
-      ok[u] = i < total && j < a && node >= 0 && node < T && dst >= 0 && dst < Lcap;
-      const size_t lbh = (size_t)lb * Hkv + h;
-      src_i[u] = (lbh * T + node) * vec_per_row + c;
-      dst_i[u] = (lbh * Lcap + dst) * vec_per_row + c;
+      for (int u = 0; u < 4; ++u) {
+        const int i = base + u * 256 + threadIdx.x;
+        int rem = min(i, total - 1);
+        which[u] = rem >= Hkv * per_head;
+        rem -= which[u] * Hkv * per_head;
+        const int h = rem / per_head, c = rem - h * per_head;
+        ok[u] = i < total;
+        const size_t lbh = (size_t)lb * Hkv + h;
+        src_i[u] = (lbh * T + node) * vec_per_row + c;
+        dst_i[u] = (lbh * Lcap + dst) * vec_per_row + c;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (ok[u]) val[u] = which[u] ? v_tree[src_i[u]] : k_tree[src_i[u]];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (ok[u]) (which[u] ? v_cache : k_cache)[dst_i[u]] = val[u];
     }
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-      if (ok[u]) val[u] = which[u] ? v_tree[src_i[u]] : k_tree[src_i[u]];
-#pragma unroll
-    for (int u = 0; u < 4; ++u)
-      if (ok[u]) (which[u] ? v_cache : k_cache)[dst_i[u]] = val[u];
   }
-  if (in_place ? !last_workgroup_of(&g_commit_ticket, gridDim.x) : blockIdx.x != 0) return;
+  if (in_place ? !last_workgroup_of(&g_commit_ticket, gridDim.x * gridDim.y) : (blockIdx.x | blockIdx.y) != 0) return;
   for (int bb = threadIdx.x; bb < B; bb += 256) {
     const int aa = min(max(accept_len[bb], 0), path_stride);
     prefix_len_out[bb] = min(max(prefix_len[bb], 0) + aa, Lcap);
@@ -73,9 +74,9 @@ extern "C" int kv_commit(void* k_cache, void* v_cache, const void* k_tree, const
   if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;
   const size_t row_bytes = (size_t)D * (dtype == MEDUSA_F32 ? 4 : 2);
   if (row_bytes % 16 != 0) return MEDUSA_EUNSUPPORTED;
-  if ((size_t)NL * B > 0x7fffffffu) return MEDUSA_EUNSUPPORTED;
+  if ((size_t)NL * B > 0x7fffffffu || path_stride > 65535) return MEDUSA_EUNSUPPORTED;
   hipStream_t stream = (hipStream_t)stream_;
-  hipLaunchKernelGGL(kv_commit_kernel, dim3(NL * B), dim3(256), 0, stream, (u32x4_t*)k_cache, (u32x4_t*)v_cache,
+  hipLaunchKernelGGL(kv_commit_kernel, dim3(NL * B, path_stride), dim3(256), 0, stream, (u32x4_t*)k_cache, (u32x4_t*)v_cache,
                      (const u32x4_t*)k_tree, (const u32x4_t*)v_tree, path_nodes, path_stride, accept_len, prefix_len,
                      prefix_len_out ? prefix_len_out : prefix_len, B, Hkv, T, Lcap, (int)(row_bytes / 16),
                      (int)(!prefix_len_out || prefix_len_out == prefix_len));
