@@ -23,7 +23,8 @@ constexpr int kMaxSplitTiles = 1024;       // output tiles x heads a split reduc
 // ---------------------------------------------------------------------------------------
 
 template <int MB, int EPI>
-__global__ __launch_bounds__(256) void gemv_bf16_kernel(GemmArgs a) {
+__global__ __launch_bounds__(MB >= 3 ? 512 : 256) void gemv_bf16_kernel(GemmArgs a) {
+  constexpr int NWV = MB >= 3 ? 8 : 4;          // wavefronts per workgroup (more of them share the bigger LDS staging)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u32x4_t* xs = (u32x4_t*)smem;                 // [MB][d/8] 16-byte chunks
   const int chunks = a.d >> 3;
@@ -42,11 +43,11 @@ __global__ __launch_bounds__(256) void gemv_bf16_kernel(GemmArgs a) {
   const int cpb = 64 * U;                       // chunks per batch and row
   const int bpr = (chunks + cpb - 1) / cpb;     // batches per row pair
   const int first_nb = n_begin + wave * R;
-  const int n_pairs = first_nb < n_end ? (n_end - first_nb + 4 * R - 1) / (4 * R) : 0;
+  const int n_pairs = first_nb < n_end ? (n_end - first_nb + NWV * R - 1) / (NWV * R) : 0;
   const int n_batches = n_pairs * bpr;
   auto load_batch = [&](int bi, u32x4_t (&w)[R][U]) __attribute__((always_inline)) {
     const int pair = bi / bpr, c0 = (bi - pair * bpr) * cpb;
-    const int nb = first_nb + pair * 4 * R;
+    const int nb = first_nb + pair * NWV * R;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const u32x4_t* wrow = (const u32x4_t*)(W + (size_t)min(nb + r, a.N - 1) * a.d);
@@ -60,7 +61,7 @@ __global__ __launch_bounds__(256) void gemv_bf16_kernel(GemmArgs a) {
   u32x4_t wa[R][U], wb[R][U];
   if (n_batches > 0) load_batch(0, wa);
 
-  for (int i = threadIdx.x; i < MB * chunks; i += 256) {
+  for (int i = threadIdx.x; i < MB * chunks; i += 64 * NWV) {
     const int mm = i / chunks, c = i - mm * chunks;
     u32x4_t v = {0, 0, 0, 0};
     if (m0 + mm < a.M) v = *(const u32x4_t*)(X + x_row_offset<kHeadMajor<EPI>>(a, m0 + mm, k) + x_col_offset<kHeadMajor<EPI>>(a, c * 8));
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(256) void gemv_bf16_kernel(GemmArgs a) {
       }
     }
     if (c0 + cpb >= chunks) {                   // last batch of the row pair: reduce and store
-      const int nb = first_nb + pair * 4 * R;
+      const int nb = first_nb + pair * NWV * R;
 #pragma unroll
       for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -833,7 +834,11 @@ hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
 
 // Weight rows per GEMV workgroup: 16 measured best on MI355X at 7B shapes (8, 32 and 64 were
 // 1-10 % slower); fewer for small matrices so that the grid still covers the chip.
-int gemv_rows_per_wg(int N, int K) {
+int gemv_rows_per_wg(int N, int K, int M) {
+  // (three or four activation rows cost a workgroup 30-40 KB of LDS staging: twice the weight rows
+  // per workgroup then, if that still leaves the chip 500 workgroups: 62 -> 59 us at d = 5120, V = 32000)
+  // (the kernel for three or four rows has eight wavefronts, each on two weight rows at a time)
+  if (M >= 3) return (long)N * K >= 16384 ? 32 : 16;
   long rows = ((long)N * K / 1024) & ~7L;
   return rows < 8 ? 8 : (rows > 16 ? 16 : (int)rows);
 }
@@ -861,7 +866,7 @@ template <int EPI>
 int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) {
   GemmArgs a = a_in;
   a.ksplit = 1;
-  a.rows_per_wg = gemv_rows_per_wg(a.N, a.K);
+  a.rows_per_wg = gemv_rows_per_wg(a.N, a.K, dtype == MEDUSA_BF16 ? a.M : 1);
   const int kGemvRowsPerWg = a.rows_per_wg;
   const dim3 block(256);
   if (dtype == MEDUSA_F32) {
@@ -878,7 +883,7 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
     const size_t lds = (size_t)MB * a.d * sizeof(uint16_t);
     if (MB == 1) hipLaunchKernelGGL((gemv_bf16_kernel<1, EPI>), grid, block, lds, stream, a);
     else if (MB == 2) hipLaunchKernelGGL((gemv_bf16_kernel<2, EPI>), grid, block, lds, stream, a);
-    else hipLaunchKernelGGL((gemv_bf16_kernel<4, EPI>), grid, block, lds, stream, a);
+    else hipLaunchKernelGGL((gemv_bf16_kernel<4, EPI>), grid, dim3(512), lds, stream, a);
   } else {
     const bool wide_offsets = (size_t)a.N * a.d >= ((size_t)1 << 31) || x_extent(a) >= ((size_t)1 << 31);
     const GemmPlan plan = plan_gemm(a.M, a.N, a.d, a.K, a.ws != nullptr, wide_offsets);
