@@ -168,3 +168,50 @@ def test_c4_13b_batch4_ragged():
 def test_c5_gqa_batch16_typical():
     a = run_config("C5", nl=8)
     assert len(set(a.tolist())) >= 2
+
+
+def test_step_replays_under_a_hip_graph():
+    """The step's eight launches captured into one HIP graph (no memset nodes: every ticket counter
+    resets itself) give, on every replay, bit for bit what the eager launches give; eager steps and
+    synchronisations run between the replays."""
+    from workloads import scaled_config
+    cfg = scaled_config("C2", V=4096, NL=2, L_min=300, L_max=300, Lcap=448)
+    x = make_step_inputs(cfg)
+    step = VerificationStep({k: to_dev(v) for k, v in x.items()}, M.MedusaTree(branching=cfg.branching), cfg.accept,
+                            cfg.temperature, cfg.eps, cfg.delta)
+    step.prepare()
+    step.commit_out_of_place()                 # every run starts from the same prefix lengths
+
+    def snapshot():
+        torch.cuda.synchronize()
+        outs = [step.medusa_logits, step.tree_tokens, step.attn_out, step.verify_logits, *step.accept_out, step.next_prefix_len]
+        return [o.clone() for o in outs]
+
+    for _ in range(2):                         # warm-up: one-time kernel attribute calls happen outside the capture
+        step.run(0)
+    eager = snapshot()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step.run(0)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step.run(0)
+    torch.cuda.synchronize()
+    for replay in range(4):
+        for t in (step.medusa_logits, step.attn_out, step.verify_logits):
+            t.fill_(float("nan"))              # a replay that skipped a kernel would leave this behind
+        step.accept_out[0].fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(eager, got):
+            assert torch.equal(a.view(torch.uint8) if a.dtype != torch.bfloat16 else a.view(torch.int16),
+                               b.view(torch.uint8) if b.dtype != torch.bfloat16 else b.view(torch.int16)), f"replay {replay}"
+        step.run(1)                            # eager work on another cache layer between the replays
+        step.run(0)
+        again = snapshot()
+        for a, b in zip(eager, again):
+            assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a.view(torch.uint8),
+                               b.view(torch.int16) if b.dtype == torch.bfloat16 else b.view(torch.uint8))
