@@ -221,3 +221,43 @@ def test_block_bf16_fused_gate_and_up():
 def test_block_bf16_fused_qkv_projection():
     block_case("bf16", (4, 3, 2, 1), 1, 512, 8, 2, 64, 1024, 300, [200], 603, adjacent_qkv=True)
     block_case("bf16", (2, 2, 1), 1, 512, 4, 4, 128, 768, 400, [300], 604, adjacent_qkv=True)
+
+
+def test_block_replays_under_a_hip_graph():
+    """The block's calls (split reductions with their tickets and workspace included) captured into
+    one HIP graph reproduce the eager result bit for bit on every replay."""
+    branching, B, h, Hq, Hkv, D, inter, Lcap = (4, 3, 2, 1), 1, 512, 8, 2, 64, 1024, 300
+    tree = M.MedusaTree(branching=branching)
+    T = tree.T
+    x = to_dev(draw_normal(701, 0, (B * T, h), 1.0, "bf16"))
+    shapes = (("wq", (Hq * D, h)), ("wk", (Hkv * D, h)), ("wv", (Hkv * D, h)), ("wu", (inter, Hq * D)),
+              ("wg", (inter, Hq * D)), ("wd", (h, inter)))
+    dw = {n: to_dev(draw_normal(701, 10 + i, s, 1.0 / math.sqrt(s[1]), "bf16")) for i, (n, s) in enumerate(shapes)}
+    kc, vc = (to_dev(draw_normal(701, 20 + i, (B, Hkv, Lcap, D), 1.0, "bf16")) for i in range(2))
+    pl = np.asarray([200], np.int32)
+    pos = to_dev((pl[:, None] + np.asarray(tree.depth, np.int32)[None, :]).astype(np.int32))
+    blk = SimplifiedBlock(tree, B, h, Hq, Hkv, D, inter, Lcap, torch.bfloat16)
+    args = (x, *(dw[n] for n in ("wq", "wk", "wv", "wu", "wg", "wd")), kc, vc, to_dev(pl), pos, 1.0 / math.sqrt(D))
+    for _ in range(2):
+        out = blk.run(*args)
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in (blk.q, blk.k, blk.v, blk.attn, blk.up, blk.act, out)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        blk.run(*args)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            blk.run(*args)
+    torch.cuda.synchronize()
+    for replay in range(4):
+        for t in (blk.q, blk.k, blk.v, blk.attn, blk.up, blk.act, out):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(eager, (blk.q, blk.k, blk.v, blk.attn, blk.up, blk.act, out)):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"replay {replay}"
+        blk.run(*args)                         # eager work between the replays
+        torch.cuda.synchronize()
