@@ -60,6 +60,28 @@ def test_linear_bf16_large_tile_kernel():
     linear_case("bf16", 4, 89, 192, 25600, 0, 0, False, 423)          # 356 rows: two 192-row tiles
 
 
+@pytest.mark.parametrize("rows,N,d,want", [
+    (128, 4096, 128, dict(kind="skinny", m_blocks=4, mt=2, ksplit=1)),    # short reduction, narrow output: more row blocks, unsplit
+    (96, 4096, 192, dict(kind="skinny", m_blocks=3, mt=2, ksplit=1)),
+    (256, 5120, 128, dict(kind="skinny", m_blocks=3, mt=6, ksplit=1)),    # one more row block instead of eight row groups per workgroup
+    (640, 4096, 128, dict(kind="square")),                                # a skinny launch would exceed one workgroup per CU
+    (384, 11008, 128, dict(kind="big", wide=False)),                      # 129 tiles of 128 x 256: one round
+    (768, 11008, 128, dict(kind="big", wide=True)),                       # 172 tiles of 192 x 256 beat 516 of 128 x 128
+    (1040, 4096, 128, dict(kind="big", wide=False)),
+    (2080, 4096, 128, dict(kind="big", wide=True)),
+    (4, 4096, 256, dict(kind="gemv")),                                    # eight-wavefront GEMV, 16 rows per workgroup
+    (3, 16390, 256, dict(kind="gemv")),                                   # 32 rows per workgroup, ragged last workgroup
+])
+def test_linear_bf16_planner_branches(rows, N, d, want):
+    """One shape per branch of the GEMM planning above 80 rows (and the wide GEMV); the plan is
+    asserted first, so the case keeps testing the branch it was written for."""
+    plan = M.medusa_gemm_plan(rows, N, d, 1, True)
+    for key, value in want.items():
+        assert plan[key] == value, f"plan {plan}, wanted {want}"
+    linear_case("bf16", 1, rows, d, N, 0, 0, False, 440 + rows)
+    linear_case("bf16", 1, rows, d, N, 0, 0, True, 441 + rows)
+
+
 def test_linear_bf16_long_run_kernel():
     # 200 tiles of 128 columns at up to 80 rows, weights declared cold: the kernel that fetches 1 KB
     # runs, with the gated epilogue and with head-major activations on both sides
