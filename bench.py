@@ -301,9 +301,10 @@ def bench_block(args, cfg):
                  for w in sets]
         names = [{"tree_rope": "rotary", "tree_attention": "QK^T, PV", "tree_linear_swiglu": "X W_u, W_g"}.get(c[0], c[0])
                  for c in plans[0]]
-        lin_names = (["X W_QKV"] if names.index("rotary") == 1 else ["X W_Q", "X W_K", "X W_V"]) + (
+        n_proj = names.index("rotary")                 # projection calls in front of the rotary embedding: 1, 2 or 3
+        lin_names = {1: ["X W_QKV"], 2: ["X W_Q", "X W_KV"], 3: ["X W_Q", "X W_K", "X W_V"]}[n_proj] + (
             ["X W_d"] if "X W_u, W_g" in names else ["X W_u", "X W_g", "X W_d"])
-        names = [lin_names.pop(0) if nm == "tree_linear" else nm for nm in names]
+        names = [lin_names.pop(0) if nm in ("tree_linear", "tree_linear_segments") else nm for nm in names]
         for j, name in enumerate(names):
             for i in range(5):
                 _, fn, a = plans[i % n_sets][j]

@@ -240,6 +240,21 @@ int tree_linear(const void* x, const void* w, const void* mul, void* y, int B, i
                 int x_heads, int y_heads, medusa_dtype_t dtype, void* workspace, size_t workspace_bytes,
                 medusa_stream_t stream);
 
+/* tree_linear with the head-major output cut into y_segments tensors (App. G: X W_Q, X W_K and X W_V
+ * read the same X, so one call over the stacked weight rows [W_Q; W_K; W_V] streams X once and
+ * launches once): segment s takes the consecutive d_out / y_segments output columns
+ * s * d_out / y_segments .. and is a head-major tensor [B, y_heads, T, d_out / (y_segments * y_heads)]
+ * that starts y_segment_stride elements after segment s - 1 (y = start of segment 0).
+ *   y_heads          heads PER SEGMENT (> 0 when y_segments > 1)
+ *   y_segment_stride elements (not bytes) between segment starts, >= B * T * d_out / y_segments
+ * y_segments == 1 is tree_linear.  Everything else as for tree_linear; workspace size from
+ * tree_linear_workspace_bytes with the total d_out.  MEDUSA_EINVAL when d_out does not divide into
+ * y_segments x y_heads whole heads or the segments would overlap.
+ */
+int tree_linear_segments(const void* x, const void* w, const void* mul, void* y, int B, int T, int d_in, int d_out,
+                         int x_heads, int y_heads, int y_segments, size_t y_segment_stride, medusa_dtype_t dtype,
+                         void* workspace, size_t workspace_bytes, medusa_stream_t stream);
+
 /* tree_rope: rotary position embedding, in place, of q [B, Hq, T, D] and k [B, Hkv, T, D] (dtype)
  * at position_ids [B, T] (int32, device; the table medusa_topk_tree writes: prefix length +
  * depth of the node).  Element j < D/2 is paired with element j + D/2; the pair is rotated by

@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = (
     "medusa_tree_create_optimized", "medusa_tree_destroy",
     "medusa_tree_query", "medusa_tree_tables", "medusa_heads", "medusa_topk_tree_workspace_bytes",
     "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "medusa_accept_workspace_bytes",
-    "medusa_accept", "kv_commit", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_swiglu", "tree_rope",
+    "medusa_accept", "kv_commit", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "tree_rope",
     "medusa_profile_set_events",
     "medusa_set_cache_resident_bytes", "medusa_gemm_plan",
 )
@@ -73,6 +73,7 @@ def lib() -> ctypes.CDLL:
         L.tree_linear_workspace_bytes.argtypes = [c_int] * 5
         L.tree_linear.argtypes = [c_void_p] * 4 + [c_int] * 7 + [c_void_p, c_size_t, c_void_p]
         L.tree_linear_swiglu.argtypes = [c_void_p] * 3 + [c_int] * 7 + [c_void_p]
+        L.tree_linear_segments.argtypes = [c_void_p] * 4 + [c_int] * 7 + [c_size_t, c_int, c_void_p, c_size_t, c_void_p]
         L.tree_rope.argtypes = [c_void_p] * 3 + [c_int] * 5 + [c_float, c_int, c_void_p]
         L.medusa_profile_set_events.argtypes = [c_void_p, c_void_p]
         L.medusa_set_cache_resident_bytes.argtypes = [ctypes.c_size_t]
@@ -368,6 +369,37 @@ def tree_linear(x: torch.Tensor, w: torch.Tensor, B: int, T: int, mul: Optional[
                              None if workspace is None else workspace.data_ptr(),
                              0 if workspace is None else workspace.numel() * workspace.element_size(),
                              _stream(stream)), "tree_linear")
+    return y
+
+
+def tree_linear_segments(x: torch.Tensor, w: torch.Tensor, B: int, T: int, y: torch.Tensor, y_heads: int,
+                         workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """One projection call for several head-major outputs (Q, K, V): w is the stacked weight
+    [segments * y_heads * Dh, d_in] and y one tensor [segments, B, y_heads, T, Dh] whose slices y[s]
+    are the outputs.  x as for tree_linear."""
+    code = _dtype_code(x)
+    d_out, d_in = w.shape
+    if x.dim() == 2:
+        x_heads = 0
+        _dev(x, "x", shape=(B * T, d_in))
+    elif x.dim() == 4:
+        x_heads = int(x.shape[1])
+        _dev(x, "x", shape=(B, x_heads, T, d_in // max(x_heads, 1)))
+    else:
+        raise MedusaError("x must be [B*T, d_in] or [B, H, T, Dh]")
+    _dev(w, "w", dtype=x.dtype, shape=(d_out, d_in))
+    if y.dim() != 5 or y_heads < 1 or d_out % (int(y.shape[0]) * y_heads) != 0:
+        raise MedusaError("y must be [segments, B, y_heads, T, Dh] with segments * y_heads * Dh == d_out")
+    segments = int(y.shape[0])
+    _dev(y, "y", dtype=x.dtype, shape=(segments, B, y_heads, T, d_out // (segments * y_heads)))
+    if workspace is None:
+        need = tree_linear_workspace_bytes(B, T, d_in, d_out, x.dtype)
+        workspace = _scratch(need, x.device) if need else None
+    _check(lib().tree_linear_segments(x.data_ptr(), w.data_ptr(), None, y.data_ptr(), B, T, d_in, d_out, x_heads, y_heads,
+                                      segments, y[0].numel(), code,
+                                      None if workspace is None else workspace.data_ptr(),
+                                      0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                      _stream(stream)), "tree_linear_segments")
     return y
 
 

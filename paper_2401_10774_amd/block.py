@@ -26,14 +26,20 @@ class SimplifiedBlock:
         if B == 1:
             self.qkv = mk(1, Hq + 2 * Hkv, T, D)
             self.q, self.k, self.v = self.qkv[:, :Hq], self.qkv[:, Hq:Hq + Hkv], self.qkv[:, Hq + Hkv:]
-        else:
+        elif Hq == Hkv:                        # three head-major tensors of one allocation: one projection call can fill them
             self.qkv = None
-            self.q, self.k, self.v = mk(B, Hq, T, D), mk(B, Hkv, T, D), mk(B, Hkv, T, D)
+            self.qkv3 = mk(3, B, Hq, T, D)
+            self.q, self.k, self.v = self.qkv3[0], self.qkv3[1], self.qkv3[2]
+        else:                                  # grouped-query attention: K and V are the same size, Q is not
+            self.qkv = None
+            self.kv2 = mk(2, B, Hkv, T, D)
+            self.q, self.k, self.v = mk(B, Hq, T, D), self.kv2[0], self.kv2[1]
         self.attn = mk(B, Hq, T, D)
         self.up, self.act, self.out = mk(B * T, inter), mk(B * T, inter), mk(B * T, h)
         self.ws = _b._scratch(_b.tree_attention_workspace_bytes(B, Hq, Hkv, T, D, Lcap), device)
         need = max(_b.tree_linear_workspace_bytes(B, T, d_in, d_out, dtype)
-                   for d_in, d_out in ((h, Hq * D), (h, Hkv * D), (h, (Hq + 2 * Hkv) * D), (Hq * D, inter), (inter, h)))
+                   for d_in, d_out in ((h, Hq * D), (h, Hkv * D), (h, 2 * Hkv * D), (h, (Hq + 2 * Hkv) * D), (Hq * D, inter),
+                                       (inter, h)))
         self.ws_lin = _b._scratch(need, device)
         self._plans = {}
 
@@ -59,10 +65,17 @@ class SimplifiedBlock:
             "tree_linear", L.tree_linear, (p(xin), p(w), None if mul is None else p(mul), p(y), B, T, d_in, d_out, xh, yh,
                                            code, p(self.ws_lin), nb(self.ws_lin)))
         nbytes = lambda t: t.numel() * t.element_size()
-        fused = (self.qkv is not None and wk.data_ptr() == wq.data_ptr() + nbytes(wq)
-                 and wv.data_ptr() == wk.data_ptr() + nbytes(wk))
-        if fused:
+        seg = lambda w, y, d_out, yh, n_seg: (
+            "tree_linear_segments", L.tree_linear_segments, (p(x), p(w), None, p(y), B, T, h, d_out, 0, yh, n_seg, y[0].numel(),
+                                                             code, p(self.ws_lin), nb(self.ws_lin)))
+        kv_adjacent = wv.data_ptr() == wk.data_ptr() + nbytes(wk)
+        qkv_adjacent = kv_adjacent and wk.data_ptr() == wq.data_ptr() + nbytes(wq)
+        if self.qkv is not None and qkv_adjacent:      # one sequence: q, k, v are head ranges of one head-major tensor
             qkv_calls = [lin(x, wq, None, self.qkv, h, (Hq + 2 * Hkv) * D, 0, Hq + 2 * Hkv)]
+        elif B > 1 and Hq == Hkv and qkv_adjacent:     # a batch: three tensors, one call over the stacked weight rows
+            qkv_calls = [seg(wq, self.qkv3, 3 * Hq * D, Hq, 3)]
+        elif B > 1 and Hq != Hkv and kv_adjacent:
+            qkv_calls = [lin(x, wq, None, self.q, h, Hq * D, 0, Hq), seg(wk, self.kv2, 2 * Hkv * D, Hkv, 2)]
         else:
             qkv_calls = [lin(x, wq, None, self.q, h, Hq * D, 0, Hq), lin(x, wk, None, self.k, h, Hkv * D, 0, Hkv),
                          lin(x, wv, None, self.v, h, Hkv * D, 0, Hkv)]

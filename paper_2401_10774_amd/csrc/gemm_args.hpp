@@ -16,7 +16,8 @@ enum { EPI_LOGITS = 0, EPI_RESID = 1, EPI_PLAIN = 2, EPI_GATED = 3, EPI_SWIGLU =
 // X is either row-major with strides (x_dh == 0): X[m*xs_m + k*xs_k + j], or head-major
 // [B][x_heads][x_T][x_dh] with m = b*x_T + t and j = head*x_dh + e (the layout tree attention
 // writes).  The EPI_PLAIN / EPI_GATED output is row-major [M][N] (y_dh == 0) or head-major
-// [B][y_heads][y_T][y_dh] with n = head*y_dh + e (the layout tree attention reads).
+// [B][y_heads][y_T][y_dh] with n = head*y_dh + e (the layout tree attention reads), or several such
+// tensors a fixed stride apart, each taking y_heads consecutive heads of the N columns.
 struct GemmArgs {
   const void* W;       // [K][N][d]
   const void* X;       // activations
@@ -26,6 +27,8 @@ struct GemmArgs {
   long xs_m, xs_k;     // element strides of X between rows m and between heads k (row-major X)
   int x_T, x_heads, x_dh;
   int y_T, y_heads, y_dh;
+  int y_seg_heads;     // > 0: the head-major output is several tensors [B][y_heads][y_T][y_dh], y_seg_stride elements apart,
+  long y_seg_stride;   //      each taking y_seg_heads (= y_heads) consecutive heads of the N columns (Q, K, V of one projection call)
   int rows_per_wg;     // GEMV kernels: weight rows per workgroup (multiple of 8)
   int ksplit;          // skinny MFMA kernel: workgroups that share one output tile, each reducing 1/ksplit of d
   void* ws;            // their fp32 partial tiles (ksplit > 1)
@@ -61,8 +64,15 @@ __device__ __forceinline__ size_t out_row_offset(const GemmArgs& a, int m, int k
 template <bool HM>
 __device__ __forceinline__ size_t out_col_offset(const GemmArgs& a, int n) {
   if (!HM || a.y_dh == 0) return (size_t)n;
-  const int head = n / a.y_dh;
-  return (size_t)head * a.y_T * a.y_dh + (n - head * a.y_dh);
+  int head = n / a.y_dh;
+  const int e = n - head * a.y_dh;
+  size_t seg_off = 0;
+  if (a.y_seg_heads > 0) {
+    const int seg = head / a.y_seg_heads;
+    head -= seg * a.y_seg_heads;
+    seg_off = (size_t)seg * a.y_seg_stride;
+  }
+  return seg_off + (size_t)head * a.y_T * a.y_dh + e;
 }
 
 typedef __bf16 dot2_t __attribute__((__vector_size__(2 * sizeof(__bf16))));

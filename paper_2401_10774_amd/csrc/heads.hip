@@ -980,8 +980,20 @@ extern "C" size_t tree_linear_workspace_bytes(int B, int T, int d_in, int d_out,
 extern "C" int tree_linear(const void* x, const void* w, const void* mul, void* y, int B, int T, int d_in, int d_out,
                            int x_heads, int y_heads, medusa_dtype_t dtype, void* workspace, size_t workspace_bytes,
                            medusa_stream_t stream_) {
+  return tree_linear_segments(x, w, mul, y, B, T, d_in, d_out, x_heads, y_heads, 1, 0, dtype, workspace, workspace_bytes, stream_);
+}
+
+extern "C" int tree_linear_segments(const void* x, const void* w, const void* mul, void* y, int B, int T, int d_in, int d_out,
+                                    int x_heads, int y_heads, int y_segments, size_t y_segment_stride, medusa_dtype_t dtype,
+                                    void* workspace, size_t workspace_bytes, medusa_stream_t stream_) {
   if (!x || !w || !y) return MEDUSA_EINVAL;
-  if (B < 1 || T < 1 || d_in < 1 || d_out < 1 || x_heads < 0 || y_heads < 0) return MEDUSA_EINVAL;
+  if (B < 1 || T < 1 || d_in < 1 || d_out < 1 || x_heads < 0 || y_heads < 0 || y_segments < 1) return MEDUSA_EINVAL;
+  if (y_segments > 1) {
+    // several head-major tensors: whole heads per segment, segments that do not overlap
+    if (y_heads < 1 || d_out % y_segments != 0 || (d_out / y_segments) % y_heads != 0) return MEDUSA_EINVAL;
+    if (y_segment_stride < (size_t)B * T * (d_out / y_segments) || y_segment_stride > ((size_t)1 << 40)) return MEDUSA_EINVAL;
+    d_out /= y_segments;                                  // (per segment, for the layout arithmetic below)
+  }
   if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;
   const long M = (long)B * T;
   if (M > 4096 || d_in > 65536) return MEDUSA_EUNSUPPORTED;
@@ -995,7 +1007,7 @@ extern "C" int tree_linear(const void* x, const void* w, const void* mul, void* 
   a.hidden = mul;
   a.out = y;
   a.M = (int)M;
-  a.N = d_out;
+  a.N = d_out * y_segments;
   a.d = d_in;
   a.K = 1;
   a.xs_m = d_in;
@@ -1009,6 +1021,10 @@ extern "C" int tree_linear(const void* x, const void* w, const void* mul, void* 
     a.y_T = T;
     a.y_heads = y_heads;
     a.y_dh = d_out / y_heads;
+    if (y_segments > 1) {
+      a.y_seg_heads = y_heads;
+      a.y_seg_stride = (long)y_segment_stride;
+    }
   }
   // the split reduction is an optimisation: without (enough) workspace the call runs unsplit
   if (workspace && dtype == MEDUSA_BF16 && workspace_bytes >= gemm_ws_bytes(a.M, a.N, a.d, 1) && gemm_ws_bytes(a.M, a.N, a.d, 1) > 0)

@@ -82,6 +82,41 @@ def test_linear_bf16_planner_branches(rows, N, d, want):
     linear_case("bf16", 1, rows, d, N, 0, 0, True, 441 + rows)
 
 
+@pytest.mark.parametrize("dtype,B,T,d_in,heads,dh,segments,x_heads", [
+    ("bf16", 4, 89, 320, 5, 64, 3, 0),        # 356 rows, Q, K, V of equal size
+    ("bf16", 16, 65, 256, 2, 128, 2, 0),      # 1040 rows (large tiles), K and V of a grouped-query block
+    ("bf16", 2, 10, 512, 4, 32, 3, 8),        # few rows, head-major activations
+    ("bf16", 1, 3, 192, 3, 16, 2, 0),         # wave-per-row kernel
+    ("f32", 2, 7, 64, 2, 8, 3, 0),
+])
+def test_linear_segments(dtype, B, T, d_in, heads, dh, segments, x_heads):
+    """One call over the stacked weight rows fills `segments` head-major tensors; every segment must be
+    what tree_linear gives for its own rows of the weight (oracle: the plain definition per segment)."""
+    rows, d_out = B * T, segments * heads * dh
+    x = draw_normal(460, 0, (rows, d_in), 1.0, dtype)
+    w = draw_normal(460, 1, (d_out, d_in), 0.05, dtype)
+    xd = to_dev(x)
+    if x_heads:
+        xd = xd.view(B, T, x_heads, d_in // x_heads).permute(0, 2, 1, 3).contiguous()
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    y = torch.full((segments, B, heads, T, dh), float("nan"), dtype=tdt, device="cuda")
+    M.tree_linear_segments(xd, to_dev(w), B, T, y, heads)
+    torch.cuda.synchronize()
+    w64 = np.asarray(w)
+    for s_ in range(segments):
+        ref = O.tree_linear_ref(x, w64[s_ * heads * dh:(s_ + 1) * heads * dh], dtype)
+        got = O.from_heads(to_host_f64(y[s_]))
+        err = row_rel_err(got, ref)
+        assert err <= TOL[dtype], f"segment {s_}: rel err {err}"
+    lib = M.lib()
+    args = lambda seg, stride: (xd.data_ptr(), to_dev(w).data_ptr(), None, y.data_ptr(), B, T, d_in, d_out, x_heads, heads, seg,
+                                stride, 1 if dtype == "bf16" else 0, None, 0, None)
+    assert lib.tree_linear_segments(*args(segments, y[0].numel() - 1)) != 0      # segments would overlap
+    assert lib.tree_linear_segments(*args(0, y[0].numel())) != 0
+    if d_out % 7 != 0:
+        assert lib.tree_linear_segments(*args(7, y[0].numel())) != 0             # no whole heads per segment
+
+
 def test_linear_bf16_long_run_kernel():
     # 200 tiles of 128 columns at up to 80 rows, weights declared cold: the kernel that fetches 1 KB
     # runs, with the gated epilogue and with head-major activations on both sides
@@ -195,6 +230,9 @@ def block_case(dtype, branching, B, h, Hq, Hkv, D, inter, Lcap, prefix, seed, ad
                   to_dev(pl), to_dev(pos), scale, w_gu)
     if adjacent_qkv and B == 1:
         assert len(blk._plans) == 1 and len(next(iter(blk._plans.values()))) == (5 if fused_gate_up else 6)   # the fused form did run
+    if adjacent_qkv and B > 1:
+        names = [c[0] for c in next(iter(blk._plans.values()))]
+        assert names.count("tree_linear_segments") == 1 and names.index("tree_rope") == (1 if Hq == Hkv else 2)
     torch.cuda.synchronize()
     ref = O.simplified_block_ref(x, ws["wq"], ws["wk"], ws["wv"], ws["wu"], ws["wg"], ws["wd"], kc, vc, pl, pos, tree_o,
                                  Hq, Hkv, scale, theta, dtype)
@@ -238,6 +276,13 @@ def test_block_bf16_head_dim_128():
 def test_block_bf16_fused_gate_and_up():
     block_case("bf16", (3, 2, 1), 2, 512, 8, 2, 64, 1024, 700, [600, 37], 605, fused_gate_up=True)       # 2 x 16 rows
     block_case("bf16", (2, 2, 1), 1, 512, 4, 4, 128, 768, 400, [300], 606, adjacent_qkv=True, fused_gate_up=True)
+
+
+def test_block_bf16_batch_with_stacked_projection_weights():
+    # a batch with W_Q, W_K, W_V in one allocation: one call for three tensors (equal head counts) or
+    # one for Q and one for K and V (grouped-query attention)
+    block_case("bf16", (4, 3, 2, 1), 3, 512, 4, 4, 128, 768, 400, [300, 17, 380], 605, adjacent_qkv=True)
+    block_case("bf16", (3, 2, 1), 4, 512, 8, 2, 64, 1024, 300, [200, 0, 290, 100], 606, adjacent_qkv=True)
 
 
 def test_block_bf16_fused_qkv_projection():
