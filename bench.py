@@ -289,9 +289,10 @@ def bench_block(args, cfg):
     ms = start.elapsed_time(stop) / K
     mean_L = float(pl.float().mean())
     M_rows = B * T
+    fused_gate_up = any(c[0] == "tree_linear_swiglu" for c in next(iter(blk._plans.values())))
     w_bytes = (Hq * D * h + 2 * Hkv * D * h + 2 * inter * Hq * D + h * inter) * es
     act_bytes = (3 * M_rows * h + 2 * M_rows * (Hq + 2 * Hkv) * D + 2 * M_rows * Hq * D + 3 * M_rows * Hq * D
-                 + (2 if dt == torch.bfloat16 and M_rows <= 80 else 4) * M_rows * inter + M_rows * h) * es   # (fused gate/up: no `up` round trip)
+                 + (2 if fused_gate_up else 4) * M_rows * inter + M_rows * h) * es   # (fused gate/up: no `up` round trip)
     kv_bytes = int(2 * B * Hkv * mean_L * D * es)
     total = w_bytes + act_bytes + kv_bytes
     flops = 2.0 * M_rows * (Hq * D * h + 2 * Hkv * D * h + 2 * inter * Hq * D + h * inter) + 4.0 * B * Hq * T * (mean_L + T) * D
@@ -378,7 +379,7 @@ def bench_speed_model(args, cfg):
                 w = wsets[i % n_sets]
                 kc, vc = caches[i % len(caches)]
                 blk.run(x, w["wq"], w["wk"], w["wv"], w["wu"], w["wg"], w["wd"], kc, vc, pl, pos, scale,
-                        w["wgu"] if B * T > 4 else None)      # (plain decoding keeps the wave-per-row kernels; the block falls back to two calls above 80 rows)
+                        w["wgu"] if B * T > 4 else None)      # (plain decoding keeps the wave-per-row kernels; the block itself decides where the fused pass pays)
 
             for i in range(12):
                 run(i)

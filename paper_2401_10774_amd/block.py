@@ -85,7 +85,10 @@ class SimplifiedBlock:
                                                   self.tree.handle, p(self.attn), B, Hq, Hkv, D, self.Lcap, float(scale),
                                                   code, p(self.ws), nb(self.ws))),
         ]
-        if w_gu is not None and B * T <= 80:       # (one row block of the fused kernel; beyond, two calls are faster)
+        # gate and up in one pass: up to 80 rows (one row block of the skinny kernel) and wherever the
+        # planning gives the stacked projection the large-tile kernel; in between two calls are faster
+        fuse_gu = w_gu is not None and (B * T <= 80 or _b.medusa_gemm_plan(B * T, 2 * inter, Hq * D, 1, False)["kind"] == "big")
+        if fuse_gu:
             _b._dev(w_gu, "w_gu", dtype=dt, shape=(2 * inter, Hq * D))
             plan.append(("tree_linear_swiglu", L.tree_linear_swiglu, (p(self.attn), p(w_gu), p(self.act), B, T, Hq * D, inter,
                                                                       Hq, 0, code)))

@@ -156,7 +156,12 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
   // area (fp32, row pitch 132 words: conflict-free both ways) and reads it back with 8 consecutive
   // columns per lane: 16- and 32-byte accesses, four lanes covering a contiguous 32-column run.
   __syncthreads();                                    // every wavefront is done with the stage buffers
-  constexpr int EP_PITCH = 16 * NT + 4;               // words
+  // EPI_SWIGLU: fragments 2j and 2j+1 of a wavefront are the gate rows and the up rows of the same 16
+  // output columns (weights interleaved in blocks of 16 rows), so half as many fragments leave.
+  constexpr bool SW = EPI == EPI_SWIGLU;
+  constexpr int NTO = SW ? NT / 2 : NT;
+  const int n_cols = SW ? a.N >> 1 : a.N, n_base = (SW ? n0 >> 1 : n0) + wn * 16 * NTO;
+  constexpr int EP_PITCH = 16 * NTO + 4;              // words
   float* ep = (float*)lds + wave * 16 * EP_PITCH;
   static_assert(4 * 16 * EP_PITCH * 4 <= 2 * STAGE, "epilogue area must fit the stage buffers");
   const int er = lane >> 2, ec = (lane & 3) * 8;      // read-back: row, first column of the lane's 8
@@ -164,19 +169,20 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
 #pragma unroll
   for (int t = 0; t < MT; ++t) {
 #pragma unroll
-    for (int j = 0; j < NT; ++j)
+    for (int j = 0; j < NTO; ++j)
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ep[(4 * q4 + r) * EP_PITCH + j * 16 + i16] = acc[t][j][r];
+      for (int r = 0; r < 4; ++r)
+        ep[(4 * q4 + r) * EP_PITCH + j * 16 + i16] = SW ? silu_fast(acc[t][2 * j][r]) * acc[t][2 * j + 1][r] : acc[t][j][r];
     const int m = m0 + (wm * MT + t) * 16 + er;
-    const size_t row_off = m < a.M ? out_row_offset<kHeadMajor<EPI>>(a, m, k) : 0;
+    const size_t row_off = m >= a.M ? 0 : (SW && a.y_dh == 0 ? (size_t)m * n_cols : out_row_offset<kHeadMajor<EPI>>(a, m, k));
 #pragma unroll
-    for (int c = 0; c < NT / 2; ++c) {
+    for (int c = 0; c < NTO / 2; ++c) {
       const floatx4_t v0 = *(const floatx4_t*)(ep + er * EP_PITCH + c * 32 + ec);
       const floatx4_t v1 = *(const floatx4_t*)(ep + er * EP_PITCH + c * 32 + ec + 4);
       const float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-      const int n = n0 + wn * 16 * NT + c * 32 + ec;
-      if (m >= a.M || n >= a.N) continue;
-      if (vec && n + 8 <= a.N) {
+      const int n = n_base + c * 32 + ec;
+      if (m >= a.M || n >= n_cols) continue;
+      if (vec && n + 8 <= n_cols) {
         const size_t o = row_off + out_col_offset<kHeadMajor<EPI>>(a, n);
         if (EPI == EPI_LOGITS) {
           float* dst = (float*)a.out + o;
@@ -184,7 +190,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
           *(floatx4_t*)(dst + 4) = v1;
         } else {
           float y[8];
-          if (EPI == EPI_PLAIN) {
+          if (EPI == EPI_PLAIN || SW) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = v[e];
           } else {
@@ -207,11 +213,11 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
       } else {
         // ragged or unaligned output: one element at a time
         for (int e = 0; e < 8; ++e) {
-          if (n + e >= a.N) break;
+          if (n + e >= n_cols) break;
           const size_t o = row_off + out_col_offset<kHeadMajor<EPI>>(a, n + e);
           if (EPI == EPI_LOGITS) {
             ((float*)a.out)[o] = v[e];
-          } else if (EPI == EPI_PLAIN) {
+          } else if (EPI == EPI_PLAIN || SW) {
             ((uint16_t*)a.out)[o] = (uint16_t)float_to_bf16_bits(v[e]);
           } else {
             const float u = bf16_bits_to_float(((const uint16_t*)a.hidden)[(size_t)m * a.N + n + e]);
@@ -229,7 +235,7 @@ int launch(const GemmArgs& a_in, bool tall, hipStream_t stream) {
   // 16-byte epilogue accesses need 8-column runs that are contiguous and aligned in the output and
   // in the tensor the epilogue reads
   const size_t align = (size_t)a.out | (size_t)(EPI == EPI_RESID || EPI == EPI_GATED ? a.hidden : nullptr);
-  a.vec_epilogue = a.N % 8 == 0 && align % 16 == 0 && (a.y_dh == 0 || a.y_dh % 8 == 0) ? 1 : 0;
+  a.vec_epilogue = (EPI == EPI_SWIGLU ? a.N % 16 == 0 : a.N % 8 == 0) && align % 16 == 0 && (a.y_dh == 0 || a.y_dh % 8 == 0) ? 1 : 0;
   // 192 x 256 or 128 x 256 tile, as the caller planned
   const int n_tiles = ceil_div(a.N, 256);
   const int m_tiles = ceil_div(a.M, tall ? 192 : 128);
@@ -250,6 +256,7 @@ int launch_gemm_big(const GemmArgs& a, int epi, bool tall, hipStream_t stream) {
     case EPI_RESID: return launch<EPI_RESID>(a, tall, stream);
     case EPI_PLAIN: return launch<EPI_PLAIN>(a, tall, stream);
     case EPI_GATED: return launch<EPI_GATED>(a, tall, stream);
+    case EPI_SWIGLU: return launch<EPI_SWIGLU>(a, tall, stream);
   }
   return MEDUSA_EINVAL;
 }

@@ -1066,12 +1066,18 @@ extern "C" int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int 
     a.y_heads = y_heads;
     a.y_dh = d_out / y_heads;
   }
+  hipStream_t stream = (hipStream_t)stream_;
+  // Many rows (a batch of trees): the large-tile kernel, if the planning gives it this shape
+  if (a.M > 80) {
+    const bool wide_offsets = (size_t)a.N * a.d >= ((size_t)1 << 31) || x_extent(a) >= ((size_t)1 << 31);
+    const GemmPlan plan = plan_gemm(a.M, a.N, a.d, 1, false, wide_offsets);
+    if (plan.kind == GemmPlan::BIG) return launch_gemm_big(a, EPI_SWIGLU, plan.wide, stream);
+  }
   // 128-column tiles (gate and up fragments of a column block side by side in a wavefront), row blocks
   // of at most 80 rows, never split: tuned for the tree-token range, correct for any M
   const int m_blocks = ceil_div(a.M, 80), mt = ceil_div(ceil_div(a.M, m_blocks), 16);
   const dim3 grid(ceil_div(a.N, 128), 1, m_blocks);
   const bool runs = (size_t)a.N * a.d * sizeof(uint16_t) > g_llc_bytes;
-  hipStream_t stream = (hipStream_t)stream_;
   int rc = MEDUSA_OK;
 #define MEDUSA_SWIGLU(MT_)                                                                                                \
   case MT_:                                                                                                               \

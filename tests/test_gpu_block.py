@@ -141,7 +141,10 @@ def interleave16(wg, wu):
 
 @pytest.mark.parametrize("B,T,d_in,d_out,x_heads,y_heads,cold", [
     (1, 65, 512, 384, 0, 0, False), (1, 65, 512, 384, 4, 0, True), (2, 50, 256, 1008, 0, 3, False),
-    (1, 5, 192, 64, 0, 0, False), (1, 1, 128, 48, 0, 0, False), (4, 89, 320, 400, 0, 0, True), (1, 33, 1024, 2064, 8, 0, True)])
+    (1, 5, 192, 64, 0, 0, False), (1, 1, 128, 48, 0, 0, False), (4, 89, 320, 400, 0, 0, True), (1, 33, 1024, 2064, 8, 0, True),
+    # many rows: the large-tile kernel's epilogue (192- and 128-row tiles, ragged last column tile, both layouts)
+    (16, 65, 128, 2688, 0, 0, False), (4, 89, 192, 6928, 3, 0, False), (16, 65, 128, 2560, 2, 20, False),
+    (4, 89, 64, 13840, 0, 0, False)])
 def test_linear_swiglu_bf16(B, T, d_in, d_out, x_heads, y_heads, cold):
     seed = 700 + B * T
     M_rows = B * T
@@ -153,6 +156,8 @@ def test_linear_swiglu_bf16(B, T, d_in, d_out, x_heads, y_heads, cold):
         xd = to_dev(np.ascontiguousarray(x.reshape(B, T, x_heads, d_in // x_heads).transpose(0, 2, 1, 3)))
     w_gu = to_dev(interleave16(wg, wu))
     assert torch.equal(w_gu, M.interleave_gate_up(to_dev(wg), to_dev(wu)))
+    if M_rows > 100 and d_out >= 2560:
+        assert M.medusa_gemm_plan(M_rows, 2 * d_out, d_in, 1, False)["kind"] == "big"      # (the case is here for that kernel)
     M.medusa_set_cache_resident_bytes(0 if cold else 256 << 20)
     try:
         y = M.tree_linear_swiglu(xd, w_gu, B, T, y_heads=y_heads)
