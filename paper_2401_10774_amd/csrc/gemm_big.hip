@@ -33,7 +33,17 @@ __device__ __forceinline__ float silu_fast(float u) {
   return u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * u));
 }
 
-template <int MT, int NT, int EPI>
+// Ticket counters of the split reduction (one per output tile and head); zero between launches.
+// Shared by all calls on a GPU: calls that overlap on different streams would race.
+constexpr int kMaxBigSplitTiles = 4096;
+__device__ unsigned int g_big_ticket[kMaxBigSplitTiles];
+
+// SPLIT: grid.z workgroups share an output tile, each reducing a contiguous 1/grid.z of d; they park
+// their fp32 partial tiles in the workspace and the one that finishes last adds them up in split
+// order (so the result does not depend on which one that is) and runs the epilogue.  For long
+// reductions into few tiles (the down projection of a batch of trees): 96 tiles of 192 x 256 over
+// d = 11008 keep 96 CUs busy for 240 us unsplit.
+template <int MT, int NT, int EPI, bool SPLIT = false>
 __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m_tiles, int n_tiles) {
   constexpr int BM = 32 * MT, BN = 32 * NT, ROWS = BM + BN;
   constexpr int LPT = ROWS / 32;                      // 16-byte chunks per thread and stage
@@ -64,10 +74,13 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
     goff[it] = it < MT ? (uint32_t)((x_row_offset<kHeadMajor<EPI>>(a, min(m0 + row, a.M - 1), k) + c * 8) * 2)
                        : (uint32_t)(((size_t)min(n0 + row - BM, a.N - 1) * a.d + c * 8) * 2);
   }
-  const int nk = a.d >> 6;
+  const int nk_all = a.d >> 6;
+  const int n_split = SPLIT ? (int)gridDim.z : 1, split = SPLIT ? (int)blockIdx.z : 0;
+  const int step0 = (int)((long)nk_all * split / n_split);
+  const int nk = (int)((long)nk_all * (split + 1) / n_split) - step0;   // this workgroup's share of the reduction (>= 1)
   u32x4_t G[LPT];
   auto gload = [&](int step, u32x4_t (&g)[LPT]) __attribute__((always_inline)) {
-    const int j0 = min(step, nk - 1) * 64;                       // past the end: harmless reload
+    const int j0 = (step0 + min(step, nk - 1)) * 64;             // past the end: harmless reload
     const uint32_t so_w = (uint32_t)j0 * 2u;
     const uint32_t so_x = (uint32_t)x_col_offset<kHeadMajor<EPI>>(a, j0) * 2u;    // differs from so_w for head-major activations
 #pragma unroll
@@ -155,6 +168,50 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
   // accesses.  Each wavefront therefore passes its tile, 16 rows at a time, through a private LDS
   // area (fp32, row pitch 132 words: conflict-free both ways) and reads it back with 8 consecutive
   // columns per lane: 16- and 32-byte accesses, four lanes covering a contiguous 32-column run.
+  if (SPLIT && n_split > 1) {
+    // partial tile of this split: [fragment][register pair][thread], 8 bytes per thread and store
+    const unsigned int tile = blockIdx.y * gridDim.x + blockIdx.x;
+    constexpr int PART = MT * NT * 2 * 256;            // 8-byte words per partial tile
+    uint64_t* part = (uint64_t*)a.ws + (size_t)tile * n_split * PART;
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int rp = 0; rp < 2; ++rp) {
+          const uint64_t v = (uint64_t)__float_as_uint(acc[t][j][2 * rp]) | ((uint64_t)__float_as_uint(acc[t][j][2 * rp + 1]) << 32);
+          store_agent(part + (size_t)split * PART + ((t * NT + j) * 2 + rp) * 256 + tid, v);
+        }
+    if (!last_workgroup_of(&g_big_ticket[tile], (unsigned int)n_split)) return;
+    // sum in split order; half a tile of one split is requested at a time (the other half of the
+    // register file holds the sums)
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) acc[t][j] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+    for (int z = 0; z < n_split; ++z) {
+      const uint64_t* pz = part + (size_t)z * PART + tid;
+#pragma unroll
+      for (int t0 = 0; t0 < MT; t0 += MT / 2) {
+        uint64_t v[MT / 2][NT][2];
+#pragma unroll
+        for (int t = 0; t < MT / 2; ++t)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int rp = 0; rp < 2; ++rp) v[t][j][rp] = load_agent(pz + (((t0 + t) * NT + j) * 2 + rp) * 256);
+#pragma unroll
+        for (int t = 0; t < MT / 2; ++t)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int rp = 0; rp < 2; ++rp) {
+              acc[t0 + t][j][2 * rp] += __uint_as_float((uint32_t)v[t][j][rp]);
+              acc[t0 + t][j][2 * rp + 1] += __uint_as_float((uint32_t)(v[t][j][rp] >> 32));
+            }
+      }
+    }
+  }
   __syncthreads();                                    // every wavefront is done with the stage buffers
   // EPI_SWIGLU: fragments 2j and 2j+1 of a wavefront are the gate rows and the up rows of the same 16
   // output columns (weights interleaved in blocks of 16 rows), so half as many fragments leave.
@@ -239,9 +296,17 @@ int launch(const GemmArgs& a_in, bool tall, hipStream_t stream) {
   // 192 x 256 or 128 x 256 tile, as the caller planned
   const int n_tiles = ceil_div(a.N, 256);
   const int m_tiles = ceil_div(a.M, tall ? 192 : 128);
-  const dim3 grid(8 * ceil_div(n_tiles, 8) * m_tiles, a.K), block(256);
-  if (tall) hipLaunchKernelGGL((gemm_big_bf16_kernel<6, 8, EPI>), grid, block, 0, stream, a, m_tiles, n_tiles);
-  else hipLaunchKernelGGL((gemm_big_bf16_kernel<4, 8, EPI>), grid, block, 0, stream, a, m_tiles, n_tiles);
+  constexpr bool kCanSplit = EPI == EPI_PLAIN || EPI == EPI_GATED;     // (the epilogues tree_linear uses)
+  const int gx = 8 * ceil_div(n_tiles, 8) * m_tiles;
+  const int ksplit = kCanSplit && a.ws && a.ksplit > 1 && (long)gx * a.K <= kMaxBigSplitTiles ? a.ksplit : 1;
+  const dim3 grid(gx, a.K, ksplit), block(256);
+  if (ksplit > 1) {
+    if (tall) hipLaunchKernelGGL((gemm_big_bf16_kernel<6, 8, EPI, kCanSplit>), grid, block, 0, stream, a, m_tiles, n_tiles);
+    else hipLaunchKernelGGL((gemm_big_bf16_kernel<4, 8, EPI, kCanSplit>), grid, block, 0, stream, a, m_tiles, n_tiles);
+  } else {
+    if (tall) hipLaunchKernelGGL((gemm_big_bf16_kernel<6, 8, EPI>), grid, block, 0, stream, a, m_tiles, n_tiles);
+    else hipLaunchKernelGGL((gemm_big_bf16_kernel<4, 8, EPI>), grid, block, 0, stream, a, m_tiles, n_tiles);
+  }
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;
 }

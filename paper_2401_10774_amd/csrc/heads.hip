@@ -751,6 +751,7 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
     double best = 1e30;
     int pick = GemmPlan::SKINNY;
     bool tall = false;
+    int big_split = 1;
     if (sq_tiles >= 200 || skinny_tiles > 256) {
       const long n = (sq_tiles + 255) / 256;
       static const double t_sq[5] = {0., 65., 88., 140., 150.};
@@ -764,10 +765,32 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
         const double t = (r == 128 ? 68.0 : 88.0) * scale * (double)((tiles + 255) / 256) + 0.6 * w_us;
         if (t < best) { best = t; pick = GemmPlan::BIG; tall = r == 192; }
       }
+      // A long reduction into few large tiles (the down projection of a batch of trees: M = 1040,
+      // 11008 -> 4096 is 96 tiles of 192 x 256) can be split over 2 or 4 workgroups per tile when there
+      // is a workspace.  Each split costs its partial tile (r KB) a write-through, a ticket and an
+      // agent-scope read, measured at 15-25 us for two and 20-70 us for four splits, so a split plan
+      // has to beat the best unsplit one (the skinny launch, where it fits one workgroup per CU, priced
+      // at 37 us per 4096 reduction elements) by a fifth, and must fit one round on every die: column
+      // tiles go round-robin over the 8 dies of 32 CUs each.  Measured: M = 1040, 11008 -> 4096
+      // 195 -> 145 us; M = 640: 150 -> 110.
+      if (have_ws) {
+        double unsplit = best;
+        if (skinny_tiles <= 256 && 37.0 * scale < unsplit) unsplit = 37.0 * scale;
+        double best_split = 0.8 * unsplit;
+        for (int r = 128; r <= 192; r += 64)
+          for (int sp = 2; sp <= 4; sp *= 2) {
+            const long tiles = (long)ceil_div(M, r) * ceil_div(N, 256) * K;
+            const long per_die = (long)ceil_div(ceil_div(N, 256), 8) * ceil_div(M, r) * K * sp;
+            if (tiles < 32 || per_die > 32 || (d / 64) / sp < 16) continue;
+            const double t = (r == 128 ? 68.0 : 88.0) * scale / sp + 0.6 * w_us + (sp == 2 ? 25.0 : 45.0);
+            if (t < best_split) { best_split = t; pick = GemmPlan::BIG; tall = r == 192; big_split = sp; }
+          }
+      }
     }
     if (pick == GemmPlan::BIG) {
       p.kind = GemmPlan::BIG;
       p.wide = tall;                                        // (for this kind: 192-row tiles)
+      p.ksplit = big_split;
       return p;
     }
     if (pick == GemmPlan::SQUARE) {
@@ -824,6 +847,10 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
 // Workspace for the fp32 partial tiles of a split reduction (0 if this shape is not split).
 size_t gemm_ws_bytes(int M, int N, int d, int K) {
   const GemmPlan p = plan_gemm(M, N, d, K, true, false);
+  if (p.kind == GemmPlan::BIG && p.ksplit > 1) {            // partial tiles of the large-tile kernel: rows x 256 floats each
+    const int rows = p.wide ? 192 : 128;
+    return (size_t)8 * ceil_div(ceil_div(N, 256), 8) * ceil_div(M, rows) * K * p.ksplit * rows * 256 * sizeof(float);
+  }
   if (p.kind != GemmPlan::SKINNY || p.ksplit <= 1) return 0;
   const int frags = p.mt * (p.wide ? 2 : 1);                // accumulator fragments per thread
   return (size_t)ceil_div(N, p.wide ? 128 : 64) * K * p.m_blocks * p.ksplit * frags * 4 * 256 * sizeof(float);
@@ -887,7 +914,10 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
   } else {
     const bool wide_offsets = (size_t)a.N * a.d >= ((size_t)1 << 31) || x_extent(a) >= ((size_t)1 << 31);
     const GemmPlan plan = plan_gemm(a.M, a.N, a.d, a.K, a.ws != nullptr, wide_offsets);
-    if (plan.kind == GemmPlan::BIG) return launch_gemm_big(a, EPI, plan.wide, stream);
+    if (plan.kind == GemmPlan::BIG) {
+      a.ksplit = plan.ksplit;
+      return launch_gemm_big(a, EPI, plan.wide, stream);
+    }
     const bool wide = plan.wide;
     a.ksplit = plan.ksplit;
     // split reductions exist for the epilogues tree_linear uses (medusa_heads passes no workspace)
