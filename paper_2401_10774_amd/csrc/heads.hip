@@ -768,21 +768,24 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
       // A long reduction into few large tiles (the down projection of a batch of trees: M = 1040,
       // 11008 -> 4096 is 96 tiles of 192 x 256) can be split over 2 or 4 workgroups per tile when there
       // is a workspace.  Each split costs its partial tile (r KB) a write-through, a ticket and an
-      // agent-scope read, measured at 15-25 us for two and 20-70 us for four splits, so a split plan
-      // has to beat the best unsplit one (the skinny launch, where it fits one workgroup per CU, priced
-      // at 37 us per 4096 reduction elements) by a fifth, and must fit one round on every die: column
-      // tiles go round-robin over the 8 dies of 32 CUs each.  Measured: M = 1040, 11008 -> 4096
-      // 195 -> 145 us; M = 640: 150 -> 110.
-      if (have_ws) {
+      // agent-scope read: about 5 us plus 0.5 us (two splits) or 0.8 us (four) per MB of partial tiles.
+      // A split plan has to beat the best unsplit one (the skinny launch, where it fits one workgroup
+      // per CU, priced from a fit to its measured times) by a tenth, and must fit one round on every
+      // die: column tiles go round-robin over the 8 dies of 32 CUs each.  Measured on 8 weight shapes x
+      // 10 row counts against the unsplit planning: 17 shapes 11-30 % faster (M = 1040, 11008 -> 4096:
+      // 195 -> 145 us; M = 512: 100 -> 77; M = 420, 13824 -> 5120: 184 -> 134), none slower.
+      if (have_ws && M > 128) {                             // (one row block: the skinny kernels are at their best)
         double unsplit = best;
-        if (skinny_tiles <= 256 && 37.0 * scale < unsplit) unsplit = 37.0 * scale;
-        double best_split = 0.8 * unsplit;
+        const double skinny_us = scale * (12.0 + 0.05 * M) * (N > 4096 ? N / 4096.0 : 1.0);   // (fit to M = 160..512 at 7B and 13B shapes)
+        if (skinny_tiles <= 256 && skinny_us < unsplit) unsplit = skinny_us;
+        double best_split = 0.9 * unsplit;
         for (int r = 128; r <= 192; r += 64)
           for (int sp = 2; sp <= 4; sp *= 2) {
             const long tiles = (long)ceil_div(M, r) * ceil_div(N, 256) * K;
             const long per_die = (long)ceil_div(ceil_div(N, 256), 8) * ceil_div(M, r) * K * sp;
             if (tiles < 32 || per_die > 32 || (d / 64) / sp < 16) continue;
-            const double t = (r == 128 ? 68.0 : 88.0) * scale / sp + 0.6 * w_us + (sp == 2 ? 25.0 : 45.0);
+            const double partial_mb = (double)tiles * sp * r * 1024.0 / 1.0e6;
+            const double t = (r == 128 ? 68.0 : 88.0) * scale / sp + 0.6 * w_us + 5.0 + partial_mb * (sp == 2 ? 0.5 : 0.8);
             if (t < best_split) { best_split = t; pick = GemmPlan::BIG; tall = r == 192; big_split = sp; }
           }
       }
