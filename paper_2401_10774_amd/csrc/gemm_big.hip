@@ -56,7 +56,10 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, q4 = lane >> 4;
   const int wm = wave >> 1, wn = wave & 1;
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  // (with a split reduction the column tiles of split s are rotated by 8/splits * s dies: when the
+  // number of column tiles is no multiple of 8, every die is then short of a tile in some splits
+  // instead of the same dies in all of them)
+  const int xcd = (blockIdx.x + (SPLIT ? (8 / (int)gridDim.z) * (int)blockIdx.z : 0)) & 7, slot = blockIdx.x >> 3;
   const int nt_local = slot / m_tiles;
   const int n_tile = nt_local * 8 + xcd;
   if (n_tile >= n_tiles) return;                      // whole workgroup leaves before any barrier
@@ -170,7 +173,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
   // columns per lane: 16- and 32-byte accesses, four lanes covering a contiguous 32-column run.
   if (SPLIT && n_split > 1) {
     // partial tile of this split: [fragment][register pair][thread], 8 bytes per thread and store
-    const unsigned int tile = blockIdx.y * gridDim.x + blockIdx.x;
+    const unsigned int tile = blockIdx.y * gridDim.x + (slot << 3 | xcd);   // (the same for all splits of a tile: xcd is the rotated one)
     constexpr int PART = MT * NT * 2 * 256;            // 8-byte words per partial tile
     uint64_t* part = (uint64_t*)a.ws + (size_t)tile * n_split * PART;
 #pragma unroll

@@ -771,7 +771,7 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
       // agent-scope read: about 5 us plus 0.5 us (two splits) or 0.8 us (four) per MB of partial tiles.
       // A split plan has to beat the best unsplit one (the skinny launch, where it fits one workgroup
       // per CU, priced from a fit to its measured times) by a tenth, and must fit one round on every
-      // die: column tiles go round-robin over the 8 dies of 32 CUs each.  Measured on 8 weight shapes x
+      // die: column tiles go round-robin over the 8 dies of 32 CUs each, rotated from split to split.  Measured on 8 weight shapes x
       // 10 row counts against the unsplit planning: 17 shapes 11-30 % faster (M = 1040, 11008 -> 4096:
       // 195 -> 145 us; M = 512: 100 -> 77; M = 420, 13824 -> 5120: 184 -> 134), none slower.
       if (have_ws && M > 128) {                             // (one row block: the skinny kernels are at their best)
@@ -782,7 +782,15 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
         for (int r = 128; r <= 192; r += 64)
           for (int sp = 2; sp <= 4; sp *= 2) {
             const long tiles = (long)ceil_div(M, r) * ceil_div(N, 256) * K;
-            const long per_die = (long)ceil_div(ceil_div(N, 256), 8) * ceil_div(M, r) * K * sp;
+            // workgroups on the busiest die: die x takes the column tiles c = x + 8/sp * s (mod 8) of split s
+            const int n_col = ceil_div(N, 256);
+            long per_die = 0;
+            for (int x = 0; x < 8; ++x) {
+              long cols = 0;
+              for (int z = 0; z < sp; ++z) cols += n_col / 8 + (((x + 8 / sp * z) & 7) < n_col % 8 ? 1 : 0);
+              per_die = cols > per_die ? cols : per_die;
+            }
+            per_die *= (long)ceil_div(M, r) * K;
             if (tiles < 32 || per_die > 32 || (d / 64) / sp < 16) continue;
             const double partial_mb = (double)tiles * sp * r * 1024.0 / 1.0e6;
             const double t = (r == 128 ? 68.0 : 88.0) * scale / sp + 0.6 * w_us + 5.0 + partial_mb * (sp == 2 ? 0.5 : 0.8);

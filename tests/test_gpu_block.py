@@ -71,6 +71,8 @@ def test_linear_bf16_large_tile_kernel():
     (2080, 4096, 128, dict(kind="big", wide=True)),
     (640, 4096, 8192, dict(kind="big", wide=False, ksplit=2)),            # long reduction into few large tiles: split over workgroups
     (640, 4096, 11008, dict(kind="big", wide=True, ksplit=4)),
+    (420, 5000, 8192, dict(kind="big", wide=False, ksplit=2)),            # 20 column tiles, ragged: rotated over the dies per split
+    (356, 5110, 13824, dict(kind="big", wide=False, ksplit=4)),
     (1040, 4096, 11008, dict(kind="big", wide=True, ksplit=2)),
     (4, 4096, 256, dict(kind="gemv")),                                    # eight-wavefront GEMV, 16 rows per workgroup
     (3, 16390, 256, dict(kind="gemv")),                                   # 32 rows per workgroup, ragged last workgroup
