@@ -762,7 +762,13 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
       for (int r = 128; r <= 192; r += 64) {
         const long tiles = (long)ceil_div(M, r) * ceil_div(N, 256) * K;
         if (tiles < 120) continue;
-        const double t = (r == 128 ? 68.0 : 88.0) * scale * (double)((tiles + 255) / 256) + 0.6 * w_us;
+        // rounds: the busiest die decides (column tiles go round-robin over 8 dies of 32 CUs: 20 column
+        // tiles x 12 row tiles are 240 tiles, yet 36 of them land on each of four dies)
+        // (a last round of only a few workgroups runs faster than a full one: 0.6 + 0.4 x its fill)
+        const long on_die = (long)ceil_div(ceil_div(N, 256), 8) * ceil_div(M, r) * K;
+        const double die_rounds = on_die <= 32 ? 1.0 : (double)(on_die / 32) + (on_die % 32 ? 0.6 + 0.4 * (on_die % 32) / 32.0 : 0.0);
+        const double rounds = die_rounds > (double)((tiles + 255) / 256) ? die_rounds : (double)((tiles + 255) / 256);
+        const double t = (r == 128 ? 68.0 : 88.0) * scale * rounds + 0.6 * w_us;
         if (t < best) { best = t; pick = GemmPlan::BIG; tall = r == 192; }
       }
       // A long reduction into few large tiles (the down projection of a batch of trees: M = 1040,
