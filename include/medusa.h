@@ -213,6 +213,22 @@ int kv_commit(void* k_cache, void* v_cache, const void* k_tree, const void* v_tr
               medusa_stream_t stream);
 
 /* ----------------------------------------------------------------------------------
+ * medusa_carry_over (Sec. 2, opening paragraph; Fig. 1 caption): the activations the next decoding
+ * step starts from.  Its Medusa heads read the hidden state of the last accepted token, and its root
+ * token is the original model's prediction there, whose logits step (2) has already produced:
+ *   h_next[b,:]  = hidden_tree[b, best_node[b], :]
+ *   lm_next[b,:] = verify_logits[b, best_node[b], :]
+ *   hidden_tree   [B, T, d] dtype    the backbone's last hidden states of the tree tokens
+ *   verify_logits [B, T, V] fp32     the logits medusa_heads(w1 == NULL) wrote for them
+ *   best_node     [B] int32          from medusa_accept (values are clamped to [0, T-1])
+ *   h_next        [B, d] dtype out;  lm_next [B, V] fp32 out (the lm_logits of the next medusa_topk_tree)
+ * Either (input, output) pair may be NULL together to skip it.  Outputs must not alias the inputs.
+ * Raw row copies: bit-exact.  Limits: B <= 65535; bf16: d even.
+ * -------------------------------------------------------------------------------- */
+int medusa_carry_over(const void* hidden_tree, const float* verify_logits, const int32_t* best_node, void* h_next,
+                      float* lm_next, int B, int T, int d, int V, medusa_dtype_t dtype, medusa_stream_t stream);
+
+/* ----------------------------------------------------------------------------------
  * Backbone operators on the tree tokens (App. G: operator table, "Parallel decoding" rows
  * X W_Q, X W_K, X W_V, X W_u, X W_g, X W_d; Sec. 2.1.2 for the positional indices).  Together
  * with tree_attention they make up the simplified decoder block whose latency App. G models.

@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = (
     "medusa_tree_create_optimized", "medusa_tree_destroy",
     "medusa_tree_query", "medusa_tree_tables", "medusa_heads", "medusa_topk_tree_workspace_bytes",
     "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "medusa_accept_workspace_bytes",
-    "medusa_accept", "kv_commit", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "tree_rope",
+    "medusa_accept", "kv_commit", "medusa_carry_over", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "tree_rope",
     "medusa_profile_set_events",
     "medusa_set_cache_resident_bytes", "medusa_gemm_plan",
 )
@@ -69,6 +69,7 @@ def lib() -> ctypes.CDLL:
         L.medusa_accept.argtypes = ([c_void_p] * 3 + [c_int] * 3 + [c_float] * 3 + [c_void_p] * 5 +
                                     [c_void_p, c_size_t, c_void_p])
         L.kv_commit.argtypes = ([c_void_p] * 5 + [c_int, c_void_p, c_void_p, c_void_p] + [c_int] * 6 + [c_int, c_void_p])
+        L.medusa_carry_over.argtypes = [c_void_p] * 5 + [c_int] * 5 + [c_void_p]
         L.tree_linear_workspace_bytes.restype = c_size_t
         L.tree_linear_workspace_bytes.argtypes = [c_int] * 5
         L.tree_linear.argtypes = [c_void_p] * 4 + [c_int] * 7 + [c_void_p, c_size_t, c_void_p]
@@ -331,6 +332,35 @@ def kv_commit(k_cache: torch.Tensor, v_cache: torch.Tensor, k_tree: torch.Tensor
                            path_nodes.data_ptr(), int(path_nodes.shape[1]), accept_len.data_ptr(),
                            prefix_len.data_ptr(), None if prefix_len_out is None else prefix_len_out.data_ptr(),
                            NL, B, Hkv, T, D, Lcap, code, _stream(stream)), "kv_commit")
+
+
+def medusa_carry_over(hidden_tree: Optional[torch.Tensor], verify_logits: Optional[torch.Tensor], best_node: torch.Tensor,
+                      h_next: Optional[torch.Tensor] = None, lm_next: Optional[torch.Tensor] = None, stream=None):
+    """The next step's starting activations: rows best_node[b] of hidden_tree [B,T,d] and of verify_logits
+    [B,T,V] gathered into h_next [B,d] and lm_next [B,V] (allocated when missing).  Returns (h_next, lm_next)."""
+    B = best_node.shape[0]
+    _dev(best_node, "best_node", dtype=torch.int32, shape=(B,))
+    T = d = V = 0
+    code = MEDUSA_F32
+    if hidden_tree is not None:
+        _, T, d = hidden_tree.shape
+        code = _dtype_code(hidden_tree)
+        _dev(hidden_tree, "hidden_tree", shape=(B, T, d))
+        if h_next is None:
+            h_next = torch.empty((B, d), dtype=hidden_tree.dtype, device=hidden_tree.device)
+        _dev(h_next, "h_next", dtype=hidden_tree.dtype, shape=(B, d))
+    if verify_logits is not None:
+        _, T, V = verify_logits.shape
+        _dev(verify_logits, "verify_logits", dtype=torch.float32, shape=(B, T, V))
+        if lm_next is None:
+            lm_next = torch.empty((B, V), dtype=torch.float32, device=verify_logits.device)
+        _dev(lm_next, "lm_next", dtype=torch.float32, shape=(B, V))
+    _check(lib().medusa_carry_over(None if hidden_tree is None else hidden_tree.data_ptr(),
+                                   None if verify_logits is None else verify_logits.data_ptr(), best_node.data_ptr(),
+                                   None if hidden_tree is None else h_next.data_ptr(),
+                                   None if verify_logits is None else lm_next.data_ptr(), B, T, d, V, code, _stream(stream)),
+           "medusa_carry_over")
+    return h_next, lm_next
 
 
 def tree_linear_workspace_bytes(B: int, T: int, d_in: int, d_out: int, dtype: torch.dtype) -> int:

@@ -307,8 +307,9 @@ extern "C" int medusa_accept(const float* logits, const int32_t* tree_tokens, co
   if (mode != MEDUSA_GREEDY && mode != MEDUSA_TYPICAL) return MEDUSA_EINVAL;
   if (mode == MEDUSA_TYPICAL && !(temperature > 0.f)) return MEDUSA_EINVAL;
   if (B > kMaxBatch) return MEDUSA_EUNSUPPORTED;
-  if (!tree->dev) return MEDUSA_EHIP;
   const int T = tree->host.T;
+  if ((long)B * T > 65535) return MEDUSA_EUNSUPPORTED;     // logits rows ride on the grid's second dimension
+  if (!tree->dev) return MEDUSA_EHIP;
   if (!workspace || workspace_bytes < medusa_accept_workspace_bytes(B, T, V) || ((uintptr_t)workspace & 7) != 0)
     return MEDUSA_EWORKSPACE;
   hipStream_t stream = (hipStream_t)stream_;

@@ -915,6 +915,7 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
   const dim3 block(256);
   if (dtype == MEDUSA_F32) {
     // activations of one m-block live in LDS: keep it within 64 KB
+    if ((size_t)a.d * sizeof(float) > 65536) return MEDUSA_EUNSUPPORTED;   // one activation row must fit the 64 KB staging
     const int MB = (size_t)4 * a.d * sizeof(float) <= 65536 ? 4 : 1;
     const dim3 grid(ceil_div(a.N, kGemvRowsPerWg), a.K, ceil_div(a.M, MB));
     const size_t lds = (size_t)MB * a.d * sizeof(float);
@@ -922,6 +923,7 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
     else hipLaunchKernelGGL((gemv_f32_kernel<1, EPI>), grid, block, lds, stream, a);
   } else if (a.M <= 4) {
     int MB = a.M <= 1 ? 1 : (a.M <= 2 ? 2 : 4);
+    if ((size_t)a.d * sizeof(uint16_t) > 65536) return MEDUSA_EUNSUPPORTED;   // one activation row must fit the 64 KB staging
     while ((size_t)MB * a.d * sizeof(uint16_t) > 65536) MB >>= 1;   // activations of one m-block live in LDS
     const dim3 grid(ceil_div(a.N, kGemvRowsPerWg), a.K, ceil_div(a.M, MB));
     const size_t lds = (size_t)MB * a.d * sizeof(uint16_t);

@@ -64,7 +64,41 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(u32x4_t* __restrict__ k_
   }
 }
 
+// grid (chunks, B), 256 threads: copies 4-byte words of the row selected by best_node[b] (clamped to
+// the tree) from `src` [B, T, words] to `dst` [B, words]; blockIdx.z picks the (src, dst) pair.
+__global__ __launch_bounds__(256) void carry_over_kernel(const uint32_t* __restrict__ src0, uint32_t* __restrict__ dst0,
+                                                         int words0, const uint32_t* __restrict__ src1,
+                                                         uint32_t* __restrict__ dst1, int words1,
+                                                         const int32_t* __restrict__ best_node, int T) {
+  const int b = blockIdx.y;
+  const uint32_t* src = blockIdx.z ? src1 : src0;
+  uint32_t* dst = blockIdx.z ? dst1 : dst0;
+  const int words = blockIdx.z ? words1 : words0;
+  if (!src || !dst) return;
+  const int node = min(max(best_node[b], 0), T - 1);
+  const uint32_t* row = src + ((size_t)b * T + node) * words;
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < words; i += gridDim.x * 256) dst[(size_t)b * words + i] = row[i];
+}
+
 }  // namespace
+
+extern "C" int medusa_carry_over(const void* hidden_tree, const float* verify_logits, const int32_t* best_node,
+                                 void* h_next, float* lm_next, int B, int T, int d, int V, medusa_dtype_t dtype,
+                                 medusa_stream_t stream_) {
+  if (!best_node || (!hidden_tree != !h_next) || (!verify_logits != !lm_next) || (!h_next && !lm_next)) return MEDUSA_EINVAL;
+  if (B < 1 || T < 1 || (h_next && d < 1) || (lm_next && V < 1)) return MEDUSA_EINVAL;
+  if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;
+  if (h_next && dtype == MEDUSA_BF16 && d % 2 != 0) return MEDUSA_EUNSUPPORTED;
+  if (B > 65535) return MEDUSA_EUNSUPPORTED;
+  const int words_h = h_next ? (dtype == MEDUSA_BF16 ? d / 2 : d) : 0, words_l = lm_next ? V : 0;
+  const int longest = words_h > words_l ? words_h : words_l;
+  int chunks = ceil_div(longest, 1024);
+  chunks = chunks > 64 ? 64 : chunks;
+  hipLaunchKernelGGL(carry_over_kernel, dim3(chunks, B, 2), dim3(256), 0, (hipStream_t)stream_, (const uint32_t*)hidden_tree,
+                     (uint32_t*)h_next, words_h, (const uint32_t*)verify_logits, (uint32_t*)lm_next, words_l, best_node, T);
+  MEDUSA_LAUNCH_CHECK();
+  return MEDUSA_OK;
+}
 
 extern "C" int kv_commit(void* k_cache, void* v_cache, const void* k_tree, const void* v_tree, const int32_t* path_nodes,
                          int path_stride, const int32_t* accept_len, int32_t* prefix_len, int32_t* prefix_len_out, int NL,

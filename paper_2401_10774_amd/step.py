@@ -126,6 +126,19 @@ class VerificationStep:
             if rc != 0:
                 B_._check(rc, name)
 
+    def carry_over(self) -> None:
+        """Enqueue the hand-over to the next step (Fig. 1): h_last and the LM logits of the last position
+        become the rows of the last accepted node.  The caller then supplies the next forward pass's
+        hidden_tree, q, k_tree and v_tree (in place) and calls run() again; prefix_len has already grown."""
+        stream = torch.cuda.current_stream().cuda_stream
+        t = self.t
+        rc = B_.lib().medusa_carry_over(t["hidden_tree"].data_ptr(), self.verify_logits.data_ptr(),
+                                        self.accept_out[1].data_ptr(), t["h_last"].data_ptr(),
+                                        self.lm_logits_last.data_ptr(), self.B, self.T, self.d, self.V,
+                                        B_._dtype_code(t["h_last"]), stream)
+        if rc != 0:
+            B_._check(rc, "medusa_carry_over")
+
     # ---- byte accounting (algorithmic, per step) --------------------------------------------
     def algorithmic_bytes(self, mean_prefix: float, mean_accept: float) -> Dict[str, float]:
         e = self.t["h_last"].element_size()

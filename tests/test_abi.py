@@ -96,6 +96,12 @@ def test_argument_checks_happen_on_the_host():
     assert L.tree_attention(None, p, p, p, p, p, t.handle, p, 1, 4, 4, 128, 64, 1.0, 1, p, 1 << 30, None) == -1
     assert L.medusa_accept(p, p, t.handle, 1, 100, 5, 1.0, 0.1, 0.1, p, p, p, p, p, p, 1 << 20, None) == -1
     assert L.medusa_accept(p, p, t.handle, 1, 100, 1, 0.0, 0.1, 0.1, p, p, p, p, p, p, 1 << 20, None) == -1
+    big = M.MedusaTree(branching=(4, 3, 2, 1))                                    # T = 65
+    assert L.medusa_accept(p, p, big.handle, 1024, 100, 0, 1.0, 0.1, 0.1, p, p, p, p, p, p, 1 << 40, None) == -2   # B*T rows exceed a grid dimension
+    # one activation row beyond the 64 KB the wave-per-row kernels stage in LDS: refused, not a division by zero
+    assert L.tree_linear(p, p, None, p, 1, 1, 40960, 64, 0, 0, 1, None, 0, None) == -2
+    assert L.tree_linear(p, p, None, p, 1, 4, 65536, 64, 0, 0, 1, None, 0, None) == -2
+    assert L.tree_linear(p, p, None, p, 1, 2, 32768, 64, 0, 0, 0, None, 0, None) == -2         # fp32: 128 KB per row
     assert L.kv_commit(p, p, p, p, p, 3, p, p, None, 1, 1, 1, 7, 4, 16, 1, None) == -2  # 8-byte rows
     assert L.kv_commit(p, p, p, None, p, 3, p, p, None, 1, 1, 1, 7, 64, 16, 1, None) == -1
     assert L.medusa_topk_tree(p, None, t.handle, p, 1, 100, 2, p, p, p, p, 1 << 20, None) == -1

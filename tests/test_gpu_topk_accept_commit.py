@@ -151,8 +151,11 @@ def test_accept_exhaustive_pass_patterns():
         check_accept(gt, ot, logits, tokens, "typical", 1.0, 0.05, 1.0)
 
 
+# The last two cases have the layer counts of the 13B- and 7B-shaped workloads (40 layers x 4 sequences,
+# 32 x 16): the (layer * B + sequence) index of the cache reaches 160 and 512 there.
 @pytest.mark.parametrize("dtype,NL,B,Hkv,T,D,Lcap", [("f32", 1, 1, 4, 10, 64, 160), ("bf16", 3, 4, 5, 65, 128, 300),
-                                                      ("bf16", 2, 2, 8, 89, 128, 200), ("f32", 2, 3, 2, 7, 8, 40)])
+                                                      ("bf16", 2, 2, 8, 89, 128, 200), ("f32", 2, 3, 2, 7, 8, 40),
+                                                      ("bf16", 40, 4, 40, 89, 128, 48), ("bf16", 32, 16, 8, 65, 128, 40)])
 def test_kv_commit_bitwise(dtype, NL, B, Hkv, T, D, Lcap):
     rng = np.random.default_rng(95)
     kc = draw_normal(95, 8, (NL, B, Hkv, Lcap, D), 1.0, dtype)
