@@ -46,7 +46,8 @@ typedef enum {
   MEDUSA_EINVAL = -1,        /* null pointer, non-positive size, inconsistent arguments */
   MEDUSA_EUNSUPPORTED = -2,  /* a size outside the supported range (see each call)      */
   MEDUSA_EWORKSPACE = -3,    /* workspace missing or too small                           */
-  MEDUSA_EHIP = -4           /* a HIP runtime call failed                                */
+  MEDUSA_EHIP = -4,          /* a HIP runtime call failed                                */
+  MEDUSA_ESCRATCH = -5       /* the shape needs more scratch than the library's built-in array holds */
 } medusa_status_t;
 
 typedef enum { MEDUSA_F32 = 0, MEDUSA_BF16 = 1 } medusa_dtype_t;
@@ -167,6 +168,23 @@ int tree_attention(const void* q, const void* k_tree, const void* v_tree, const 
                    const void* v_cache, const int32_t* prefix_len, const medusa_tree_t* tree, void* out,
                    int B, int Hq, int Hkv, int D, int Lcap, float scale, medusa_dtype_t dtype,
                    void* workspace, size_t workspace_bytes, medusa_stream_t stream);
+
+/* tree_attention_static: tree_attention for callers that cannot allocate device memory or keep a
+ * workspace -- code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results and kernels as tree_attention, but the split partials go to an array
+ * built into the library's device image (tree_attention_static_scratch_bytes() = 8 MiB per GPU, held
+ * until the process ends) instead of a caller workspace.  The call allocates nothing: no hipMalloc,
+ * no hipFree, no allocating library routine; the first call on a device looks the array's address
+ * up once.  Shapes whose tree_attention_workspace_bytes() exceeds the array are refused with
+ * MEDUSA_ESCRATCH and nothing is enqueued (the 7B shapes at batch 1, any prefix length, need 4.4 MB).
+ * All calls on one GPU share the array, which keeps the last call's partials (nothing in it has to
+ * start at zero: every partial that is read was written by the same call): calls that overlap on
+ * one GPU -- two streams, two threads -- race; order them. */
+size_t tree_attention_static_scratch_bytes(void);
+int tree_attention_static(const void* q, const void* k_tree, const void* v_tree, const void* k_cache,
+                          const void* v_cache, const int32_t* prefix_len, const medusa_tree_t* tree, void* out,
+                          int B, int Hq, int Hkv, int D, int Lcap, float scale, medusa_dtype_t dtype,
+                          medusa_stream_t stream);
 
 /* ----------------------------------------------------------------------------------
  * medusa_accept (Sec. 2.3.1): node t (t >= 1) passes its test on the original model's

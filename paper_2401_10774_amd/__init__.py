@@ -18,6 +18,7 @@ from .binding import (
     medusa_set_cache_resident_bytes,
     medusa_topk_tree,
     tree_attention,
+    tree_attention_static,
     tree_attention_workspace_bytes,
     interleave_gate_up,
     tree_linear,
@@ -30,6 +31,6 @@ from .binding import (
 __all__ = [
     "MedusaError", "MedusaTree", "kv_commit", "lib", "library_path", "medusa_accept",
     "medusa_accept_workspace_bytes", "medusa_carry_over", "medusa_heads", "medusa_gemm_plan", "medusa_set_cache_resident_bytes", "medusa_topk_tree", "tree_attention",
-    "tree_attention_workspace_bytes", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "interleave_gate_up",
+    "tree_attention_workspace_bytes", "tree_attention_static", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "interleave_gate_up",
     "tree_linear_workspace_bytes", "tree_rope",
 ]

@@ -24,7 +24,8 @@ EXPORTED_SYMBOLS = (
     "medusa_status_string", "medusa_tree_create_cartesian", "medusa_tree_create_nodes",
     "medusa_tree_create_optimized", "medusa_tree_destroy",
     "medusa_tree_query", "medusa_tree_tables", "medusa_heads", "medusa_topk_tree_workspace_bytes",
-    "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "medusa_accept_workspace_bytes",
+    "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "tree_attention_static",
+    "tree_attention_static_scratch_bytes", "medusa_accept_workspace_bytes",
     "medusa_accept", "kv_commit", "medusa_carry_over", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "tree_rope",
     "medusa_profile_set_events",
     "medusa_set_cache_resident_bytes", "medusa_gemm_plan",
@@ -64,6 +65,9 @@ def lib() -> ctypes.CDLL:
         L.tree_attention_workspace_bytes.restype = c_size_t
         L.tree_attention_workspace_bytes.argtypes = [c_int] * 6
         L.tree_attention.argtypes = [c_void_p] * 8 + [c_int] * 5 + [c_float, c_int, c_void_p, c_size_t, c_void_p]
+        L.tree_attention_static.argtypes = [c_void_p] * 8 + [c_int] * 5 + [c_float, c_int, c_void_p]
+        L.tree_attention_static_scratch_bytes.restype = c_size_t
+        L.tree_attention_static_scratch_bytes.argtypes = []
         L.medusa_accept_workspace_bytes.restype = c_size_t
         L.medusa_accept_workspace_bytes.argtypes = [c_int] * 3
         L.medusa_accept.argtypes = ([c_void_p] * 3 + [c_int] * 3 + [c_float] * 3 + [c_void_p] * 5 +
@@ -270,6 +274,29 @@ def tree_attention(q: torch.Tensor, k_tree: torch.Tensor, v_tree: torch.Tensor, 
                                 v_cache.data_ptr(), prefix_len.data_ptr(), tree.handle, out.data_ptr(), B, Hq, Hkv, D,
                                 Lcap, float(scale), code, workspace.data_ptr(),
                                 workspace.numel() * workspace.element_size(), _stream(stream)), "tree_attention")
+    return out
+
+
+def tree_attention_static(q: torch.Tensor, k_tree: torch.Tensor, v_tree: torch.Tensor, k_cache: torch.Tensor,
+                          v_cache: torch.Tensor, prefix_len: torch.Tensor, tree: MedusaTree, scale: float,
+                          out: torch.Tensor, stream=None) -> torch.Tensor:
+    """tree_attention on the library's built-in scratch array: the call allocates nothing, so `out` is
+    required.  Raises MedusaError (MEDUSA_ESCRATCH) for shapes whose split partials exceed the array."""
+    B, Hq, T, D = q.shape
+    Hkv, Lcap = k_cache.shape[1], k_cache.shape[2]
+    if T != tree.T:
+        raise MedusaError(f"q has {T} tree tokens, the tree has {tree.T}")
+    code = _dtype_code(q)
+    _dev(q, "q")
+    _dev(k_tree, "k_tree", dtype=q.dtype, shape=(B, Hkv, T, D))
+    _dev(v_tree, "v_tree", dtype=q.dtype, shape=(B, Hkv, T, D))
+    _dev(k_cache, "k_cache", dtype=q.dtype, shape=(B, Hkv, Lcap, D))
+    _dev(v_cache, "v_cache", dtype=q.dtype, shape=(B, Hkv, Lcap, D))
+    _dev(prefix_len, "prefix_len", dtype=torch.int32, shape=(B,))
+    _dev(out, "out", dtype=q.dtype, shape=(B, Hq, T, D))
+    _check(lib().tree_attention_static(q.data_ptr(), k_tree.data_ptr(), v_tree.data_ptr(), k_cache.data_ptr(),
+                                       v_cache.data_ptr(), prefix_len.data_ptr(), tree.handle, out.data_ptr(), B, Hq, Hkv,
+                                       D, Lcap, float(scale), code, _stream(stream)), "tree_attention_static")
     return out
 
 

@@ -148,6 +148,7 @@ extern "C" const char* medusa_status_string(int status) {
     case MEDUSA_EUNSUPPORTED: return "size outside the supported range";
     case MEDUSA_EWORKSPACE: return "workspace missing or too small";
     case MEDUSA_EHIP: return "HIP runtime error";
+    case MEDUSA_ESCRATCH: return "shape needs more scratch than the library's built-in array holds";
     default: return "unknown status";
   }
 }

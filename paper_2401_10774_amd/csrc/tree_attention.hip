@@ -31,6 +31,8 @@
 // fp32 path (and any D the MFMA path does not cover): one workgroup per query row, plain FMAs.
 #include <math.h>
 
+#include <mutex>
+
 #include "common.hpp"
 
 namespace {
@@ -489,6 +491,49 @@ extern "C" size_t tree_attention_workspace_bytes(int B, int Hq, int Hkv, int T, 
   const size_t R = (size_t)(Hq / Hkv) * T;
   const size_t bytes = (size_t)B * Hkv * p.n_splits * R * (D * 2 + 8);   // fp16 rows + (max, sum)
   return (bytes + 255) & ~(size_t)255;
+}
+
+// Scratch of tree_attention_static: the split partials live in this array instead of a caller
+// workspace.  Every GPU the library runs on holds its own copy until the process ends; host code
+// reaches it only through the per-device address looked up once below, never through the name.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[64] = {};
+
+int static_scratch(void** out) {
+  int dev = 0;
+  MEDUSA_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) return MEDUSA_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    MEDUSA_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || ((uintptr_t)p & 255) != 0) return MEDUSA_EHIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MEDUSA_OK;
+}
+}  // namespace
+
+extern "C" size_t tree_attention_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" int tree_attention_static(const void* q, const void* k_tree, const void* v_tree, const void* k_cache,
+                                     const void* v_cache, const int32_t* prefix_len, const medusa_tree_t* tree, void* out,
+                                     int B, int Hq, int Hkv, int D, int Lcap, float scale, medusa_dtype_t dtype,
+                                     medusa_stream_t stream_) {
+  if (!tree) return MEDUSA_EINVAL;
+  if (B < 1 || Hq < 1 || Hkv < 1 || Lcap < 1 || Hq % Hkv != 0) return MEDUSA_EINVAL;
+  const size_t need = tree_attention_workspace_bytes(B, Hq, Hkv, tree->host.T, D, Lcap);
+  if (need > kStaticScratchBytes) return MEDUSA_ESCRATCH;     // the shape's split partials exceed the built-in scratch
+  void* ptr = nullptr;
+  const int rc = static_scratch(&ptr);
+  if (rc != MEDUSA_OK) return rc;
+  return tree_attention(q, k_tree, v_tree, k_cache, v_cache, prefix_len, tree, out, B, Hq, Hkv, D, Lcap, scale, dtype, ptr,
+                        kStaticScratchBytes, stream_);
 }
 
 extern "C" int tree_attention(const void* q, const void* k_tree, const void* v_tree, const void* k_cache,
