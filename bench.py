@@ -23,11 +23,23 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE (two runs), each scaled by what the same counter reads for a plain 1 GiB copy
-# (FETCH_SIZE counts 2 KiB units on this chip, WRITE_SIZE 1 KiB units).  bench.py cannot run the
-# profiler itself; the figure is the recorded measurement for the workload it was taken on.
-MEASURED_TRAFFIC_BYTES = {"C2": 512192 * 2 * 1024 + 505 * 1024, "C3": 512192 * 2 * 1024 + 505 * 1024}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "heads_w2_hbm_traffic.md")
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc (FETCH_SIZE and
+    WRITE_SIZE in two runs, each scaled by what the same counter reads for a plain 1 GiB copy), read
+    from the tracked summary of those runs: lines `traffic_bytes <workload> <bytes> commit <hash>`.
+    bench.py cannot run the profiler itself; None when the summary has no line for the workload."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                w = line.split()
+                if len(w) >= 5 and w[0] == "traffic_bytes" and w[1] == workload and w[3] == "commit":
+                    return {"bytes": int(w[2]), "commit": w[4]}
+    except OSError:
+        pass
+    return None
 
 
 def parse_args():
@@ -40,7 +52,7 @@ def parse_args():
                     help="time the dominant kernel with a HIP event pair in every N-th timed step (a pair costs the "
                          "step about 5 us of dispatch gaps, so not every step carries one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--breakdown", action="store_true", help="also time every library call on its own (stderr)")
+    ap.add_argument("--breakdown", action="store_true", help="also print the per-call timings of the JSON line to stderr")
     ap.add_argument("--block", action="store_true",
                     help="time the simplified decoder block of App. G on the tree tokens instead of the verification "
                          "step (its own JSON line; the headline metric stays the verification step)")
@@ -54,29 +66,28 @@ def parse_args():
 
 
 class HipEvents:
-    """Raw hipEvent_t handles for the library's profiling hook (timed on whatever stream the hook records on)."""
+    """Raw hipEvent_t handles for the library's timed entry (recorded on the stream the call is given)."""
 
     def __init__(self, n):
         self.hip = ctypes.CDLL("libamdhip64.so")
         self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
         self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
         self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
-        self.pairs = []
+        self.handles = []
         for _ in range(n):
-            a, b = ctypes.c_void_p(), ctypes.c_void_p()
-            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0 and self.hip.hipEventCreate(ctypes.byref(b)) == 0
-            self.pairs.append((a, b))
+            a = ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0
+            self.handles.append(a)
 
-    def elapsed_ms(self, i):
+    def elapsed_ms(self, i, j):
         ms = ctypes.c_float()
-        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.pairs[i][0], self.pairs[i][1])
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.handles[i], self.handles[j])
         assert rc == 0, f"hipEventElapsedTime failed ({rc})"
         return ms.value
 
     def close(self):
-        for a, b in self.pairs:
+        for a in self.handles:
             self.hip.hipEventDestroy(a)
-            self.hip.hipEventDestroy(b)
 
 
 def main():
@@ -126,42 +137,56 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    L = M.lib()
     K, W = args.steps, args.warmup
     step.commit_out_of_place()   # every timed step sees the same prefix lengths; no reset between steps
     plant_accepted_paths(step, tensors, tree, cfg)
-    for i in range(W):
-        step.run(i % cfg.NL)
-    torch.cuda.synchronize()
-
+    # Between two verification steps a decoder streams its whole backbone, so nothing of this step's
+    # weights is left in the 256 MB last-level cache.  The timed loop reproduces that: the W1 stack and
+    # the LM head rotate over copies (W2, 1 GB, and the KV layers, which rotate too, evict themselves),
+    # and the library is told to plan for weights that come from HBM.
+    w1_bytes = tensors["w1"].numel() * tensors["w1"].element_size()
+    lm_bytes = tensors["w_lm"].numel() * tensors["w_lm"].element_size()
+    n_w1 = max(2, min(4, int(math.ceil(600e6 / w1_bytes))))
+    n_lm = max(2, min(4, int(math.ceil(700e6 / lm_bytes))))
+    step.add_weight_copies(n_w1, n_lm)
     every = max(1, args.event_every)
-    timed = [i for i in range(K) if i % every == 0]
-    events = HipEvents(len(timed))
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    start.record()
-    for i in range(K):
-        if i % every == 0:
-            L.medusa_profile_set_events(events.pairs[i // every][0], events.pairs[i // every][1])
-        else:
-            L.medusa_profile_set_events(None, None)
-        step.run((W + i) % cfg.NL)
-    stop.record()
-    torch.cuda.synchronize()
-    L.medusa_profile_set_events(None, None)
-    ms_per_step = start.elapsed_time(stop) / K
-    kern_ms = sum(events.elapsed_ms(j) for j in range(len(timed))) / len(timed)
-    events.close()
-    accept_len = step.accept_out[0].cpu().numpy()
 
-    e = 2 if cfg.dtype == "bf16" else 4
+    def timed_loop(cold):
+        M.medusa_set_cache_resident_bytes(0 if cold else 256 << 20)
+        for i in range(W):
+            step.run(i % cfg.NL, wset=i if cold else 0)
+        timed = [i for i in range(K) if i % every == 0]
+        events = HipEvents(3 * len(timed))
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        start.record()
+        for i in range(K):
+            ev = events.handles[3 * (i // every):3 * (i // every) + 3] if i % every == 0 else None
+            step.run((W + i) % cfg.NL, wset=(W + i) if cold else 0, heads_events=ev)
+        stop.record()
+        torch.cuda.synchronize()
+        ms = start.elapsed_time(stop) / K
+        w1_ms = sum(events.elapsed_ms(3 * j, 3 * j + 1) for j in range(len(timed))) / len(timed)
+        w2_ms = sum(events.elapsed_ms(3 * j + 1, 3 * j + 2) for j in range(len(timed))) / len(timed)
+        events.close()
+        return ms, w1_ms, w2_ms, len(timed)
+
+    ms_per_step, w1_ms, kern_ms, n_timed = timed_loop(cold=True)
+    accept_len = step.accept_out[0].cpu().numpy()
+    warm_ms, _, _, _ = timed_loop(cold=False)
+    M.medusa_set_cache_resident_bytes(0)
+
     mean_prefix = float(np.mean(x["prefix_len"]))
     parts = step.algorithmic_bytes(mean_prefix, float(accept_len.mean()))
     steps_per_s = 1e3 / ms_per_step
     step_gbs = parts["total"] / (ms_per_step * 1e-3) / 1e9
+    warm_gbs = parts["total"] / (warm_ms * 1e-3) / 1e9
     # dominant kernel: the W2 stream of medusa_heads (M = B rows): weights once + activations + fp32 logits
     dom_bytes = parts["heads_w2"]
     dom_gbs = dom_bytes / (kern_ms * 1e-3) / 1e9
+    kernels = per_call_timings(step, cfg, parts, w1_ms, kern_ms)
+    M.medusa_set_cache_resident_bytes(256 << 20)
+    traffic = measured_traffic(cfg.name)
 
     out = {
         "metric": "verification steps/sec + achieved HBM GB/s vs peak, 7B shapes, 64-node tree",
@@ -179,12 +204,19 @@ def main():
         "config": {
             "workload": f"{cfg.name}: B={cfg.B} d={cfg.d} heads={cfg.Hq}/{cfg.Hkv}x{cfg.D} V={cfg.V} K={cfg.K} "
                         f"tree={cfg.branching} T={cfg.T} prefix=[{cfg.L_min},{cfg.L_max}] NL={cfg.NL} "
-                        f"accept={cfg.accept}",
+                        f"accept={cfg.accept}, accepted paths planted in the hidden states",
+            "planted": True,
             "seed": cfg.seed,
-            "launch": "eager, one stream, attended cache layer rotates every step",
+            "launch": f"eager, one stream; every step streams its weights from HBM: attended cache layer, W1 ({n_w1} "
+                      f"copies) and LM head ({n_lm} copies) rotate every step",
         },
         "step_hbm": {"algorithmic_bytes": int(parts["total"]), "achieved_GBps": round(step_gbs, 1),
-                     "frac_of_peak": round(step_gbs / HBM_PEAK_GBS, 4)},
+                     "frac_of_peak": round(step_gbs / HBM_PEAK_GBS, 4),
+                     "cold_lm_head": {"steps_per_s": round(steps_per_s, 2), "frac_of_peak": round(step_gbs / HBM_PEAK_GBS, 4),
+                                      "note": "the headline: W1 and LM head rotate over copies, nothing is cache-resident"},
+                     "warm_lm_head": {"steps_per_s": round(1e3 / warm_ms, 2), "frac_of_peak": round(warm_gbs / HBM_PEAK_GBS, 4),
+                                      "note": "same step with one copy of W1 and of the LM head re-read every step "
+                                              "(they stay in the last-level cache); not what a decoder sees"}},
         "roofline": {
             "kernel": "gemv_bf16_kernel<1, EPI_LOGITS> (medusa_heads W2 projection, M=B)" if cfg.dtype == "bf16" and cfg.B <= 4
                       else "medusa_heads W2 projection",
@@ -195,18 +227,59 @@ def main():
             "frac": round(dom_gbs / HBM_PEAK_GBS, 4),
             "bytes_per_launch": int(dom_bytes),
             "avg_launch_us": round(kern_ms * 1e3, 2),
-            "launches_timed": len(timed),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+            "launches_timed": n_timed,
+            "traffic": None if traffic is None else traffic["bytes"],
+            "traffic_measured_at_commit": None if traffic is None else traffic["commit"],
         },
+        "kernels": kernels,
         "mean_accept_len": round(float(accept_len.mean()), 3),
     }
 
     if args.breakdown:
-        breakdown(step, cfg, parts)
+        for name, k in kernels.items():
+            print(f"[bench]   {name:16s} {k['us']:9.1f} us  {k['MB']:9.1f} MB  {k['GBps']:8.1f} GB/s", file=sys.stderr)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, x)
     print(json.dumps(out), flush=True)
+
+
+def per_call_timings(step, cfg, parts, w1_ms, w2_ms, n=48):
+    """Every library call of the step timed with an event pair around it, in steps of their own
+    after the timed region (a pair costs the step several microseconds of dispatch gaps), with the
+    same rotation of layers and weight copies; the two kernels of the heads call keep the figures
+    measured inside the timed region.  us = average duration of the call on the stream (a call is
+    one kernel, except attention: split kernel + merge); MB = its algorithmic bytes."""
+    import torch
+    stream = torch.cuda.current_stream().cuda_stream
+    names = ["heads", "topk_tree", "attention", "verify_lm_head", "accept", "commit"]
+    pairs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in names] for _ in range(n)]
+    for i in range(n):
+        pre, post = step._calls(i % cfg.NL, i)
+        for j, (name, fn, fargs) in enumerate(pre + post):
+            pairs[i][j][0].record()
+            rc = fn(*fargs, stream)
+            pairs[i][j][1].record()
+            assert rc == 0, (name, rc)
+    torch.cuda.synchronize()
+    us = {nm: sum(p[j][0].elapsed_time(p[j][1]) for p in pairs[8:]) / (n - 8) * 1e3 for j, nm in enumerate(names)}
+    keys = {"topk_tree": ("topk",), "attention": ("attention",), "verify_lm_head": ("verify",), "accept": ("accept",),
+            "commit": ("commit",)}
+    out = {}
+
+    def entry(t_us, nbytes):
+        return {"us": round(t_us, 2), "MB": round(nbytes / 1e6, 2), "GBps": round(nbytes / t_us / 1e3, 1),
+                "frac_of_hbm_peak": round(nbytes / t_us / 1e3 / HBM_PEAK_GBS, 4)}
+
+    out["heads_w1"] = entry(w1_ms * 1e3, parts["heads_w1"])
+    out["heads_w2"] = entry(w2_ms * 1e3, parts["heads_w2"])
+    for nm in names[1:]:
+        out[nm] = entry(us[nm], sum(parts[k] for k in keys[nm]))
+    flops = 2.0 * cfg.B * cfg.T * cfg.d * cfg.V
+    out["verify_lm_head"]["useful_TFLOPs"] = round(flops / us["verify_lm_head"] / 1e6, 1)
+    out["verify_lm_head"]["frac_of_bf16_mfma_peak"] = round(flops / us["verify_lm_head"] / 1e6 / 2500.0, 4)
+    out["heads_w1"]["note"] = out["heads_w2"]["note"] = "timed inside the timed region (medusa_heads_timed)"
+    return out
 
 
 def plant_accepted_paths(step, tensors, tree, cfg):
@@ -417,51 +490,40 @@ def bench_speed_model(args, cfg):
         "experiments": results}), flush=True)
 
 
-def breakdown(step, cfg, parts):
-    """Per-call timings (each call 50x back to back, attended layer rotating); informational, stderr only."""
-    import torch
-    pre, post = step._calls(0)
-    names = ["heads (W1+W2)", "topk_tree", "attention", "verify GEMM", "accept", "commit"]
-    keys = [("heads_w1", "heads_w2"), ("topk",), ("attention",), ("verify",), ("accept",), ("commit",)]
-    stream = torch.cuda.current_stream().cuda_stream
-    n = 50
-    for idx, name in enumerate(names):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        a.record()
-        for i in range(n):
-            calls = step._calls(i % cfg.NL)
-            _, fn, fargs = (calls[0] + calls[1])[idx]
-            fn(*fargs, stream)
-        b.record()
-        torch.cuda.synchronize()
-        us = a.elapsed_time(b) / n * 1e3
-        nbytes = sum(parts[k] for k in keys[idx])
-        print(f"[bench]   {name:14s} {us:9.1f} us  {nbytes / 1e6:9.1f} MB  {nbytes / us / 1e3:8.1f} GB/s", file=sys.stderr)
-
-
 def cpu_baseline(cfg, x):
-    """The CPU oracle, as it stands, on one full step of the same inputs (host cores of this machine)."""
+    """The CPU oracle, as it stands, on whole steps of the same inputs (host cores of this machine): at the
+    thread count numpy's BLAS takes by itself, and limited to one thread."""
     from oracle import medusa_oracle as O
     try:
-        from threadpoolctl import threadpool_info
+        from threadpoolctl import threadpool_info, threadpool_limits
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
+        threadpool_limits = None
         cores = os.cpu_count() or 1
     otree = O.tree_cartesian(cfg.branching)
     pl0 = x["prefix_len"].copy()
-    n, t0 = 0, time.time()
-    while True:                                  # whole steps until about 10 s of CPU work are on the clock
-        x["prefix_len"][:] = pl0
-        O.verification_step_ref(x, otree, cfg.dtype, 1.0 / math.sqrt(cfg.D), cfg.accept, cfg.temperature, cfg.eps,
-                                cfg.delta)
-        n += 1
-        dt = time.time() - t0
-        if dt >= 10.0 or n >= 50:
-            break
-    return {"value": round(n / dt, 4), "unit": "steps/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{n} full step(s) of {cfg.name} (all heads, all tree rows, all {cfg.NL} committed layers), "
-                      f"{dt:.1f} s wall, numpy float64"}
+
+    def run(budget_s, max_steps):
+        n, t0 = 0, time.time()
+        while True:                              # whole steps until the budget of CPU work is on the clock
+            x["prefix_len"][:] = pl0
+            O.verification_step_ref(x, otree, cfg.dtype, 1.0 / math.sqrt(cfg.D), cfg.accept, cfg.temperature, cfg.eps,
+                                    cfg.delta)
+            n += 1
+            dt = time.time() - t0
+            if dt >= budget_s or n >= max_steps:
+                return n, dt
+
+    n, dt = run(10.0, 50)
+    out = {"value": round(n / dt, 4), "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+           "sample": f"{n} full step(s) of {cfg.name} (all heads, all tree rows, all {cfg.NL} committed layers), "
+                     f"{dt:.1f} s wall, numpy float64"}
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            n1, dt1 = run(8.0, 3)
+        out["one_thread"] = {"value": round(n1 / dt1, 4), "unit": "steps/s", "cores": 1,
+                             "sample": f"{n1} full step(s), {dt1:.1f} s wall"}
+    return out
 
 
 if __name__ == "__main__":

@@ -336,13 +336,16 @@ int medusa_set_cache_resident_bytes(size_t bytes);
 int medusa_gemm_plan(int M, int N, int d, int K, int have_workspace, int* plan6);
 
 /* ----------------------------------------------------------------------------------
- * Benchmark hook (no counterpart in the paper): while a pair of hipEvent_t handles is set,
- * every medusa_heads call with w1 != NULL records `start` right before and `stop` right after
- * its vocabulary-projection kernel (the W2 stream, the largest single read of the step) on the
- * call's stream, so a caller can time that kernel inside a running step.  Pass NULL, NULL to
- * switch it off (the default).  Process-wide, not thread-safe; the events stay caller-owned.
+ * Profiling entry (no counterpart in the paper): medusa_heads with three caller-owned hipEvent_t
+ * handles recorded on the call's stream -- ev_begin before the residual-block kernel (the W1
+ * stream), ev_between after it and before the vocabulary projection (the W2 stream, the largest
+ * single read of a step), ev_end after that -- so that a benchmark can time the two kernels
+ * inside a running step.  With w1 == NULL ev_begin and ev_between are recorded back to back.
+ * Everything else is medusa_heads; MEDUSA_EINVAL if an event is NULL.
  * -------------------------------------------------------------------------------- */
-int medusa_profile_set_events(void* start, void* stop);
+int medusa_heads_timed(const void* hidden, const void* w1, const void* w2, void* resid, float* logits, int M, int d,
+                       int V, int K, medusa_dtype_t dtype, medusa_stream_t stream, void* ev_begin, void* ev_between,
+                       void* ev_end);
 
 #ifdef __cplusplus
 }

@@ -27,7 +27,7 @@ EXPORTED_SYMBOLS = (
     "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "tree_attention_static",
     "tree_attention_static_scratch_bytes", "medusa_accept_workspace_bytes",
     "medusa_accept", "kv_commit", "medusa_carry_over", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "tree_rope",
-    "medusa_profile_set_events",
+    "medusa_heads_timed",
     "medusa_set_cache_resident_bytes", "medusa_gemm_plan",
 )
 
@@ -80,7 +80,7 @@ def lib() -> ctypes.CDLL:
         L.tree_linear_swiglu.argtypes = [c_void_p] * 3 + [c_int] * 7 + [c_void_p]
         L.tree_linear_segments.argtypes = [c_void_p] * 4 + [c_int] * 7 + [c_size_t, c_int, c_void_p, c_size_t, c_void_p]
         L.tree_rope.argtypes = [c_void_p] * 3 + [c_int] * 5 + [c_float, c_int, c_void_p]
-        L.medusa_profile_set_events.argtypes = [c_void_p, c_void_p]
+        L.medusa_heads_timed.argtypes = [c_void_p] * 5 + [c_int] * 5 + [c_void_p] * 4
         L.medusa_set_cache_resident_bytes.argtypes = [ctypes.c_size_t]
         L.medusa_gemm_plan.argtypes = [c_int] * 5 + [ctypes.POINTER(c_int)]
         for name in EXPORTED_SYMBOLS:

@@ -873,9 +873,6 @@ size_t gemm_ws_bytes(int M, int N, int d, int K) {
   return (size_t)ceil_div(N, p.wide ? 128 : 64) * K * p.m_blocks * p.ksplit * frags * 4 * 256 * sizeof(float);
 }
 
-// Optional event pair recorded around the vocabulary-projection launch (benchmark hook).
-hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
-
 // Weight rows per GEMV workgroup: 16 measured best on MI355X at 7B shapes (8, 32 and 64 were
 // 1-10 % slower); fewer for small matrices so that the grid still covers the chip.
 int gemv_rows_per_wg(int N, int K, int M) {
@@ -979,8 +976,10 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
 
 }  // namespace
 
-extern "C" int medusa_heads(const void* hidden, const void* w1, const void* w2, void* resid, float* logits, int M,
-                            int d, int V, int K, medusa_dtype_t dtype, medusa_stream_t stream_) {
+// medusa_heads; `ev` is null, or three events recorded before the residual-block kernel, between
+// the two kernels and after the vocabulary projection.
+static int heads_impl(const void* hidden, const void* w1, const void* w2, void* resid, float* logits, int M, int d, int V,
+                      int K, medusa_dtype_t dtype, medusa_stream_t stream_, hipEvent_t* ev) {
   if (!hidden || !w2 || !logits || (w1 && !resid)) return MEDUSA_EINVAL;
   if (M < 1 || d < 1 || V < 1 || K < 1) return MEDUSA_EINVAL;
   if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;
@@ -1000,6 +999,7 @@ extern "C" int medusa_heads(const void* hidden, const void* w1, const void* w2, 
     a.N = d;
     a.xs_m = d;
     a.xs_k = 0;
+    if (ev) MEDUSA_HIP_TRY(hipEventRecord(ev[0], stream));
     const int rc = launch_gemm<EPI_RESID>(a, dtype, stream);
     if (rc != MEDUSA_OK) return rc;
     a.X = resid;
@@ -1013,11 +1013,26 @@ extern "C" int medusa_heads(const void* hidden, const void* w1, const void* w2, 
   a.W = w2;
   a.out = logits;
   a.N = V;
-  const bool prof = w1 && g_prof_start && g_prof_stop;
-  if (prof) MEDUSA_HIP_TRY(hipEventRecord(g_prof_start, stream));
+  if (ev) {
+    if (!w1) MEDUSA_HIP_TRY(hipEventRecord(ev[0], stream));
+    MEDUSA_HIP_TRY(hipEventRecord(ev[1], stream));
+  }
   const int rc = launch_gemm<EPI_LOGITS>(a, dtype, stream);
-  if (prof && rc == MEDUSA_OK) MEDUSA_HIP_TRY(hipEventRecord(g_prof_stop, stream));
+  if (ev && rc == MEDUSA_OK) MEDUSA_HIP_TRY(hipEventRecord(ev[2], stream));
   return rc;
+}
+
+extern "C" int medusa_heads(const void* hidden, const void* w1, const void* w2, void* resid, float* logits, int M,
+                            int d, int V, int K, medusa_dtype_t dtype, medusa_stream_t stream_) {
+  return heads_impl(hidden, w1, w2, resid, logits, M, d, V, K, dtype, stream_, nullptr);
+}
+
+extern "C" int medusa_heads_timed(const void* hidden, const void* w1, const void* w2, void* resid, float* logits, int M,
+                                  int d, int V, int K, medusa_dtype_t dtype, medusa_stream_t stream_, void* ev_begin,
+                                  void* ev_between, void* ev_end) {
+  if (!ev_begin || !ev_between || !ev_end) return MEDUSA_EINVAL;
+  hipEvent_t ev[3] = {(hipEvent_t)ev_begin, (hipEvent_t)ev_between, (hipEvent_t)ev_end};
+  return heads_impl(hidden, w1, w2, resid, logits, M, d, V, K, dtype, stream_, ev);
 }
 
 // Backbone linear layer on the tree tokens (App. G, operator table, parallel-decoding rows).
@@ -1153,9 +1168,4 @@ extern "C" int medusa_set_cache_resident_bytes(size_t bytes) {
   return MEDUSA_OK;
 }
 
-extern "C" int medusa_profile_set_events(void* start, void* stop) {
-  if ((start == nullptr) != (stop == nullptr)) return MEDUSA_EINVAL;
-  g_prof_start = (hipEvent_t)start;
-  g_prof_stop = (hipEvent_t)stop;
-  return MEDUSA_OK;
-}
+

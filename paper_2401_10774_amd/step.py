@@ -54,6 +54,8 @@ class VerificationStep:
         self.hidden_rows = dev["hidden_tree"].view(B * T, self.d)
         self.prefix_len0 = dev["prefix_len"].clone()
         self.next_prefix_len = None
+        self.w1_sets = [dev["w1"]]
+        self.w_lm_sets = [self.w_lm3]
         self._plans = {}
 
     def prepare(self) -> None:
@@ -72,10 +74,23 @@ class VerificationStep:
             self._plans = {}
         return self.next_prefix_len
 
-    def _calls(self, layer: int):
-        """The step's library calls with their arguments marshalled once (pointers into layer `layer`)."""
-        if layer in self._plans:
-            return self._plans[layer]
+    def add_weight_copies(self, n_w1: int, n_w_lm: int) -> None:
+        """Keep n copies of W1 and of the LM head; run(wset=i) reads copy i % n.  A benchmark rotates them so
+        that no step finds these weights in the last-level cache (in a decoder the whole backbone streams
+        through between two verification steps)."""
+        while len(self.w1_sets) < n_w1:
+            self.w1_sets.append(self.w1_sets[0].clone())
+        while len(self.w_lm_sets) < n_w_lm:
+            self.w_lm_sets.append(self.w_lm_sets[0].clone())
+        self._plans = {}
+
+    def _calls(self, layer: int, wset: int = 0):
+        """The step's library calls with their arguments marshalled once (pointers into layer `layer`,
+        weight copies `wset`)."""
+        key = (layer, wset % len(self.w1_sets), wset % len(self.w_lm_sets))
+        if key in self._plans:
+            return self._plans[key]
+        w1, w_lm3 = self.w1_sets[key[1]], self.w_lm_sets[key[2]]
         L, t, tree = B_.lib(), self.t, self.tree
         p = lambda x: x.data_ptr()
         code = B_._dtype_code(t["h_last"])
@@ -85,7 +100,7 @@ class VerificationStep:
         kt, vt, kc, vc = (t[n][layer] for n in ("k_tree", "v_tree", "k_cache", "v_cache"))
         a = self.accept_out
         pre = [
-            ("medusa_heads", L.medusa_heads, (p(t["h_last"]), p(t["w1"]), p(t["w2"]), p(self.resid),
+            ("medusa_heads", L.medusa_heads, (p(t["h_last"]), p(w1), p(t["w2"]), p(self.resid),
                                               p(self.medusa_logits), B, d, V, K, code)),
             ("medusa_topk_tree", L.medusa_topk_tree, (p(self.medusa_logits), p(self.lm_logits_last), tree.handle,
                                                       p(t["prefix_len"]), B, V, K, p(self.topk_ids),
@@ -94,7 +109,7 @@ class VerificationStep:
             ("tree_attention", L.tree_attention, (p(t["q"]), p(kt), p(vt), p(kc), p(vc), p(t["prefix_len"]),
                                                   tree.handle, p(self.attn_out), B, self.Hq, self.Hkv, self.D,
                                                   self.Lcap, self.scale, code, p(self.ws_attn), nbytes(self.ws_attn))),
-            ("medusa_heads", L.medusa_heads, (p(self.hidden_rows), None, p(self.w_lm3), None, p(self.verify_logits),
+            ("medusa_heads", L.medusa_heads, (p(self.hidden_rows), None, p(w_lm3), None, p(self.verify_logits),
                                               B * T, d, V, 1, code)),
         ]
         post = [
@@ -107,16 +122,21 @@ class VerificationStep:
                                         self.NL, B, self.Hkv, T,
                                         self.D, self.Lcap, code)),
         ]
-        self._plans[layer] = (pre, post)
-        return self._plans[layer]
+        self._plans[key] = (pre, post)
+        return self._plans[key]
 
-    def run(self, attn_layer: int = 0, plant=None) -> None:
+    def run(self, attn_layer: int = 0, plant=None, wset: int = 0, heads_events=None) -> None:
         """Enqueue one step on the current stream.  `plant`, if given, may edit the verification logits
-        between the LM-head GEMM and acceptance (parity tests use it to force long accepted paths)."""
+        between the LM-head GEMM and acceptance (parity tests use it to force long accepted paths).
+        `heads_events`: three raw hipEvent_t handles recorded before, between and after the two kernels
+        of the heads call (medusa_heads_timed) -- a benchmark's way to time them inside a running step."""
         stream = torch.cuda.current_stream().cuda_stream
-        pre, post = self._calls(attn_layer)
-        for name, fn, args in pre:
-            rc = fn(*args, stream)
+        pre, post = self._calls(attn_layer, wset)
+        for i, (name, fn, args) in enumerate(pre):
+            if i == 0 and heads_events is not None:
+                rc = B_.lib().medusa_heads_timed(*args, stream, *heads_events)
+            else:
+                rc = fn(*args, stream)
             if rc != 0:
                 B_._check(rc, name)
         if plant is not None:
