@@ -23,7 +23,11 @@ Readings of points the paper leaves open (all mirrored by the HIP path):
     the first one wins;
   * p_original = softmax(logits / temperature); entropy in nats; strict ">";
   * accept length counts the root (1..K+1); the next root is the arg-max of the
-    original model's logits at the last accepted node.
+    original model's logits at the last accepted node;
+  * rejection-sampling acceptance: the paper names the scheme and defines
+    nothing, so medusa_accept_sampled_ref is a reading (stated in its
+    docstring): "parity unpinned" by the paper, pinned by the exact
+    reproduction of the original model's distribution on a tiny case.
 
 Pins: every function below is pinned by tests/test_oracle_*.py (closed forms,
 brute force on tiny inputs, invariants from the paper).  The paper prints no
@@ -360,6 +364,84 @@ def medusa_accept_ref(logits, tree_tokens, tree: Tree, mode: str,
         res.path_nodes[b, :best_len] = best_path[:best_len]
         res.accepted_tokens[b, :best_len] = tree_tokens[b, best_path[:best_len]]
         res.next_root[b] = top1[res.best_node[b]]
+    return res
+
+
+@dataclass
+class SampledAcceptResult:
+    accept_len: np.ndarray        # [B] int32, root included
+    best_node: np.ndarray         # [B] int32 last accepted node
+    path_nodes: np.ndarray        # [B, K+1] int32, -1 padded
+    accepted_tokens: np.ndarray   # [B, K+1] int32, -1 padded
+    next_token: np.ndarray        # [B] int32 token sampled after the last accepted node
+    margin: np.ndarray            # [B] float64 smallest distance of a uniform from the boundary it was compared with
+
+
+def medusa_accept_sampled_ref(logits, tree_tokens, tree: Tree, uniforms, temperature: float = 1.0) -> SampledAcceptResult:
+    """Sec. 2 (opening paragraph) and Sec. 2.3.1 (first paragraph) name "the rejection sampling
+    scheme as used in speculative decoding" as the acceptance rule that keeps the original model's
+    distribution, without defining it.  READING (parity unpinned by the paper; pinned by the
+    distribution it must reproduce): Medusa's candidates under a node are a deterministic list, so
+    each child, in rank order, is a draft whose proposal distribution is a point mass on its token x.
+    Speculative rejection sampling against the current target distribution r then accepts x with
+    probability min(1, r(x) / 1) = r(x), and after a rejection continues with the normalised
+    residual max(r - point mass, 0), i.e. r with x removed and renormalised.  With
+    p = softmax(logits[node] / temperature) as the first target, child i of a node is therefore
+    accepted iff all earlier children were rejected and
+        u_i < p(x_i) / (1 - sum_{j<i} p(x_j)),
+    u_i = uniforms[b, child i].  The walk starts at the root (always accepted) and moves to the
+    accepted child while there is one.  At the node where it stops the next token is drawn from
+    the final residual (p without the tokens of that node's children, renormalised; p itself at a
+    leaf) by inversion in token-id order with the uniform uniforms[b, 0] (the root's slot, which no
+    test uses): the smallest token y whose cumulative residual mass exceeds u * total.
+    logits [B, T, V]; tree_tokens [B, T]; uniforms [B, T] in [0, 1)."""
+    logits = np.asarray(logits, dtype=np.float64)
+    uniforms = np.asarray(uniforms, dtype=np.float64)
+    B, T, V = logits.shape
+    K = tree.K
+    res = SampledAcceptResult(np.zeros(B, np.int32), np.zeros(B, np.int32), np.full((B, K + 1), -1, np.int32),
+                              np.full((B, K + 1), -1, np.int32), np.zeros(B, np.int32), np.full(B, np.inf))
+    children = [[c for c in range(T) if tree.parent[c] == t] for t in range(T)]      # in node order = rank order
+    for b in range(B):
+        node, path = 0, [0]
+        while True:
+            z = logits[b, node] / temperature
+            e = np.exp(z - z.max())
+            p = e / e.sum()
+            removed = 0.0                      # probability mass of the children rejected so far
+            moved = False
+            for c in children[node]:
+                x = int(tree_tokens[b, c])
+                ratio = p[x] / (1.0 - removed) if removed < 1.0 else 0.0
+                res.margin[b] = min(res.margin[b], abs(uniforms[b, c] - ratio))
+                if uniforms[b, c] < ratio:
+                    node, moved = c, True
+                    path.append(c)
+                    break
+                removed += p[x]
+            if moved:
+                continue
+            resid = p.copy()
+            for c in children[node]:
+                resid[int(tree_tokens[b, c])] = 0.0
+            cdf = np.cumsum(resid)
+            target = uniforms[b, 0] * cdf[-1]
+            y = int(np.searchsorted(cdf, target, side="right"))
+            y = min(y, V - 1)
+            while resid[y] == 0.0 and y > 0:   # (rounding at the upper end only; a removed token is never drawn)
+                y -= 1
+            lo, hi = cdf[y] - resid[y], cdf[y]       # the drawn token's interval; its ends at 0 and at the total decide nothing
+            if lo > 0.0:
+                res.margin[b] = min(res.margin[b], (target - lo) / cdf[-1])
+            if hi < cdf[-1]:
+                res.margin[b] = min(res.margin[b], (hi - target) / cdf[-1])
+            res.next_token[b] = y
+            break
+        n = len(path)
+        res.accept_len[b] = n
+        res.best_node[b] = path[-1]
+        res.path_nodes[b, :n] = path
+        res.accepted_tokens[b, :n] = [int(tree_tokens[b, t]) for t in path]
     return res
 
 
