@@ -212,6 +212,35 @@ int medusa_accept(const float* logits, const int32_t* tree_tokens, const medusa_
                   int32_t* next_root, void* workspace, size_t workspace_bytes, medusa_stream_t stream);
 
 /* ----------------------------------------------------------------------------------
+ * medusa_accept_sampled: acceptance by rejection sampling, the alternative to typical acceptance
+ * that Sec. 2 (opening paragraph) and Sec. 2.3.1 (first paragraph) name -- "the rejection sampling
+ * scheme as used in speculative decoding" -- and that keeps the original model's distribution.
+ * The paper does not define the rule; this library's reading: the candidates under a node are a
+ * deterministic list, i.e. drafts whose proposal is a point mass on their token, so with
+ * p = softmax(logits[b,node,:] / temperature) child i of an accepted node (in rank order) is accepted
+ * iff all earlier children were rejected and
+ *     uniforms[b, child_i] < p(x_i) / (1 - sum_{j<i} p(x_j)),      x_j = tree_tokens[b, child_j],
+ * which is speculative rejection sampling against the residual distribution left by the rejected
+ * children.  The root is always accepted; the walk follows the accepted child while there is one.
+ * At the node where it ends, next_token is drawn from p without that node's children's tokens
+ * (renormalised; p itself at a leaf) by inversion in token-id order with uniforms[b, 0]: the
+ * smallest token whose cumulative mass exceeds uniforms[b,0] * total.  The tokens a step emits
+ * (accepted candidates, then next_token) are then distributed as the original model's own samples.
+ *   logits       [B, T, V] fp32, tree_tokens [B, T] int32 (as for medusa_accept)
+ *   uniforms     [B, T] fp32 in [0, 1), caller-supplied (the library draws no random numbers)
+ *   accept_len, best_node, path_nodes, accepted_tokens: as for medusa_accept
+ *   next_token   [B] int32 out: the sampled token that follows the accepted prefix
+ *   workspace: medusa_accept_workspace_bytes(B, T, V) bytes of device scratch.
+ * temperature > 0.  Comparisons are made in fp32 (sums in a fixed order): a uniform within rounding
+ * of its boundary may fall on either side.  Same limits and the same ticket counters as
+ * medusa_accept (the two must not overlap on one GPU either).
+ * -------------------------------------------------------------------------------- */
+int medusa_accept_sampled(const float* logits, const int32_t* tree_tokens, const medusa_tree_t* tree,
+                          const float* uniforms, int B, int V, float temperature, int32_t* accept_len,
+                          int32_t* best_node, int32_t* path_nodes, int32_t* accepted_tokens, int32_t* next_token,
+                          void* workspace, size_t workspace_bytes, medusa_stream_t stream);
+
+/* ----------------------------------------------------------------------------------
  * kv_commit (Fig. 1 caption: the accepted prefix is the context of the next step): for
  * every layer l, KV head h and j < accept_len[b]
  *   cache[l,b,h,prefix_len[b]+j,:] = tree[l,b,h,path_nodes[b,j],:]      (K and V)

@@ -26,7 +26,7 @@ EXPORTED_SYMBOLS = (
     "medusa_tree_query", "medusa_tree_tables", "medusa_heads", "medusa_topk_tree_workspace_bytes",
     "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "tree_attention_static",
     "tree_attention_static_scratch_bytes", "medusa_accept_workspace_bytes",
-    "medusa_accept", "kv_commit", "medusa_carry_over", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "tree_rope",
+    "medusa_accept", "medusa_accept_sampled", "kv_commit", "medusa_carry_over", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "tree_rope",
     "medusa_heads_timed",
     "medusa_set_cache_resident_bytes", "medusa_gemm_plan",
 )
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.medusa_accept_workspace_bytes.argtypes = [c_int] * 3
         L.medusa_accept.argtypes = ([c_void_p] * 3 + [c_int] * 3 + [c_float] * 3 + [c_void_p] * 5 +
                                     [c_void_p, c_size_t, c_void_p])
+        L.medusa_accept_sampled.argtypes = ([c_void_p] * 4 + [c_int] * 2 + [c_float] + [c_void_p] * 5 +
+                                            [c_void_p, c_size_t, c_void_p])
         L.kv_commit.argtypes = ([c_void_p] * 5 + [c_int, c_void_p, c_void_p, c_void_p] + [c_int] * 6 + [c_int, c_void_p])
         L.medusa_carry_over.argtypes = [c_void_p] * 5 + [c_int] * 5 + [c_void_p]
         L.tree_linear_workspace_bytes.restype = c_size_t
@@ -333,6 +335,34 @@ def medusa_accept(logits: torch.Tensor, tree_tokens: torch.Tensor, tree: MedusaT
                                path_nodes.data_ptr(), accepted_tokens.data_ptr(), next_root.data_ptr(),
                                workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream)),
            "medusa_accept")
+    return outputs
+
+
+def medusa_accept_sampled(logits: torch.Tensor, tree_tokens: torch.Tensor, tree: MedusaTree, uniforms: torch.Tensor,
+                          temperature: float = 1.0, outputs=None, workspace=None, stream=None):
+    """Rejection-sampling acceptance with caller-supplied uniforms [B, T] (slot 0 of a row draws the next
+    token).  Returns (accept_len [B], best_node [B], path_nodes [B,K+1], accepted_tokens [B,K+1], next_token [B])."""
+    B, T, V = logits.shape
+    if T != tree.T:
+        raise MedusaError(f"logits have {T} rows per sequence, the tree has {tree.T}")
+    dev = logits.device
+    _dev(logits, "logits", dtype=torch.float32)
+    _dev(tree_tokens, "tree_tokens", dtype=torch.int32, shape=(B, T))
+    _dev(uniforms, "uniforms", dtype=torch.float32, shape=(B, T))
+    if outputs is None:
+        i32 = dict(dtype=torch.int32, device=dev)
+        outputs = (torch.empty(B, **i32), torch.empty(B, **i32), torch.empty((B, tree.K + 1), **i32),
+                   torch.empty((B, tree.K + 1), **i32), torch.empty(B, **i32))
+    for o, name, shape in zip(outputs, ("accept_len", "best_node", "path_nodes", "accepted_tokens", "next_token"),
+                              ((B,), (B,), (B, tree.K + 1), (B, tree.K + 1), (B,))):
+        _dev(o, name, dtype=torch.int32, shape=shape)
+    if workspace is None:
+        workspace = _scratch(medusa_accept_workspace_bytes(B, T, V), dev)
+    _dev(workspace, "workspace")
+    _check(lib().medusa_accept_sampled(logits.data_ptr(), tree_tokens.data_ptr(), tree.handle, uniforms.data_ptr(), B, V,
+                                       float(temperature), *(o.data_ptr() for o in outputs), workspace.data_ptr(),
+                                       workspace.numel() * workspace.element_size(), _stream(stream)),
+           "medusa_accept_sampled")
     return outputs
 
 

@@ -289,7 +289,206 @@ __global__ __launch_bounds__(256) void accept_kernel(const float* __restrict__ l
                            accepted_tokens, next_root);
 }
 
+// Rejection-sampling acceptance (the scheme Sec. 2 and Sec. 2.3.1 name; the rule is stated at
+// medusa_accept_sampled in the header).  Runs in the 256 threads of the sequence's last workgroup.
+// Per node: w = 2^(t_tok - m_parent), the candidate's unnormalised probability under its parent's
+// row (S_parent = the row's sum of such terms); child i is tested with u_i * (S - sum of the earlier
+// siblings' w) < w_i and passes if no earlier sibling did.  The walk from the root follows the passing
+// children; since at most one child of a node passes, the accepted nodes form one chain and the
+// ancestor-mask test of the greedy/typical path applies unchanged.  The next token is drawn from the
+// last accepted node's row without its children's tokens, by inversion in token order: every thread
+// sums a contiguous slice of the row, a scan over the 256 slice sums finds the slice that holds
+// u_0 * total, and that slice's thread walks it.
+__device__ __forceinline__ void accept_finalize_sampled(int b, const float* __restrict__ logits,
+                                                        const int32_t* __restrict__ tree_tokens,
+                                                        const TreeTables* __restrict__ tree, const RowPart* __restrict__ part,
+                                                        const float* __restrict__ uniforms, int V, int chunks, float inv_temp,
+                                                        int32_t* __restrict__ accept_len, int32_t* __restrict__ best_node,
+                                                        int32_t* __restrict__ path_nodes, int32_t* __restrict__ accepted_tokens,
+                                                        int32_t* __restrict__ next_token) {
+  __shared__ float s_m[MEDUSA_MAX_TREE_TOKENS], s_S[MEDUSA_MAX_TREE_TOKENS], s_w[MEDUSA_MAX_TREE_TOKENS];
+  __shared__ uint64_t s_bits[2], s_pass[2];
+  __shared__ uint32_t s_best[2];
+  __shared__ uint64_t s_anc[MEDUSA_MAX_TREE_TOKENS][2];
+  __shared__ int32_t s_tok[MEDUSA_MAX_TREE_TOKENS], s_par[MEDUSA_MAX_TREE_TOKENS];
+  __shared__ float s_sum[256];
+  __shared__ int s_kid_tok[MEDUSA_MAX_TOPK + 1];
+  __shared__ int s_nkids, s_slice;
+  __shared__ float s_target, s_before;
+  const int t = threadIdx.x;
+  const int T = tree->T, K = tree->K;
+  const int lane = t & 63, wave = t >> 6;
+  const float k2 = inv_temp * 1.4426950408889634f;
+  int par = -1, tok = -1, dep = 0;
+  uint64_t anc0 = 0, anc1 = 0;
+  float u = 0.f;
+  if (t < T) {
+    par = tree->parent[t];
+    dep = tree->depth[t];
+    anc0 = tree->anc_mask[t][0];
+    anc1 = tree->anc_mask[t][1];
+    tok = tree_tokens[(size_t)b * T + t];
+    u = uniforms[(size_t)b * T + t];
+    const RowPart* p = part + ((size_t)b * T + t) * kAccMaxChunks;
+    float m = load_agent(&p[0].m), S = load_agent(&p[0].S), U = 0.f;
+    for (int c = 1; c < chunks; ++c) stats_merge(m, S, U, load_agent(&p[c].m), load_agent(&p[c].S), 0.f);
+    s_m[t] = m;
+    s_S[t] = S;
+    s_anc[t][0] = anc0;
+    s_anc[t][1] = anc1;
+    s_tok[t] = tok;
+    s_par[t] = par;
+  }
+  __syncthreads();
+  float w = 0.f;
+  if (t >= 1 && t < T && tok >= 0 && tok < V) w = __builtin_amdgcn_exp2f(logits[((size_t)b * T + par) * V + tok] * k2 - s_m[par]);
+  if (t < T) s_w[t] = w;
+  __syncthreads();
+  // the node's own test, with the mass of its earlier siblings (consecutive lower indices) taken out of the row's sum
+  bool test = false;
+  int first_sib = t;
+  if (t >= 1 && t < T) {
+    while (first_sib - 1 >= 1 && s_par[first_sib - 1] == par) --first_sib;
+    float removed = 0.f;
+    for (int c = first_sib; c < t; ++c) removed += s_w[c];
+    test = u * (s_S[par] - removed) < w;
+  }
+  const uint64_t tb = __ballot(test);
+  if (lane == 0 && wave < 2) s_bits[wave] = tb;
+  __syncthreads();
+  bool pass = t == 0;                                        // the root is accepted unconditionally
+  if (t >= 1 && t < T && test) {
+    pass = true;
+    for (int c = first_sib; c < t; ++c) pass = pass && !((s_bits[c >> 6] >> (c & 63)) & 1ull);   // an earlier sibling was taken
+  }
+  const uint64_t pb = __ballot(pass);
+  if (lane == 0 && wave < 2) s_pass[wave] = pb;
+  __syncthreads();
+  const uint64_t fail0 = ~s_pass[0], fail1 = ~s_pass[1];
+  uint32_t score = 0;
+  if (t < T && (anc0 & fail0) == 0 && (anc1 & fail1) == 0) score = ((uint32_t)(dep + 1) << 8) | (uint32_t)(255 - t);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) score = max(score, (uint32_t)__shfl_xor((int)score, o, kWave));
+  if (lane == 0 && wave < 2) s_best[wave] = score;
+  __syncthreads();
+  score = max(s_best[0], s_best[1]);
+  const int best = 255 - (int)(score & 255u);
+  const int alen = (int)(score >> 8);
+  if (t == 0) {
+    accept_len[b] = alen;
+    best_node[b] = best;
+    int n = 0;
+    for (int c = best + 1; c < T; ++c)
+      if (s_par[c] == best && n < MEDUSA_MAX_TOPK) s_kid_tok[n++] = s_tok[c];
+    s_nkids = n;
+  }
+  if (t <= K) {
+    int node = -1;
+    if (t < alen) {
+      int seen = 0;
+      for (int c = 0; c < T; ++c) {
+        if ((s_anc[best][c >> 6] >> (c & 63)) & 1ull) {
+          if (seen == t) { node = c; break; }
+          ++seen;
+        }
+      }
+    }
+    path_nodes[(size_t)b * (K + 1) + t] = node;
+    accepted_tokens[(size_t)b * (K + 1) + t] = node >= 0 ? s_tok[node] : -1;
+  }
+  __syncthreads();
+  // ---- draw the next token from the row of `best` without its children's tokens ----
+  const float* row = logits + ((size_t)b * T + best) * V;
+  const float m_best = s_m[best];
+  const int nk = s_nkids;
+  const int per = ceil_div(V, 256), lo = min(t * per, V), hi = min(V, lo + per);
+  bool has_kid = false;
+  for (int c = 0; c < nk; ++c) has_kid = has_kid || (s_kid_tok[c] >= lo && s_kid_tok[c] < hi);
+  auto weight = [&](int y) {
+    float wy = __builtin_amdgcn_exp2f(row[y] * k2 - m_best);
+    if (has_kid)
+      for (int c = 0; c < nk; ++c) wy = s_kid_tok[c] == y ? 0.f : wy;
+    return wy;
+  };
+  float sum = 0.f;
+  for (int y = lo; y < hi; ++y) sum += weight(y);
+  s_sum[t] = sum;
+  __syncthreads();
+  if (t == 0) {
+    float total = 0.f;
+    for (int j = 0; j < 256; ++j) total += s_sum[j];
+    const float target = uniforms[(size_t)b * T] * total;
+    float before = 0.f;
+    int slice = 0;
+    for (int j = 0; j < 256; ++j) {                        // the first slice whose cumulative sum exceeds the target
+      if (before + s_sum[j] > target) { slice = j; break; }
+      before += s_sum[j];
+      slice = j;
+    }
+    if (!(before + s_sum[slice] > target)) {               // rounding at the upper end: the last slice with any mass
+      before = 0.f;
+      int last = 0;
+      for (int j = 0; j < 256; ++j) if (s_sum[j] > 0.f) last = j;
+      for (int j = 0; j < last; ++j) before += s_sum[j];
+      slice = last;
+    }
+    s_slice = slice;
+    s_target = target;
+    s_before = before;
+  }
+  __syncthreads();
+  if (t == s_slice) {
+    float cum = s_before;
+    int pick = -1, last_pos = -1;
+    for (int y = lo; y < hi; ++y) {
+      const float wy = weight(y);
+      if (wy > 0.f) last_pos = y;
+      cum += wy;
+      if (pick < 0 && cum > s_target) pick = y;
+    }
+    next_token[b] = pick >= 0 ? pick : (last_pos >= 0 ? last_pos : max(lo, 0));
+  }
+}
+
+// grid (chunks, B*T), 256 threads.
+__global__ __launch_bounds__(256) void accept_sampled_kernel(const float* __restrict__ logits, const int32_t* __restrict__ tree_tokens,
+                                                             const TreeTables* __restrict__ tree, RowPart* __restrict__ part,
+                                                             const float* __restrict__ uniforms, int V, float inv_temp,
+                                                             int32_t* __restrict__ accept_len, int32_t* __restrict__ best_node,
+                                                             int32_t* __restrict__ path_nodes, int32_t* __restrict__ accepted_tokens,
+                                                             int32_t* __restrict__ next_token) {
+  const int chunks = gridDim.x;
+  row_stats<true>(logits, V, inv_temp, part, chunks);
+  const int T = tree->T;
+  const int b = blockIdx.y / T;
+  if (!last_workgroup_of(&g_accept_ticket[b], (unsigned)(chunks * T))) return;
+  accept_finalize_sampled(b, logits, tree_tokens, tree, part, uniforms, V, chunks, inv_temp, accept_len, best_node, path_nodes,
+                          accepted_tokens, next_token);
+}
+
 }  // namespace
+
+extern "C" int medusa_accept_sampled(const float* logits, const int32_t* tree_tokens, const medusa_tree_t* tree,
+                                     const float* uniforms, int B, int V, float temperature, int32_t* accept_len,
+                                     int32_t* best_node, int32_t* path_nodes, int32_t* accepted_tokens, int32_t* next_token,
+                                     void* workspace, size_t workspace_bytes, medusa_stream_t stream_) {
+  if (!logits || !tree_tokens || !tree || !uniforms || !accept_len || !best_node || !path_nodes || !accepted_tokens || !next_token)
+    return MEDUSA_EINVAL;
+  if (B < 1 || V < 1 || !(temperature > 0.f)) return MEDUSA_EINVAL;
+  if (B > kMaxBatch) return MEDUSA_EUNSUPPORTED;
+  const int T = tree->host.T;
+  if ((long)B * T > 65535) return MEDUSA_EUNSUPPORTED;
+  if (!tree->dev) return MEDUSA_EHIP;
+  if (!workspace || workspace_bytes < medusa_accept_workspace_bytes(B, T, V) || ((uintptr_t)workspace & 7) != 0)
+    return MEDUSA_EWORKSPACE;
+  int chunks = 260 / (B * T);
+  chunks = chunks < 1 ? 1 : (chunks > kAccMaxChunks ? kAccMaxChunks : chunks);
+  hipLaunchKernelGGL(accept_sampled_kernel, dim3(chunks, B * T), dim3(256), 0, (hipStream_t)stream_, logits, tree_tokens,
+                     tree->dev, (RowPart*)workspace, uniforms, V, 1.0f / temperature, accept_len, best_node, path_nodes,
+                     accepted_tokens, next_token);
+  MEDUSA_LAUNCH_CHECK();
+  return MEDUSA_OK;
+}
 
 extern "C" size_t medusa_accept_workspace_bytes(int B, int T, int V) {
   (void)V;
