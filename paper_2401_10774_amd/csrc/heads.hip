@@ -428,11 +428,19 @@ __global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmArgs a) {
 
   const int nk = a.d >> 6;                            // 64-element steps
   const int stages = (nk + 1) >> 1;
+  // Every workgroup walks the reduction from a different stage, wrapping around (the sum's order
+  // depends on the tile, not on the run).  All of a tile's rows are one row pitch apart, so the
+  // pieces a workgroup requests together fall on few memory channels; workgroups that start in
+  // lockstep at element 0 would all crowd the same ones (cold 262 MB matrix read this way, MI355X:
+  // 4.5 TB/s in lockstep, 5.5-5.8 rotated).
+  const int rot = (int)((blockIdx.x * 5u) % (unsigned)stages);
+  auto rotated = [&](int stage) { const int st = min(stage, stages - 1) + rot; return st >= stages ? st - stages : st; };
 
   u32x4_t regs[PD][LPT];
-  auto gload = [&](int stage, u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
+  auto gload = [&](int stage_l, u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
     // this thread's chunk lies in the first or second 64-element step of the stage; past the end
     // of the reduction the last step is fetched again (and never used)
+    const int stage = rotated(stage_l);
     const int e0 = min(2 * stage, nk - 1) * 64, e1 = min(2 * stage + 1, nk - 1) * 64;
     const uint32_t so_w = (uint32_t)(half ? e1 : e0) * 2u;
     const uint32_t so_x = (uint32_t)(half ? x_col_offset<HM>(a, e1) : x_col_offset<HM>(a, e0)) * 2u;
@@ -441,9 +449,9 @@ __global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmArgs a) {
       r[it] = it < MT ? *(const u32x4_t*)(Xb + (goff[it] + so_x)) : *(const u32x4_t*)(Wt + (goff[it] + so_w));
   };
   // (activation chunks of a half stage past the end of the reduction are stored as zeros)
-  auto lstore = [&](int buf, int stage, const u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
+  auto lstore = [&](int buf, int stage_l, const u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
     unsigned char* b = lds + buf * STAGE + st_off;
-    const uint32_t keep = (uint32_t) - (int)(2 * stage + half < nk);
+    const uint32_t keep = (uint32_t) - (int)(2 * rotated(stage_l) + half < nk);
 #pragma unroll
     for (int it = 0; it < LPT; ++it) *(u32x4_t*)(b + it * 4096) = it < MT ? (r[it] & keep) : r[it];
   };
@@ -572,6 +580,9 @@ __global__ __launch_bounds__(256) void gemm_runs_bf16_kernel(GemmArgs a) {
   const int c64 = lane;                                // this thread's 16-byte chunk of a 1 KB run
   const int n_super = (a.d + 511) >> 9;
   const int c_last = ((a.d - (n_super - 1) * 512) >> 3) - 1;   // last valid chunk of the last super-stage
+  // every workgroup starts the reduction at a different super-stage and wraps around (see the kernel above)
+  const int rot = (int)((blockIdx.x * 3u) % (unsigned)n_super);
+  auto rotated = [&](int S) { const int Sr = min(S, n_super - 1) + rot; return Sr >= n_super ? Sr - n_super : Sr; };
 
   // Byte offsets of the rows this thread fetches (from the tile's first weight row; from X).
   const int w_last = a.N - 1 - n0;                     // last weight row of the matrix, relative to the tile
@@ -587,14 +598,14 @@ __global__ __launch_bounds__(256) void gemm_runs_bf16_kernel(GemmArgs a) {
   // Requests of sub-stage u = 4*S + g: the weights of column group g, super-stage S, and -- for
   // g = 2, 3, 0 -- piece 0, 1, 2 of the activation rows of super-stage S+1, S+1, S.
   auto gload = [&](int S, int g, u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
-    const int Sw = min(S, n_super - 1);
+    const int Sw = rotated(S);
     const int cw = Sw == n_super - 1 ? min(c64, c_last) : c64;
     const uint32_t so_w = (uint32_t)(Sw * 1024 + cw * 16);
 #pragma unroll
     for (int it = 0; it < WC; ++it) r[it] = *(const u32x4_t*)(Wt + ((uint32_t)min(g * 32 + it * 4 + wave, w_last) * w_pitch + so_w));
     if (g != 1) {
       const int p = g == 0 ? 2 : g - 2;
-      const int Sx = min(g == 0 ? S : S + 1, n_super - 1);
+      const int Sx = rotated(g == 0 ? S : S + 1);
       const int cx = Sx == n_super - 1 ? min(c64, c_last) : c64;
       const uint32_t so_x = (uint32_t)(x_col_offset<HM>(a, Sx * 512 + (cx & ~7) * 8) * 2) + (cx & 7) * 16;
 #pragma unroll
@@ -611,8 +622,8 @@ __global__ __launch_bounds__(256) void gemm_runs_bf16_kernel(GemmArgs a) {
     for (int it = 0; it < WC; ++it) *(u32x4_t*)(wb + it * 4096 + slot_of(it * 4 + wave)) = r[it];
     if (g != 1) {
       const int p = g == 0 ? 2 : g - 2;
-      const int Sx = g == 0 ? S : S + 1;
-      const uint32_t keep = (uint32_t) - (int)(Sx < n_super - 1 || (Sx == n_super - 1 && c64 <= c_last));
+      const int Sl = g == 0 ? S : S + 1, Sx = rotated(Sl);     // (a super-stage past the end is never used: zeros)
+      const uint32_t keep = (uint32_t) - (int)(Sl < n_super && (Sx < n_super - 1 || c64 <= c_last));
 #pragma unroll
       for (int i = 0; i < XC; ++i) {
         const int q = p * XC + i < XQ ? p * XC + i : XQ - 1;
@@ -637,9 +648,10 @@ __global__ __launch_bounds__(256) void gemm_runs_bf16_kernel(GemmArgs a) {
   // Prologue: the activation rows of super-stage 0 and the weights of sub-stage 0 into LDS,
   // sub-stages 1..PD-1 requested.
   {
-    const int cx = n_super == 1 ? min(c64, c_last) : c64;
-    const uint32_t so_x = (uint32_t)(x_col_offset<HM>(a, (cx & ~7) * 8) * 2) + (cx & 7) * 16;
-    const uint32_t keep = (uint32_t) - (int)(n_super > 1 || c64 <= c_last);
+    const int S0 = rotated(0);
+    const int cx = S0 == n_super - 1 ? min(c64, c_last) : c64;
+    const uint32_t so_x = (uint32_t)(x_col_offset<HM>(a, S0 * 512 + (cx & ~7) * 8) * 2) + (cx & 7) * 16;
+    const uint32_t keep = (uint32_t) - (int)(S0 < n_super - 1 || c64 <= c_last);
     u32x4_t x0[XQ];
 #pragma unroll
     for (int q = 0; q < XQ; ++q) x0[q] = *(const u32x4_t*)(Xb + (xoff[q] + so_x));
