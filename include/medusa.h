@@ -50,6 +50,9 @@ typedef enum {
   MEDUSA_ESCRATCH = -5       /* the shape needs more scratch than the library's built-in array holds */
 } medusa_status_t;
 
+/* Values of the `dtype` and `mode` arguments.  The arguments themselves are plain ints, so that any
+ * value a caller passes is looked at by the argument checks (and refused with MEDUSA_EINVAL) rather
+ * than being an out-of-range enumeration value. */
 typedef enum { MEDUSA_F32 = 0, MEDUSA_BF16 = 1 } medusa_dtype_t;
 typedef enum { MEDUSA_GREEDY = 0, MEDUSA_TYPICAL = 1 } medusa_accept_mode_t;
 
@@ -125,7 +128,7 @@ int medusa_tree_tables(const medusa_tree_t* tree, int32_t* parent, int32_t* dept
  * Limits: 1 <= M <= 4096, 1 <= K <= 8, d a multiple of 8 (bf16: of 64), d <= 16384, V >= 1.
  * -------------------------------------------------------------------------------- */
 int medusa_heads(const void* hidden, const void* w1, const void* w2, void* resid, float* logits,
-                 int M, int d, int V, int K, medusa_dtype_t dtype, medusa_stream_t stream);
+                 int M, int d, int V, int K, int dtype, medusa_stream_t stream);
 
 /* ----------------------------------------------------------------------------------
  * medusa_topk_tree (Sec. 2.1.2): per sequence, the top-S_k tokens of head k (sorted, best
@@ -166,7 +169,7 @@ int medusa_topk_tree(const float* medusa_logits, const float* lm_logits, const m
 size_t tree_attention_workspace_bytes(int B, int Hq, int Hkv, int T, int D, int Lcap);
 int tree_attention(const void* q, const void* k_tree, const void* v_tree, const void* k_cache,
                    const void* v_cache, const int32_t* prefix_len, const medusa_tree_t* tree, void* out,
-                   int B, int Hq, int Hkv, int D, int Lcap, float scale, medusa_dtype_t dtype,
+                   int B, int Hq, int Hkv, int D, int Lcap, float scale, int dtype,
                    void* workspace, size_t workspace_bytes, medusa_stream_t stream);
 
 /* tree_attention_static: tree_attention for callers that cannot allocate device memory or keep a
@@ -183,7 +186,7 @@ int tree_attention(const void* q, const void* k_tree, const void* v_tree, const 
 size_t tree_attention_static_scratch_bytes(void);
 int tree_attention_static(const void* q, const void* k_tree, const void* v_tree, const void* k_cache,
                           const void* v_cache, const int32_t* prefix_len, const medusa_tree_t* tree, void* out,
-                          int B, int Hq, int Hkv, int D, int Lcap, float scale, medusa_dtype_t dtype,
+                          int B, int Hq, int Hkv, int D, int Lcap, float scale, int dtype,
                           medusa_stream_t stream);
 
 /* ----------------------------------------------------------------------------------
@@ -207,7 +210,7 @@ int tree_attention_static(const void* q, const void* k_tree, const void* v_tree,
  * -------------------------------------------------------------------------------- */
 size_t medusa_accept_workspace_bytes(int B, int T, int V);
 int medusa_accept(const float* logits, const int32_t* tree_tokens, const medusa_tree_t* tree, int B, int V,
-                  medusa_accept_mode_t mode, float temperature, float eps, float delta,
+                  int mode, float temperature, float eps, float delta,
                   int32_t* accept_len, int32_t* best_node, int32_t* path_nodes, int32_t* accepted_tokens,
                   int32_t* next_root, void* workspace, size_t workspace_bytes, medusa_stream_t stream);
 
@@ -256,7 +259,7 @@ int medusa_accept_sampled(const float* logits, const int32_t* tree_tokens, const
  * -------------------------------------------------------------------------------- */
 int kv_commit(void* k_cache, void* v_cache, const void* k_tree, const void* v_tree,
               const int32_t* path_nodes, int path_stride, const int32_t* accept_len, int32_t* prefix_len,
-              int32_t* prefix_len_out, int NL, int B, int Hkv, int T, int D, int Lcap, medusa_dtype_t dtype,
+              int32_t* prefix_len_out, int NL, int B, int Hkv, int T, int D, int Lcap, int dtype,
               medusa_stream_t stream);
 
 /* ----------------------------------------------------------------------------------
@@ -273,7 +276,7 @@ int kv_commit(void* k_cache, void* v_cache, const void* k_tree, const void* v_tr
  * Raw row copies: bit-exact.  Limits: B <= 65535; bf16: d even.
  * -------------------------------------------------------------------------------- */
 int medusa_carry_over(const void* hidden_tree, const float* verify_logits, const int32_t* best_node, void* h_next,
-                      float* lm_next, int B, int T, int d, int V, medusa_dtype_t dtype, medusa_stream_t stream);
+                      float* lm_next, int B, int T, int d, int V, int dtype, medusa_stream_t stream);
 
 /* ----------------------------------------------------------------------------------
  * Backbone operators on the tree tokens (App. G: operator table, "Parallel decoding" rows
@@ -298,9 +301,9 @@ int medusa_carry_over(const void* hidden_tree, const float* verify_logits, const
  * of y_heads.  All pointers are device pointers; returns MEDUSA_EINVAL / MEDUSA_EUNSUPPORTED
  * without launching anything when a limit is violated.
  * -------------------------------------------------------------------------------- */
-size_t tree_linear_workspace_bytes(int B, int T, int d_in, int d_out, medusa_dtype_t dtype);
+size_t tree_linear_workspace_bytes(int B, int T, int d_in, int d_out, int dtype);
 int tree_linear(const void* x, const void* w, const void* mul, void* y, int B, int T, int d_in, int d_out,
-                int x_heads, int y_heads, medusa_dtype_t dtype, void* workspace, size_t workspace_bytes,
+                int x_heads, int y_heads, int dtype, void* workspace, size_t workspace_bytes,
                 medusa_stream_t stream);
 
 /* tree_linear with the head-major output cut into y_segments tensors (App. G: X W_Q, X W_K and X W_V
@@ -315,7 +318,7 @@ int tree_linear(const void* x, const void* w, const void* mul, void* y, int B, i
  * y_segments x y_heads whole heads or the segments would overlap.
  */
 int tree_linear_segments(const void* x, const void* w, const void* mul, void* y, int B, int T, int d_in, int d_out,
-                         int x_heads, int y_heads, int y_segments, size_t y_segment_stride, medusa_dtype_t dtype,
+                         int x_heads, int y_heads, int y_segments, size_t y_segment_stride, int dtype,
                          void* workspace, size_t workspace_bytes, medusa_stream_t stream);
 
 /* tree_rope: rotary position embedding, in place, of q [B, Hq, T, D] and k [B, Hkv, T, D] (dtype)
@@ -323,7 +326,7 @@ int tree_linear_segments(const void* x, const void* w, const void* mul, void* y,
  * depth of the node).  Element j < D/2 is paired with element j + D/2; the pair is rotated by
  * position * theta^(-2j/D).  D must be even. */
 int tree_rope(void* q, void* k, const int32_t* position_ids, int B, int Hq, int Hkv, int T, int D, float theta,
-              medusa_dtype_t dtype, medusa_stream_t stream);
+              int dtype, medusa_stream_t stream);
 
 /* Gate and up projections of the gated feed-forward in one pass (App. G, operator table, rows
  * X W_g and X W_u): y = SiLU(x w_g^T) * (x w_u^T), rounded once, with no intermediate in memory.
@@ -338,7 +341,7 @@ int tree_rope(void* q, void* k, const int32_t* position_ids, int B, int Hq, int 
  * kernel (medusa_gemm_plan(B*T, 2*d_out, d_in, 1, 0) says kind 3); correct, but slower than two
  * tree_linear calls, for row counts in between. */
 int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int B, int T, int d_in, int d_out, int x_heads,
-                       int y_heads, medusa_dtype_t dtype, medusa_stream_t stream);
+                       int y_heads, int dtype, medusa_stream_t stream);
 
 /* ----------------------------------------------------------------------------------
  * Tuning knob (no counterpart in the paper).  The MFMA kernels of medusa_heads and tree_linear
@@ -373,7 +376,7 @@ int medusa_gemm_plan(int M, int N, int d, int K, int have_workspace, int* plan6)
  * Everything else is medusa_heads; MEDUSA_EINVAL if an event is NULL.
  * -------------------------------------------------------------------------------- */
 int medusa_heads_timed(const void* hidden, const void* w1, const void* w2, void* resid, float* logits, int M, int d,
-                       int V, int K, medusa_dtype_t dtype, medusa_stream_t stream, void* ev_begin, void* ev_between,
+                       int V, int K, int dtype, medusa_stream_t stream, void* ev_begin, void* ev_between,
                        void* ev_end);
 
 #ifdef __cplusplus

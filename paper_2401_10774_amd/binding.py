@@ -14,7 +14,8 @@ from typing import Optional, Sequence, Tuple
 import numpy as np
 import torch
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmedusa_hip.so")
+# MEDUSA_LIB_PATH names another build of the same library (the host-sanitizer build the CPU tests use).
+_LIB_PATH = os.environ.get("MEDUSA_LIB_PATH") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmedusa_hip.so")
 _lib_handle = None
 
 MEDUSA_F32, MEDUSA_BF16 = 0, 1

@@ -49,9 +49,26 @@ def _run(cmd):
     return proc.stdout
 
 
-def build_library(verbose: bool = False) -> str:
+# Host-side sanitizers (AddressSanitizer + UndefinedBehaviorSanitizer) for the library's host code --
+# argument checks, tree builders, GEMM planning -- in a second library that the CPU tests load in a
+# child process (tests/test_host_sanitizer.py).  Device code is compiled as usual.
+HOST_SANITIZER_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                        "-Xarch_host", "-fno-omit-frame-pointer", "-Xarch_host", "-fno-sanitize-recover=undefined", "-g"]
+
+
+def sanitizer_runtime() -> str:
+    """The shared AddressSanitizer runtime of hipcc's clang (to be preloaded into the Python process)."""
+    import glob
+    hits = sorted(glob.glob("/opt/rocm/lib/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so"))
+    if not hits:
+        raise RuntimeError("no shared AddressSanitizer runtime found next to hipcc's clang")
+    return hits[-1]
+
+
+def build_library(verbose: bool = False, host_sanitizers: bool = False, out_path: str = None) -> str:
     hipcc = _hipcc()
-    extra = os.environ.get("MEDUSA_HIPCC_EXTRA", "").split()      # tuning knobs, e.g. -DMEDUSA_GEMM_STAGES=3
+    extra = HOST_SANITIZER_FLAGS if host_sanitizers else []
+    out_path = out_path or LIB_PATH
     tmp = tempfile.mkdtemp(prefix="medusa_hip_build_")
     try:
         objs = [os.path.join(tmp, s.replace(".hip", ".o")) for s in SOURCES]
@@ -68,11 +85,12 @@ def build_library(verbose: bool = False) -> str:
                 if text.strip():
                     print("[%s]\n%s" % (s, text))
         out_tmp = os.path.join(tmp, "libmedusa_hip.so")
-        _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out_tmp])
-        shutil.move(out_tmp, LIB_PATH)
+        link_extra = ["-fsanitize=address", "-fsanitize=undefined", "-shared-libsan"] if host_sanitizers else []
+        _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *link_extra, *objs, "-o", out_tmp])
+        shutil.move(out_tmp, out_path)
     finally:
         shutil.rmtree(tmp, ignore_errors=True)
-    return LIB_PATH
+    return out_path
 
 
 if __name__ == "__main__":

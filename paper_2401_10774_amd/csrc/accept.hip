@@ -497,7 +497,7 @@ extern "C" size_t medusa_accept_workspace_bytes(int B, int T, int V) {
 }
 
 extern "C" int medusa_accept(const float* logits, const int32_t* tree_tokens, const medusa_tree_t* tree, int B, int V,
-                             medusa_accept_mode_t mode, float temperature, float eps, float delta, int32_t* accept_len,
+                             int mode, float temperature, float eps, float delta, int32_t* accept_len,
                              int32_t* best_node, int32_t* path_nodes, int32_t* accepted_tokens, int32_t* next_root,
                              void* workspace, size_t workspace_bytes, medusa_stream_t stream_) {
   if (!logits || !tree_tokens || !tree || !accept_len || !best_node || !path_nodes || !accepted_tokens || !next_root)

@@ -916,7 +916,7 @@ int launch_skinny(dim3 grid, size_t lds, hipStream_t stream, const GemmArgs& a) 
 }
 
 template <int EPI>
-int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) {
+int launch_gemm(const GemmArgs& a_in, int dtype, hipStream_t stream) {
   GemmArgs a = a_in;
   a.ksplit = 1;
   a.rows_per_wg = gemv_rows_per_wg(a.N, a.K, dtype == MEDUSA_BF16 ? a.M : 1);
@@ -991,7 +991,7 @@ int launch_gemm(const GemmArgs& a_in, medusa_dtype_t dtype, hipStream_t stream) 
 // medusa_heads; `ev` is null, or three events recorded before the residual-block kernel, between
 // the two kernels and after the vocabulary projection.
 static int heads_impl(const void* hidden, const void* w1, const void* w2, void* resid, float* logits, int M, int d, int V,
-                      int K, medusa_dtype_t dtype, medusa_stream_t stream_, hipEvent_t* ev) {
+                      int K, int dtype, medusa_stream_t stream_, hipEvent_t* ev) {
   if (!hidden || !w2 || !logits || (w1 && !resid)) return MEDUSA_EINVAL;
   if (M < 1 || d < 1 || V < 1 || K < 1) return MEDUSA_EINVAL;
   if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;
@@ -1035,12 +1035,12 @@ static int heads_impl(const void* hidden, const void* w1, const void* w2, void* 
 }
 
 extern "C" int medusa_heads(const void* hidden, const void* w1, const void* w2, void* resid, float* logits, int M,
-                            int d, int V, int K, medusa_dtype_t dtype, medusa_stream_t stream_) {
+                            int d, int V, int K, int dtype, medusa_stream_t stream_) {
   return heads_impl(hidden, w1, w2, resid, logits, M, d, V, K, dtype, stream_, nullptr);
 }
 
 extern "C" int medusa_heads_timed(const void* hidden, const void* w1, const void* w2, void* resid, float* logits, int M,
-                                  int d, int V, int K, medusa_dtype_t dtype, medusa_stream_t stream_, void* ev_begin,
+                                  int d, int V, int K, int dtype, medusa_stream_t stream_, void* ev_begin,
                                   void* ev_between, void* ev_end) {
   if (!ev_begin || !ev_between || !ev_end) return MEDUSA_EINVAL;
   hipEvent_t ev[3] = {(hipEvent_t)ev_begin, (hipEvent_t)ev_between, (hipEvent_t)ev_end};
@@ -1048,19 +1048,19 @@ extern "C" int medusa_heads_timed(const void* hidden, const void* w1, const void
 }
 
 // Backbone linear layer on the tree tokens (App. G, operator table, parallel-decoding rows).
-extern "C" size_t tree_linear_workspace_bytes(int B, int T, int d_in, int d_out, medusa_dtype_t dtype) {
+extern "C" size_t tree_linear_workspace_bytes(int B, int T, int d_in, int d_out, int dtype) {
   if (dtype != MEDUSA_BF16 || B < 1 || T < 1 || d_in < 64 || d_out < 1) return 0;
   return gemm_ws_bytes(B * T, d_out, d_in, 1);
 }
 
 extern "C" int tree_linear(const void* x, const void* w, const void* mul, void* y, int B, int T, int d_in, int d_out,
-                           int x_heads, int y_heads, medusa_dtype_t dtype, void* workspace, size_t workspace_bytes,
+                           int x_heads, int y_heads, int dtype, void* workspace, size_t workspace_bytes,
                            medusa_stream_t stream_) {
   return tree_linear_segments(x, w, mul, y, B, T, d_in, d_out, x_heads, y_heads, 1, 0, dtype, workspace, workspace_bytes, stream_);
 }
 
 extern "C" int tree_linear_segments(const void* x, const void* w, const void* mul, void* y, int B, int T, int d_in, int d_out,
-                                    int x_heads, int y_heads, int y_segments, size_t y_segment_stride, medusa_dtype_t dtype,
+                                    int x_heads, int y_heads, int y_segments, size_t y_segment_stride, int dtype,
                                     void* workspace, size_t workspace_bytes, medusa_stream_t stream_) {
   if (!x || !w || !y) return MEDUSA_EINVAL;
   if (B < 1 || T < 1 || d_in < 1 || d_out < 1 || x_heads < 0 || y_heads < 0 || y_segments < 1) return MEDUSA_EINVAL;
@@ -1112,7 +1112,7 @@ extern "C" int tree_linear_segments(const void* x, const void* w, const void* mu
 // Gate and up projections of the gated feed-forward in one pass over both weight matrices (App. G,
 // operator table: X W_g and X W_u; the product SiLU(X W_g) * (X W_u) is what X W_d consumes).
 extern "C" int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int B, int T, int d_in, int d_out, int x_heads,
-                                  int y_heads, medusa_dtype_t dtype, medusa_stream_t stream_) {
+                                  int y_heads, int dtype, medusa_stream_t stream_) {
   if (!x || !w_gu || !y) return MEDUSA_EINVAL;
   if (B < 1 || T < 1 || d_in < 1 || d_out < 1 || x_heads < 0 || y_heads < 0) return MEDUSA_EINVAL;
   if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;

@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256) void carry_over_kernel(const uint32_t* __restr
 }  // namespace
 
 extern "C" int medusa_carry_over(const void* hidden_tree, const float* verify_logits, const int32_t* best_node,
-                                 void* h_next, float* lm_next, int B, int T, int d, int V, medusa_dtype_t dtype,
+                                 void* h_next, float* lm_next, int B, int T, int d, int V, int dtype,
                                  medusa_stream_t stream_) {
   if (!best_node || (!hidden_tree != !h_next) || (!verify_logits != !lm_next) || (!h_next && !lm_next)) return MEDUSA_EINVAL;
   if (B < 1 || T < 1 || (h_next && d < 1) || (lm_next && V < 1)) return MEDUSA_EINVAL;
@@ -102,7 +102,7 @@ extern "C" int medusa_carry_over(const void* hidden_tree, const float* verify_lo
 
 extern "C" int kv_commit(void* k_cache, void* v_cache, const void* k_tree, const void* v_tree, const int32_t* path_nodes,
                          int path_stride, const int32_t* accept_len, int32_t* prefix_len, int32_t* prefix_len_out, int NL,
-                         int B, int Hkv, int T, int D, int Lcap, medusa_dtype_t dtype, medusa_stream_t stream_) {
+                         int B, int Hkv, int T, int D, int Lcap, int dtype, medusa_stream_t stream_) {
   if (!k_cache || !v_cache || !k_tree || !v_tree || !path_nodes || !accept_len || !prefix_len) return MEDUSA_EINVAL;
   if (NL < 1 || B < 1 || Hkv < 1 || T < 1 || D < 1 || Lcap < 1 || path_stride < 1) return MEDUSA_EINVAL;
   if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;

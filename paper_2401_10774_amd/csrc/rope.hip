@@ -62,7 +62,7 @@ __global__ __launch_bounds__(1024) void tree_rope_kernel(RopeArgs a) {
 }  // namespace
 
 extern "C" int tree_rope(void* q, void* k, const int32_t* position_ids, int B, int Hq, int Hkv, int T, int D, float theta,
-                         medusa_dtype_t dtype, medusa_stream_t stream_) {
+                         int dtype, medusa_stream_t stream_) {
   if (!q || !k || !position_ids) return MEDUSA_EINVAL;
   if (B < 1 || Hq < 1 || Hkv < 1 || T < 1 || D < 2 || (D & 1) || !(theta > 0.f)) return MEDUSA_EINVAL;
   if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;

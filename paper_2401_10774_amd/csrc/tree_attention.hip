@@ -660,7 +660,7 @@ extern "C" size_t tree_attention_static_scratch_bytes(void) { return kStaticScra
 
 extern "C" int tree_attention_static(const void* q, const void* k_tree, const void* v_tree, const void* k_cache,
                                      const void* v_cache, const int32_t* prefix_len, const medusa_tree_t* tree, void* out,
-                                     int B, int Hq, int Hkv, int D, int Lcap, float scale, medusa_dtype_t dtype,
+                                     int B, int Hq, int Hkv, int D, int Lcap, float scale, int dtype,
                                      medusa_stream_t stream_) {
   if (!tree) return MEDUSA_EINVAL;
   if (B < 1 || Hq < 1 || Hkv < 1 || Lcap < 1 || Hq % Hkv != 0) return MEDUSA_EINVAL;
@@ -675,7 +675,7 @@ extern "C" int tree_attention_static(const void* q, const void* k_tree, const vo
 
 extern "C" int tree_attention(const void* q, const void* k_tree, const void* v_tree, const void* k_cache,
                               const void* v_cache, const int32_t* prefix_len, const medusa_tree_t* tree, void* out, int B,
-                              int Hq, int Hkv, int D, int Lcap, float scale, medusa_dtype_t dtype, void* workspace,
+                              int Hq, int Hkv, int D, int Lcap, float scale, int dtype, void* workspace,
                               size_t workspace_bytes, medusa_stream_t stream_) {
   if (!q || !k_tree || !v_tree || !k_cache || !v_cache || !prefix_len || !tree || !out) return MEDUSA_EINVAL;
   if (B < 1 || Hq < 1 || Hkv < 1 || Lcap < 1 || Hq % Hkv != 0) return MEDUSA_EINVAL;
