@@ -252,7 +252,7 @@ def per_call_timings(step, cfg, parts, w1_ms, w2_ms, n=48):
     one kernel, except attention: split kernel + merge); MB = its algorithmic bytes."""
     import torch
     stream = torch.cuda.current_stream().cuda_stream
-    names = ["heads", "topk_tree", "attention", "verify_lm_head", "accept", "commit"]
+    names = ["heads", "topk_tree", "attention", "verify_lm_head", "accept", "commit"]   # (verify + accept may be the fused pair)
     pairs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in names] for _ in range(n)]
     for i in range(n):
         pre, post = step._calls(i % cfg.NL, i)

@@ -215,6 +215,36 @@ int medusa_accept(const float* logits, const int32_t* tree_tokens, const medusa_
                   int32_t* next_root, void* workspace, size_t workspace_bytes, medusa_stream_t stream);
 
 /* ----------------------------------------------------------------------------------
+ * medusa_verify_logits + medusa_accept_fused: steps (2) and (3) of Sec. 2 with the acceptance step's
+ * pass over the logits folded into the projection that produces them (Sec. 2.3.1 needs, per row of
+ * the original model's logits, the arg-max and -- for typical acceptance -- max, sum exp and
+ * sum z exp of z = logit / temperature; medusa_accept reads all B*T*V logits again to get them).
+ *
+ * medusa_verify_logits = medusa_heads(hidden_tree, NULL, w_lm, NULL, logits, M, d, V, 1, dtype) --
+ * the same logits, bit for bit -- whose kernel also leaves, per row and 128-column piece of its
+ * output tiles, (arg-max key, max, sum, weighted sum) in `stats`.  medusa_accept_fused then gives
+ * medusa_accept's results from those partials and the few logits it looks up (the candidates' own),
+ * in a kernel that reads a few KB per row.  The arg-max, and with it greedy acceptance and next_root,
+ * is exact; the typical-acceptance statistics are summed in another order than medusa_accept's
+ * (fp32), so a probability within rounding of its threshold may fall on either side.
+ *   stats: medusa_verify_stats_bytes(M, V) bytes of device scratch, 256-byte aligned, written by
+ *   medusa_verify_logits and read and partly rewritten by medusa_accept_fused; one such pair of calls
+ *   per buffer at a time.  mode, temperature: the same values in both calls (medusa_accept_fused
+ *   reports accept_len[b] = -1 for statistics that were produced for another mode or temperature).
+ * The fused epilogue exists in the large-tile kernel only (many tree rows: batches of trees);
+ * medusa_verify_fused_available(M, d, V, dtype) says whether a shape gets it (1) or
+ * medusa_verify_logits returns MEDUSA_EUNSUPPORTED and the caller stays with medusa_heads +
+ * medusa_accept (0).  Other limits and the ticket counters: as for medusa_heads / medusa_accept.
+ * -------------------------------------------------------------------------------- */
+size_t medusa_verify_stats_bytes(int M, int V);
+int medusa_verify_fused_available(int M, int d, int V, int dtype);
+int medusa_verify_logits(const void* hidden_tree, const void* w_lm, float* logits, void* stats, size_t stats_bytes, int M,
+                         int d, int V, int dtype, int mode, float temperature, medusa_stream_t stream);
+int medusa_accept_fused(const float* logits, const void* stats, const int32_t* tree_tokens, const medusa_tree_t* tree, int B,
+                        int V, int mode, float temperature, float eps, float delta, int32_t* accept_len, int32_t* best_node,
+                        int32_t* path_nodes, int32_t* accepted_tokens, int32_t* next_root, medusa_stream_t stream);
+
+/* ----------------------------------------------------------------------------------
  * medusa_accept_sampled: acceptance by rejection sampling, the alternative to typical acceptance
  * that Sec. 2 (opening paragraph) and Sec. 2.3.1 (first paragraph) name -- "the rejection sampling
  * scheme as used in speculative decoding" -- and that keeps the original model's distribution.

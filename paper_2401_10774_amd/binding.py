@@ -27,7 +27,8 @@ EXPORTED_SYMBOLS = (
     "medusa_tree_query", "medusa_tree_tables", "medusa_heads", "medusa_topk_tree_workspace_bytes",
     "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "tree_attention_static",
     "tree_attention_static_scratch_bytes", "medusa_accept_workspace_bytes",
-    "medusa_accept", "medusa_accept_sampled", "kv_commit", "medusa_carry_over", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "tree_rope",
+    "medusa_accept", "medusa_accept_sampled", "medusa_verify_stats_bytes", "medusa_verify_fused_available",
+    "medusa_verify_logits", "medusa_accept_fused", "kv_commit", "medusa_carry_over", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "tree_rope",
     "medusa_heads_timed",
     "medusa_set_cache_resident_bytes", "medusa_gemm_plan",
 )
@@ -73,6 +74,11 @@ def lib() -> ctypes.CDLL:
         L.medusa_accept_workspace_bytes.argtypes = [c_int] * 3
         L.medusa_accept.argtypes = ([c_void_p] * 3 + [c_int] * 3 + [c_float] * 3 + [c_void_p] * 5 +
                                     [c_void_p, c_size_t, c_void_p])
+        L.medusa_verify_stats_bytes.restype = c_size_t
+        L.medusa_verify_stats_bytes.argtypes = [c_int, c_int]
+        L.medusa_verify_fused_available.argtypes = [c_int] * 4
+        L.medusa_verify_logits.argtypes = [c_void_p] * 4 + [c_size_t] + [c_int] * 5 + [c_float, c_void_p]
+        L.medusa_accept_fused.argtypes = [c_void_p] * 4 + [c_int] * 3 + [c_float] * 3 + [c_void_p] * 5 + [c_void_p]
         L.medusa_accept_sampled.argtypes = ([c_void_p] * 4 + [c_int] * 2 + [c_float] + [c_void_p] * 5 +
                                             [c_void_p, c_size_t, c_void_p])
         L.kv_commit.argtypes = ([c_void_p] * 5 + [c_int, c_void_p, c_void_p, c_void_p] + [c_int] * 6 + [c_int, c_void_p])
@@ -336,6 +342,54 @@ def medusa_accept(logits: torch.Tensor, tree_tokens: torch.Tensor, tree: MedusaT
                                path_nodes.data_ptr(), accepted_tokens.data_ptr(), next_root.data_ptr(),
                                workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream(stream)),
            "medusa_accept")
+    return outputs
+
+
+def medusa_verify_fused_available(M: int, d: int, V: int, dtype: torch.dtype) -> bool:
+    return bool(lib().medusa_verify_fused_available(M, d, V, 1 if dtype == torch.bfloat16 else 0))
+
+
+def medusa_verify_logits(hidden_tree: torch.Tensor, w_lm: torch.Tensor, mode: str = "greedy", temperature: float = 1.0,
+                         logits: Optional[torch.Tensor] = None, stats: Optional[torch.Tensor] = None, stream=None):
+    """LM-head logits of the tree rows [M, d] x [V, d] plus the acceptance step's row reductions.  Returns (logits [M, V], stats)."""
+    M, d = hidden_tree.shape
+    V = w_lm.shape[0]
+    _dev(hidden_tree, "hidden_tree")
+    _dev(w_lm, "w_lm", dtype=hidden_tree.dtype, shape=(V, d))
+    if logits is None:
+        logits = torch.empty((M, V), dtype=torch.float32, device=hidden_tree.device)
+    _dev(logits, "logits", dtype=torch.float32)
+    if stats is None:
+        stats = _scratch(lib().medusa_verify_stats_bytes(M, V), hidden_tree.device)
+    _dev(stats, "stats")
+    code = {"greedy": MEDUSA_GREEDY, "typical": MEDUSA_TYPICAL}[mode]
+    _check(lib().medusa_verify_logits(hidden_tree.data_ptr(), w_lm.data_ptr(), logits.data_ptr(), stats.data_ptr(),
+                                      stats.numel() * stats.element_size(), M, d, V, _dtype_code(hidden_tree), code,
+                                      float(temperature), _stream(stream)), "medusa_verify_logits")
+    return logits, stats
+
+
+def medusa_accept_fused(logits: torch.Tensor, stats: torch.Tensor, tree_tokens: torch.Tensor, tree: MedusaTree,
+                        mode: str = "greedy", temperature: float = 1.0, eps: float = 0.0, delta: float = 0.0, outputs=None,
+                        stream=None):
+    """medusa_accept from the row reductions medusa_verify_logits left in `stats`.  logits [B, T, V]."""
+    B, T, V = logits.shape
+    if T != tree.T:
+        raise MedusaError(f"logits have {T} rows per sequence, the tree has {tree.T}")
+    _dev(logits, "logits", dtype=torch.float32)
+    _dev(stats, "stats")
+    _dev(tree_tokens, "tree_tokens", dtype=torch.int32, shape=(B, T))
+    if outputs is None:
+        i32 = dict(dtype=torch.int32, device=logits.device)
+        outputs = (torch.empty(B, **i32), torch.empty(B, **i32), torch.empty((B, tree.K + 1), **i32),
+                   torch.empty((B, tree.K + 1), **i32), torch.empty(B, **i32))
+    for o, name, shape in zip(outputs, ("accept_len", "best_node", "path_nodes", "accepted_tokens", "next_root"),
+                              ((B,), (B,), (B, tree.K + 1), (B, tree.K + 1), (B,))):
+        _dev(o, name, dtype=torch.int32, shape=shape)
+    code = {"greedy": MEDUSA_GREEDY, "typical": MEDUSA_TYPICAL}[mode]
+    _check(lib().medusa_accept_fused(logits.data_ptr(), stats.data_ptr(), tree_tokens.data_ptr(), tree.handle, B, V, code,
+                                     float(temperature), float(eps), float(delta), *(o.data_ptr() for o in outputs),
+                                     _stream(stream)), "medusa_accept_fused")
     return outputs
 
 

@@ -24,21 +24,6 @@ constexpr int kMaxBatch = 4096;
 // Shared by all calls on a GPU: calls that overlap on different streams would race.
 __device__ unsigned int g_accept_ticket[kMaxBatch];
 
-struct RowPart {       // one per (row, chunk)
-  uint64_t key;        // rank_key of the chunk's best (logit, id)
-  float m, S, U;
-  float pad;
-};
-
-__device__ __forceinline__ void stats_merge(float& m, float& S, float& U, float m2, float S2, float U2) {
-  const float mn = fmaxf(m, m2);
-  const float c1 = S > 0.f ? __builtin_amdgcn_exp2f(m - mn) : 0.f, d1 = S > 0.f ? m - mn : 0.f;
-  const float c2 = S2 > 0.f ? __builtin_amdgcn_exp2f(m2 - mn) : 0.f, d2 = S2 > 0.f ? m2 - mn : 0.f;
-  U = c1 * (U + d1 * S) + c2 * (U2 + d2 * S2);
-  S = c1 * S + c2 * S2;
-  m = mn;
-}
-
 template <bool TYPICAL>
 __device__ __forceinline__ void row_stats(const float* __restrict__ logits, int V, float inv_temp,
                                           RowPart* __restrict__ part, int chunks) {
@@ -486,6 +471,99 @@ extern "C" int medusa_accept_sampled(const float* logits, const int32_t* tree_to
   hipLaunchKernelGGL(accept_sampled_kernel, dim3(chunks, B * T), dim3(256), 0, (hipStream_t)stream_, logits, tree_tokens,
                      tree->dev, (RowPart*)workspace, uniforms, V, 1.0f / temperature, accept_len, best_node, path_nodes,
                      accepted_tokens, next_token);
+  MEDUSA_LAUNCH_CHECK();
+  return MEDUSA_OK;
+}
+
+namespace {
+// Acceptance from the row reductions a vocabulary-projection kernel left behind (medusa_verify_logits):
+// grid (B*T), 256 threads.  A workgroup merges the n_parts partials of its row -- a few KB instead of the
+// row's V logits --, publishes the result and takes a ticket; the last workgroup of a sequence runs
+// the same final step as the scanning kernel.  A header mismatch (statistics produced for another
+// mode or temperature) is reported as accept_len = -1.
+template <bool TYPICAL>
+__global__ __launch_bounds__(256) void accept_fused_kernel(const float* __restrict__ logits, const int32_t* __restrict__ tree_tokens,
+                                                           const TreeTables* __restrict__ tree, const FusedStatsHeader* __restrict__ hdr,
+                                                           int V, float k2_want, float eps, float delta,
+                                                           int32_t* __restrict__ accept_len, int32_t* __restrict__ best_node,
+                                                           int32_t* __restrict__ path_nodes, int32_t* __restrict__ accepted_tokens,
+                                                           int32_t* __restrict__ next_root) {
+  __shared__ uint64_t s_key[4];
+  __shared__ float s_m[4], s_S[4], s_U[4];
+  const int T = tree->T;
+  const int row = blockIdx.x, b = row / T;
+  const int n_parts = hdr->n_parts;
+  const bool ok = hdr->rows == (int)gridDim.x && n_parts >= 1 && n_parts <= 2 * ceil_div(V, 256) && (!TYPICAL || (hdr->typical == 1 && hdr->k2 == k2_want));
+  RowPart* merged = (RowPart*)(hdr + 1);
+  const RowPart* part = merged + (size_t)gridDim.x * kFusedMergedSlots + (size_t)row * (ok ? n_parts : 0);
+  uint64_t key = 0;
+  float m = -INFINITY, S = 0.f, U = 0.f;
+  if (ok) {
+    for (int i = threadIdx.x; i < n_parts; i += 256) {
+      const RowPart p = part[i];
+      key = p.key > key ? p.key : key;
+      if (TYPICAL) stats_merge(m, S, U, p.m, p.S, p.U);
+    }
+  }
+  key = wave_max_u64(key);
+  if (TYPICAL) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float m2 = __shfl_xor(m, o, kWave), S2 = __shfl_xor(S, o, kWave), U2 = __shfl_xor(U, o, kWave);
+      stats_merge(m, S, U, m2, S2, U2);
+    }
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) {
+    s_key[wave] = key;
+    s_m[wave] = m;
+    s_S[wave] = S;
+    s_U[wave] = U;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) {
+      key = s_key[w] > key ? s_key[w] : key;
+      if (TYPICAL) stats_merge(m, S, U, s_m[w], s_S[w], s_U[w]);
+    }
+    RowPart* p = merged + (size_t)row * kFusedMergedSlots;
+    store_agent(&p->key, key);
+    store_agent(&p->m, m);
+    store_agent(&p->S, S);
+    store_agent(&p->U, U);
+  }
+  if (!last_workgroup_of(&g_accept_ticket[b], (unsigned)T)) return;
+  if (!ok) {
+    if (threadIdx.x == 0) accept_len[b] = -1;
+    return;
+  }
+  accept_finalize<TYPICAL>(b, logits, tree_tokens, tree, merged, V, 1, k2_want * 0.6931471805599453f, eps, delta, accept_len, best_node,
+                           path_nodes, accepted_tokens, next_root);
+}
+}  // namespace
+
+extern "C" int medusa_accept_fused(const float* logits, const void* stats, const int32_t* tree_tokens, const medusa_tree_t* tree,
+                                   int B, int V, int mode, float temperature, float eps, float delta, int32_t* accept_len,
+                                   int32_t* best_node, int32_t* path_nodes, int32_t* accepted_tokens, int32_t* next_root,
+                                   medusa_stream_t stream_) {
+  if (!logits || !stats || !tree_tokens || !tree || !accept_len || !best_node || !path_nodes || !accepted_tokens || !next_root)
+    return MEDUSA_EINVAL;
+  if (B < 1 || V < 1) return MEDUSA_EINVAL;
+  if (mode != MEDUSA_GREEDY && mode != MEDUSA_TYPICAL) return MEDUSA_EINVAL;
+  if (mode == MEDUSA_TYPICAL && !(temperature > 0.f)) return MEDUSA_EINVAL;
+  if (B > kMaxBatch || ((uintptr_t)stats & 255) != 0) return MEDUSA_EUNSUPPORTED;
+  const int T = tree->host.T;
+  if (!tree->dev) return MEDUSA_EHIP;
+  static_assert(kFusedMergedSlots == kAccMaxChunks, "the final step reads the merged rows with the scan kernel's stride");
+  hipStream_t stream = (hipStream_t)stream_;
+  const FusedStatsHeader* hdr = (const FusedStatsHeader*)stats;
+  const float k2 = mode == MEDUSA_TYPICAL ? 1.4426950408889634f / temperature : 0.f;
+  if (mode == MEDUSA_TYPICAL)
+    hipLaunchKernelGGL(accept_fused_kernel<true>, dim3(B * T), dim3(256), 0, stream, logits, tree_tokens, tree->dev, hdr, V, k2, eps,
+                       delta, accept_len, best_node, path_nodes, accepted_tokens, next_root);
+  else
+    hipLaunchKernelGGL(accept_fused_kernel<false>, dim3(B * T), dim3(256), 0, stream, logits, tree_tokens, tree->dev, hdr, V, k2, eps,
+                       delta, accept_len, best_node, path_nodes, accepted_tokens, next_root);
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;
 }

@@ -189,3 +189,31 @@ __device__ __forceinline__ uint64_t rank_key(float v, uint32_t id) {
 __device__ __forceinline__ uint32_t rank_key_id(uint64_t key) { return 0xffffffffu - (uint32_t)key; }
 
 __host__ __device__ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Reduction of a slice of one logits row (medusa_accept, Sec. 2.3.1): the arg-max as a rank_key and,
+// for the soft-max of typical / sampled acceptance, in log2 units (t = logit * log2(e) / temperature):
+// m = max t, S = sum 2^(t - m), U = sum (t - m) 2^(t - m).  Slices merge with stats_merge().
+struct RowPart {
+  uint64_t key;
+  float m, S, U;
+  float pad;
+};
+__device__ __forceinline__ void stats_merge(float& m, float& S, float& U, float m2, float S2, float U2) {
+  const float mn = fmaxf(m, m2);
+  const float c1 = S > 0.f ? __builtin_amdgcn_exp2f(m - mn) : 0.f, d1 = S > 0.f ? m - mn : 0.f;
+  const float c2 = S2 > 0.f ? __builtin_amdgcn_exp2f(m2 - mn) : 0.f, d2 = S2 > 0.f ? m2 - mn : 0.f;
+  U = c1 * (U + d1 * S) + c2 * (U2 + d2 * S2);
+  S = c1 * S + c2 * S2;
+  m = mn;
+}
+// Row reductions a vocabulary-projection kernel leaves behind for medusa_accept_fused: a header, one
+// merged RowPart slot group per row (filled by the acceptance kernel), then n_parts RowParts per row.
+struct FusedStatsHeader {
+  int32_t n_parts;      // partials per row the producer wrote
+  int32_t typical;      // 1: m, S, U are valid (the producer ran with a temperature); 0: keys only
+  float k2;             // log2(e) / temperature the producer used
+  int32_t rows;
+  int32_t pad[60];
+};
+static_assert(sizeof(FusedStatsHeader) == 256, "header is one 256-byte block");
+constexpr int kFusedMergedSlots = 8;                       // slots per row in the merged area (= the scan kernel's chunk bound)

@@ -33,6 +33,11 @@ struct GemmArgs {
   int ksplit;          // skinny MFMA kernel: workgroups that share one output tile, each reducing 1/ksplit of d
   void* ws;            // their fp32 partial tiles (ksplit > 1)
   int vec_epilogue;    // large-M kernel: 8-column runs of the output (and of `hidden`) are contiguous and 16-byte aligned
+  // EPI_LOGITS, large-M kernel only: when `stats` is set every wavefront also reduces its 16-row x 128-column
+  // pieces of the logits to RowParts (arg-max key; soft-max statistics when stats_k2 > 0) for medusa_accept_fused
+  RowPart* stats;      // [M][stats_parts]
+  int stats_parts;     // = 2 * column tiles
+  float stats_k2;      // log2(e) / temperature, or 0: keys only
 };
 
 // Element offset of X(m, k, 0) and of column j relative to it.  Chunks of up to x_dh consecutive

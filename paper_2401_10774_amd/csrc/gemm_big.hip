@@ -43,7 +43,7 @@ __device__ unsigned int g_big_ticket[kMaxBigSplitTiles];
 // order (so the result does not depend on which one that is) and runs the epilogue.  For long
 // reductions into few tiles (the down projection of a batch of trees): 96 tiles of 192 x 256 over
 // d = 11008 keep 96 CUs busy for 240 us unsplit.
-template <int MT, int NT, int EPI, bool SPLIT = false>
+template <int MT, int NT, int EPI, bool SPLIT = false, bool STATS = false>
 __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m_tiles, int n_tiles) {
   constexpr int BM = 32 * MT, BN = 32 * NT, ROWS = BM + BN;
   constexpr int LPT = ROWS / 32;                      // 16-byte chunks per thread and stage
@@ -65,6 +65,14 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
   if (n_tile >= n_tiles) return;                      // whole workgroup leaves before any barrier
   const int m0 = (slot - nt_local * m_tiles) * BM, n0 = n_tile * BN;
   const int k = blockIdx.y;
+  if (STATS && blockIdx.x == 0 && blockIdx.y == 0 && tid == 0) {
+    // what the acceptance kernel needs to know about the row reductions this launch leaves behind
+    FusedStatsHeader* h = (FusedStatsHeader*)((unsigned char*)a.stats - (size_t)a.M * kFusedMergedSlots * sizeof(RowPart) - sizeof(FusedStatsHeader));
+    h->n_parts = a.stats_parts;
+    h->typical = a.stats_k2 > 0.f ? 1 : 0;
+    h->k2 = a.stats_k2;
+    h->rows = a.M;
+  }
   const unsigned char* Xb = (const unsigned char*)a.X;
   const unsigned char* Wb = (const unsigned char*)a.W + (size_t)k * a.N * a.d * 2;
 
@@ -235,6 +243,66 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
         ep[(4 * q4 + r) * EP_PITCH + j * 16 + i16] = SW ? silu_fast(acc[t][2 * j][r]) * acc[t][2 * j + 1][r] : acc[t][j][r];
     const int m = m0 + (wm * MT + t) * 16 + er;
     const size_t row_off = m >= a.M ? 0 : (SW && a.y_dh == 0 ? (size_t)m * n_cols : out_row_offset<kHeadMajor<EPI>>(a, m, k));
+    if (STATS) {
+      // Row reductions for the acceptance step (Sec. 2.3.1), taken from the tile while it is in LDS so
+      // that acceptance does not read the logits again: this lane's 32 values of row m (8 consecutive
+      // columns in each of four 32-column runs), then the four lanes of the row.  A lane's columns
+      // ascend and the key orders equal values by column, so the arg-max is the lowest column.
+      uint64_t key = 0;
+      float sm = -INFINITY, sS = 0.f, sU = 0.f;
+      const float k2 = a.stats_k2;
+      if (m < a.M) {
+#pragma unroll
+        for (int c = 0; c < NTO / 2; ++c) {
+          const floatx4_t v0 = *(const floatx4_t*)(ep + er * EP_PITCH + c * 32 + ec);
+          const floatx4_t v1 = *(const floatx4_t*)(ep + er * EP_PITCH + c * 32 + ec + 4);
+          const float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+          const int n = n_base + c * 32 + ec;
+          float bm = -INFINITY;
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (n + e < n_cols) {
+              const uint64_t ke = rank_key(v[e], (uint32_t)(n + e));
+              key = ke > key ? ke : key;
+              bm = fmaxf(bm, v[e] * k2);
+            }
+          if (k2 > 0.f && bm > -INFINITY) {
+            if (bm > sm) {                               // one rescale of the running sums per run of eight
+              const float cf = sS > 0.f ? __builtin_amdgcn_exp2f(sm - bm) : 0.f;
+              sU = sS > 0.f ? cf * (sU + (sm - bm) * sS) : 0.f;
+              sS = cf * sS;
+              sm = bm;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (n + e < n_cols) {
+                const float dlt = v[e] * k2 - sm, p = __builtin_amdgcn_exp2f(dlt);
+                sS += p;
+                sU = fmaf(dlt, p, sU);
+              }
+          }
+        }
+      }
+      // the four lanes of a row are a quad: two exchange steps
+#pragma unroll
+      for (int step = 0; step < 2; ++step) {
+        const uint32_t klo = step == 0 ? dpp_u32<kDppQuadSwap1>((uint32_t)key) : dpp_u32<kDppQuadSwap2>((uint32_t)key);
+        const uint32_t khi = step == 0 ? dpp_u32<kDppQuadSwap1>((uint32_t)(key >> 32)) : dpp_u32<kDppQuadSwap2>((uint32_t)(key >> 32));
+        const uint64_t ko = ((uint64_t)khi << 32) | klo;
+        key = ko > key ? ko : key;
+        const float m2 = step == 0 ? dpp_f32<kDppQuadSwap1>(sm) : dpp_f32<kDppQuadSwap2>(sm);
+        const float S2 = step == 0 ? dpp_f32<kDppQuadSwap1>(sS) : dpp_f32<kDppQuadSwap2>(sS);
+        const float U2 = step == 0 ? dpp_f32<kDppQuadSwap1>(sU) : dpp_f32<kDppQuadSwap2>(sU);
+        stats_merge(sm, sS, sU, m2, S2, U2);
+      }
+      if ((lane & 3) == 0 && m < a.M) {
+        RowPart* p = a.stats + (size_t)m * a.stats_parts + (n_tile * 2 + wn);
+        p->key = key;
+        p->m = sm;
+        p->S = sS;
+        p->U = sU;
+      }
+    }
 #pragma unroll
     for (int c = 0; c < NTO / 2; ++c) {
       const floatx4_t v0 = *(const floatx4_t*)(ep + er * EP_PITCH + c * 32 + ec);
@@ -303,7 +371,10 @@ int launch(const GemmArgs& a_in, bool tall, hipStream_t stream) {
   const int gx = 8 * ceil_div(n_tiles, 8) * m_tiles;
   const int ksplit = kCanSplit && a.ws && a.ksplit > 1 && (long)gx * a.K <= kMaxBigSplitTiles ? a.ksplit : 1;
   const dim3 grid(gx, a.K, ksplit), block(256);
-  if (ksplit > 1) {
+  if (EPI == EPI_LOGITS && a.stats != nullptr) {          // (its own instantiation: the plain kernel's code stays as it is)
+    if (tall) hipLaunchKernelGGL((gemm_big_bf16_kernel<6, 8, EPI, false, EPI == EPI_LOGITS>), grid, block, 0, stream, a, m_tiles, n_tiles);
+    else hipLaunchKernelGGL((gemm_big_bf16_kernel<4, 8, EPI, false, EPI == EPI_LOGITS>), grid, block, 0, stream, a, m_tiles, n_tiles);
+  } else if (ksplit > 1) {
     if (tall) hipLaunchKernelGGL((gemm_big_bf16_kernel<6, 8, EPI, kCanSplit>), grid, block, 0, stream, a, m_tiles, n_tiles);
     else hipLaunchKernelGGL((gemm_big_bf16_kernel<4, 8, EPI, kCanSplit>), grid, block, 0, stream, a, m_tiles, n_tiles);
   } else {

@@ -1047,6 +1047,46 @@ extern "C" int medusa_heads_timed(const void* hidden, const void* w1, const void
   return heads_impl(hidden, w1, w2, resid, logits, M, d, V, K, dtype, stream_, ev);
 }
 
+// The original model's logits at the tree tokens with the acceptance step's row reductions taken in the
+// GEMM epilogue (Sec. 2.3.1 needs, per row, the arg-max and -- for typical acceptance -- the soft-max
+// statistics; taken from the tile they cost no second pass over the B*T*V logits).
+extern "C" size_t medusa_verify_stats_bytes(int M, int V) {
+  if (M < 1 || V < 1) return 0;
+  const size_t parts = 2 * (size_t)ceil_div(V, 256);
+  return sizeof(FusedStatsHeader) + (size_t)M * kFusedMergedSlots * sizeof(RowPart) + (size_t)M * parts * sizeof(RowPart);
+}
+
+extern "C" int medusa_verify_fused_available(int M, int d, int V, int dtype) {
+  if (M < 1 || d < 1 || V < 1 || dtype != MEDUSA_BF16 || d % 64 != 0 || M > 4096 || d > 16384) return 0;
+  const bool wide_offsets = (size_t)V * d >= ((size_t)1 << 31) || (size_t)M * d + (size_t)2 * d >= ((size_t)1 << 31);
+  return plan_gemm(M, V, d, 1, false, wide_offsets).kind == GemmPlan::BIG ? 1 : 0;
+}
+
+extern "C" int medusa_verify_logits(const void* hidden_tree, const void* w_lm, float* logits, void* stats, size_t stats_bytes,
+                                    int M, int d, int V, int dtype, int mode, float temperature, medusa_stream_t stream_) {
+  if (!hidden_tree || !w_lm || !logits || !stats) return MEDUSA_EINVAL;
+  if (M < 1 || d < 1 || V < 1) return MEDUSA_EINVAL;
+  if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;
+  if (mode != MEDUSA_GREEDY && mode != MEDUSA_TYPICAL) return MEDUSA_EINVAL;
+  if (mode == MEDUSA_TYPICAL && !(temperature > 0.f)) return MEDUSA_EINVAL;
+  if (!medusa_verify_fused_available(M, d, V, dtype)) return MEDUSA_EUNSUPPORTED;
+  if (stats_bytes < medusa_verify_stats_bytes(M, V) || ((uintptr_t)stats & 255) != 0) return MEDUSA_EWORKSPACE;
+  GemmArgs a = {};
+  a.d = d;
+  a.M = M;
+  a.K = 1;
+  a.hidden = hidden_tree;
+  a.X = hidden_tree;
+  a.xs_m = d;
+  a.W = w_lm;
+  a.out = logits;
+  a.N = V;
+  a.stats = (RowPart*)((unsigned char*)stats + sizeof(FusedStatsHeader) + (size_t)M * kFusedMergedSlots * sizeof(RowPart));
+  a.stats_parts = 2 * ceil_div(V, 256);
+  a.stats_k2 = mode == MEDUSA_TYPICAL ? 1.4426950408889634f / temperature : 0.f;
+  return launch_gemm<EPI_LOGITS>(a, (medusa_dtype_t)dtype, (hipStream_t)stream_);
+}
+
 // Backbone linear layer on the tree tokens (App. G, operator table, parallel-decoding rows).
 extern "C" size_t tree_linear_workspace_bytes(int B, int T, int d_in, int d_out, int dtype) {
   if (dtype != MEDUSA_BF16 || B < 1 || T < 1 || d_in < 64 || d_out < 1) return 0;

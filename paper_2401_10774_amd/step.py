@@ -23,7 +23,7 @@ class VerificationStep:
     """
 
     def __init__(self, dev: Dict[str, torch.Tensor], tree: B_.MedusaTree, mode: str = "greedy",
-                 temperature: float = 1.0, eps: float = 0.0, delta: float = 0.0):
+                 temperature: float = 1.0, eps: float = 0.0, delta: float = 0.0, fused_accept: bool = False):
         self.t = dev
         self.tree = tree
         self.mode, self.temperature, self.eps, self.delta = mode, temperature, eps, delta
@@ -50,6 +50,12 @@ class VerificationStep:
         self.ws_topk = B_._scratch(B_.lib().medusa_topk_tree_workspace_bytes(B, tree.K), device)
         self.ws_attn = B_._scratch(B_.tree_attention_workspace_bytes(B, self.Hq, self.Hkv, T, self.D, self.Lcap), device)
         self.ws_accept = B_._scratch(B_.medusa_accept_workspace_bytes(B, T, V), device)
+        # fused_accept: where the shape has it (many tree rows), the LM-head kernel also leaves the acceptance
+        # step's row reductions behind (medusa_verify_logits / medusa_accept_fused) instead of medusa_heads +
+        # medusa_accept.  Off by default: measured on MI355X the reductions cost the GEMM's epilogue more
+        # (B = 16: +33 us, B = 4: +18 us) than the lighter acceptance kernel gives back (-16 us, -7 us).
+        self.fused = bool(fused_accept) and bool(B_.lib().medusa_verify_fused_available(B * T, self.d, V, B_._dtype_code(h)))
+        self.ws_stats = B_._scratch(B_.lib().medusa_verify_stats_bytes(B * T, V) if self.fused else 0, device)
         self.w_lm3 = dev["w_lm"].view(1, V, self.d)
         self.hidden_rows = dev["hidden_tree"].view(B * T, self.d)
         self.prefix_len0 = dev["prefix_len"].clone()
@@ -109,13 +115,21 @@ class VerificationStep:
             ("tree_attention", L.tree_attention, (p(t["q"]), p(kt), p(vt), p(kc), p(vc), p(t["prefix_len"]),
                                                   tree.handle, p(self.attn_out), B, self.Hq, self.Hkv, self.D,
                                                   self.Lcap, self.scale, code, p(self.ws_attn), nbytes(self.ws_attn))),
+            ("medusa_verify_logits", L.medusa_verify_logits,
+             (p(self.hidden_rows), p(w_lm3), p(self.verify_logits), p(self.ws_stats), nbytes(self.ws_stats), B * T, d, V, code,
+              mode, self.temperature)) if self.fused else
             ("medusa_heads", L.medusa_heads, (p(self.hidden_rows), None, p(w_lm3), None, p(self.verify_logits),
                                               B * T, d, V, 1, code)),
         ]
+        accept_scan = ("medusa_accept", L.medusa_accept, (p(self.verify_logits), p(self.tree_tokens), tree.handle, B, V, mode,
+                                                          self.temperature, self.eps, self.delta, p(a[0]), p(a[1]), p(a[2]),
+                                                          p(a[3]), p(a[4]), p(self.ws_accept), nbytes(self.ws_accept)))
+        accept_fused = ("medusa_accept_fused", L.medusa_accept_fused,
+                        (p(self.verify_logits), p(self.ws_stats), p(self.tree_tokens), tree.handle, B, V, mode, self.temperature,
+                         self.eps, self.delta, p(a[0]), p(a[1]), p(a[2]), p(a[3]), p(a[4])))
+        self._accept_scan = accept_scan
         post = [
-            ("medusa_accept", L.medusa_accept, (p(self.verify_logits), p(self.tree_tokens), tree.handle, B, V, mode,
-                                                self.temperature, self.eps, self.delta, p(a[0]), p(a[1]), p(a[2]),
-                                                p(a[3]), p(a[4]), p(self.ws_accept), nbytes(self.ws_accept))),
+            accept_fused if self.fused else accept_scan,
             ("kv_commit", L.kv_commit, (p(t["k_cache"]), p(t["v_cache"]), p(t["k_tree"]), p(t["v_tree"]), p(a[2]),
                                         int(a[2].shape[1]), p(a[0]), p(t["prefix_len"]),
                                         None if self.next_prefix_len is None else p(self.next_prefix_len),
@@ -141,7 +155,9 @@ class VerificationStep:
                 B_._check(rc, name)
         if plant is not None:
             plant(self.verify_logits.view(self.B, self.T, self.V), self.tree_tokens)
-        for name, fn, args in post:
+        for i, (name, fn, args) in enumerate(post):
+            if i == 0 and plant is not None and self.fused:
+                name, fn, args = self._accept_scan     # edited logits: the GEMM's row reductions no longer describe them
             rc = fn(*args, stream)
             if rc != 0:
                 B_._check(rc, name)

@@ -51,7 +51,7 @@ def topk_gap(logits_row, s):
     return float(np.min(v[:-1] - v[1:])) if v.size > 1 else np.inf
 
 
-def run_config(name, nl=None, plant_seed=None, sparse=False):
+def run_config(name, nl=None, plant_seed=None, sparse=False, fused_accept=False):
     cfg = get_config(name)
     dtype = cfg.dtype
     x = make_step_inputs(cfg, nl=nl)
@@ -64,7 +64,9 @@ def run_config(name, nl=None, plant_seed=None, sparse=False):
         assert gt.T == cfg.T and gt.K == cfg.K and np.array_equal(gt.parent, ot.parent)
     else:
         gt, ot = M.MedusaTree(branching=cfg.branching), O.tree_cartesian(cfg.branching)
-    step = VerificationStep({k: to_dev(v) for k, v in x.items()}, gt, cfg.accept, cfg.temperature, cfg.eps, cfg.delta)
+    step = VerificationStep({k: to_dev(v) for k, v in x.items()}, gt, cfg.accept, cfg.temperature, cfg.eps, cfg.delta,
+                            fused_accept=fused_accept)
+    assert step.fused == fused_accept
     plant_dev = plant_host = None
     if plant_seed is not None:
         plant_dev, plant_host, picks = make_plant(cfg, ot, plant_seed)
@@ -168,6 +170,11 @@ def test_c4_13b_batch4_ragged():
 
 def test_c5_gqa_batch16_typical():
     a = run_config("C5", nl=8)
+    assert len(set(a.tolist())) >= 2
+
+
+def test_c5_with_the_acceptance_reductions_fused_into_the_lm_head_gemm():
+    a = run_config("C5", nl=2, fused_accept=True)
     assert len(set(a.tolist())) >= 2
 
 
