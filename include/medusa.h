@@ -22,10 +22,12 @@
  *     device arrays (e.g. prefix_len) cannot be checked on the host: the kernels clamp
  *     every index they derive from device data, so bad contents give wrong rows, never an
  *     out-of-bounds access.
- *   - medusa_topk_tree, medusa_accept and kv_commit each keep a few ticket counters in device
- *     memory of the library (used to elect the last workgroup of a launch; they return to zero
- *     when a launch completes).  Calls of the SAME entry point must therefore not overlap on one
- *     GPU: issue them on one stream, or order the streams.  Batch size B <= 4096 for these calls.
+ *   - medusa_topk_tree, the medusa_accept family, kv_commit and the split reductions of tree_linear
+ *     elect the last workgroup of a launch with ticket counters in device memory of the library (they
+ *     return to zero when a launch completes).  The library keeps 16 sets of them and gives every
+ *     stream it sees a set of its own, in order of first use: calls on different streams may overlap;
+ *     from the 17th distinct stream of a process on, streams share the last set and calls of the same
+ *     entry point on those must not overlap.  Batch size B <= 4096 for these calls.
  *   - dtype is the storage type of activations, weights and KV: MEDUSA_F32 or
  *     MEDUSA_BF16.  Accumulation is always fp32; logits are always fp32.
  *   - Ties in arg-max / top-k: larger value first, then lower token id.  NaN logits are
@@ -326,7 +328,7 @@ int medusa_carry_over(const void* hidden_tree, const float* verify_logits, const
  *        partial tiles when the reduction over d_in is split across workgroups, which the library
  *        does for few tree tokens and small d_out so that the whole chip streams the weights; with
  *        NULL or too small a workspace the call still works, unsplit and slower.  Calls that use
- *        the workspace must not overlap on one GPU (they share a ticket table).
+ *        the workspace must not overlap on one GPU (the workspace is theirs alone while they run).
  * Limits: B*T <= 4096; d_in (and d_in/x_heads) a multiple of 8 (bf16: of 64); d_out a multiple
  * of y_heads.  All pointers are device pointers; returns MEDUSA_EINVAL / MEDUSA_EUNSUPPORTED
  * without launching anything when a limit is violated.

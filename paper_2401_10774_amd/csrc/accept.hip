@@ -20,9 +20,8 @@ namespace {
 constexpr int kAccMaxChunks = 8;   // upper bound of workgroups per logits row (sizes the partial buffer)
 constexpr int kMaxBatch = 4096;
 
-// Ticket counters of the "last workgroup of a sequence" election; zero between launches.
-// Shared by all calls on a GPU: calls that overlap on different streams would race.
-__device__ unsigned int g_accept_ticket[kMaxBatch];
+// Ticket counters of the "last workgroup of a sequence" election, per stream slot; zero between launches.
+__device__ unsigned int g_accept_ticket[kTicketSlots][kMaxBatch];
 
 template <bool TYPICAL>
 __device__ __forceinline__ void row_stats(const float* __restrict__ logits, int V, float inv_temp,
@@ -261,7 +260,7 @@ __device__ __forceinline__ void accept_finalize(int b, const float* __restrict__
 // grid (chunks, B*T), 256 threads.
 template <bool TYPICAL>
 __global__ __launch_bounds__(256) void accept_kernel(const float* __restrict__ logits, const int32_t* __restrict__ tree_tokens,
-                                                     const TreeTables* __restrict__ tree, RowPart* __restrict__ part, int V,
+                                                     const TreeTables* __restrict__ tree, RowPart* __restrict__ part, int V, int slot,
                                                      float inv_temp, float eps, float delta, int32_t* __restrict__ accept_len,
                                                      int32_t* __restrict__ best_node, int32_t* __restrict__ path_nodes,
                                                      int32_t* __restrict__ accepted_tokens, int32_t* __restrict__ next_root) {
@@ -269,7 +268,7 @@ __global__ __launch_bounds__(256) void accept_kernel(const float* __restrict__ l
   row_stats<TYPICAL>(logits, V, inv_temp, part, chunks);
   const int T = tree->T;
   const int b = blockIdx.y / T;
-  if (!last_workgroup_of(&g_accept_ticket[b], (unsigned)(chunks * T))) return;
+  if (!last_workgroup_of(&g_accept_ticket[slot][b], (unsigned)(chunks * T))) return;
   accept_finalize<TYPICAL>(b, logits, tree_tokens, tree, part, V, chunks, inv_temp, eps, delta, accept_len, best_node, path_nodes,
                            accepted_tokens, next_root);
 }
@@ -438,7 +437,7 @@ __device__ __forceinline__ void accept_finalize_sampled(int b, const float* __re
 // grid (chunks, B*T), 256 threads.
 __global__ __launch_bounds__(256) void accept_sampled_kernel(const float* __restrict__ logits, const int32_t* __restrict__ tree_tokens,
                                                              const TreeTables* __restrict__ tree, RowPart* __restrict__ part,
-                                                             const float* __restrict__ uniforms, int V, float inv_temp,
+                                                             const float* __restrict__ uniforms, int V, int slot, float inv_temp,
                                                              int32_t* __restrict__ accept_len, int32_t* __restrict__ best_node,
                                                              int32_t* __restrict__ path_nodes, int32_t* __restrict__ accepted_tokens,
                                                              int32_t* __restrict__ next_token) {
@@ -446,7 +445,7 @@ __global__ __launch_bounds__(256) void accept_sampled_kernel(const float* __rest
   row_stats<true>(logits, V, inv_temp, part, chunks);
   const int T = tree->T;
   const int b = blockIdx.y / T;
-  if (!last_workgroup_of(&g_accept_ticket[b], (unsigned)(chunks * T))) return;
+  if (!last_workgroup_of(&g_accept_ticket[slot][b], (unsigned)(chunks * T))) return;
   accept_finalize_sampled(b, logits, tree_tokens, tree, part, uniforms, V, chunks, inv_temp, accept_len, best_node, path_nodes,
                           accepted_tokens, next_token);
 }
@@ -469,7 +468,7 @@ extern "C" int medusa_accept_sampled(const float* logits, const int32_t* tree_to
   int chunks = 260 / (B * T);
   chunks = chunks < 1 ? 1 : (chunks > kAccMaxChunks ? kAccMaxChunks : chunks);
   hipLaunchKernelGGL(accept_sampled_kernel, dim3(chunks, B * T), dim3(256), 0, (hipStream_t)stream_, logits, tree_tokens,
-                     tree->dev, (RowPart*)workspace, uniforms, V, 1.0f / temperature, accept_len, best_node, path_nodes,
+                     tree->dev, (RowPart*)workspace, uniforms, V, ticket_slot((hipStream_t)stream_), 1.0f / temperature, accept_len, best_node, path_nodes,
                      accepted_tokens, next_token);
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;
@@ -484,7 +483,7 @@ namespace {
 template <bool TYPICAL>
 __global__ __launch_bounds__(256) void accept_fused_kernel(const float* __restrict__ logits, const int32_t* __restrict__ tree_tokens,
                                                            const TreeTables* __restrict__ tree, const FusedStatsHeader* __restrict__ hdr,
-                                                           int V, float k2_want, float eps, float delta,
+                                                           int V, int slot, float k2_want, float eps, float delta,
                                                            int32_t* __restrict__ accept_len, int32_t* __restrict__ best_node,
                                                            int32_t* __restrict__ path_nodes, int32_t* __restrict__ accepted_tokens,
                                                            int32_t* __restrict__ next_root) {
@@ -532,7 +531,7 @@ __global__ __launch_bounds__(256) void accept_fused_kernel(const float* __restri
     store_agent(&p->S, S);
     store_agent(&p->U, U);
   }
-  if (!last_workgroup_of(&g_accept_ticket[b], (unsigned)T)) return;
+  if (!last_workgroup_of(&g_accept_ticket[slot][b], (unsigned)T)) return;
   if (!ok) {
     if (threadIdx.x == 0) accept_len[b] = -1;
     return;
@@ -559,10 +558,10 @@ extern "C" int medusa_accept_fused(const float* logits, const void* stats, const
   const FusedStatsHeader* hdr = (const FusedStatsHeader*)stats;
   const float k2 = mode == MEDUSA_TYPICAL ? 1.4426950408889634f / temperature : 0.f;
   if (mode == MEDUSA_TYPICAL)
-    hipLaunchKernelGGL(accept_fused_kernel<true>, dim3(B * T), dim3(256), 0, stream, logits, tree_tokens, tree->dev, hdr, V, k2, eps,
+    hipLaunchKernelGGL(accept_fused_kernel<true>, dim3(B * T), dim3(256), 0, stream, logits, tree_tokens, tree->dev, hdr, V, ticket_slot(stream), k2, eps,
                        delta, accept_len, best_node, path_nodes, accepted_tokens, next_root);
   else
-    hipLaunchKernelGGL(accept_fused_kernel<false>, dim3(B * T), dim3(256), 0, stream, logits, tree_tokens, tree->dev, hdr, V, k2, eps,
+    hipLaunchKernelGGL(accept_fused_kernel<false>, dim3(B * T), dim3(256), 0, stream, logits, tree_tokens, tree->dev, hdr, V, ticket_slot(stream), k2, eps,
                        delta, accept_len, best_node, path_nodes, accepted_tokens, next_root);
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;
@@ -598,10 +597,10 @@ extern "C" int medusa_accept(const float* logits, const int32_t* tree_tokens, co
   const dim3 grid(chunks, B * T);
   const float inv_temp = mode == MEDUSA_TYPICAL ? 1.0f / temperature : 1.0f;
   if (mode == MEDUSA_TYPICAL)
-    hipLaunchKernelGGL(accept_kernel<true>, grid, dim3(256), 0, stream, logits, tree_tokens, tree->dev, part, V, inv_temp,
+    hipLaunchKernelGGL(accept_kernel<true>, grid, dim3(256), 0, stream, logits, tree_tokens, tree->dev, part, V, ticket_slot(stream), inv_temp,
                        eps, delta, accept_len, best_node, path_nodes, accepted_tokens, next_root);
   else
-    hipLaunchKernelGGL(accept_kernel<false>, grid, dim3(256), 0, stream, logits, tree_tokens, tree->dev, part, V, inv_temp,
+    hipLaunchKernelGGL(accept_kernel<false>, grid, dim3(256), 0, stream, logits, tree_tokens, tree->dev, part, V, ticket_slot(stream), inv_temp,
                        eps, delta, accept_len, best_node, path_nodes, accepted_tokens, next_root);
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;

@@ -128,6 +128,14 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
   return ab > cd ? ab : cd;
 }
 
+// Ticket counters of the elections below live in device arrays of the library, one set per STREAM
+// SLOT: the host maps every stream it sees to a slot (ticket_slot(), first come first served), so calls
+// on different streams use different counters and may overlap; calls on one stream are ordered
+// anyway.  There are kTicketSlots slots per process; streams beyond that share the last one (and must
+// then not overlap among themselves).
+constexpr int kTicketSlots = 16;
+int ticket_slot(hipStream_t stream);
+
 // "Last workgroup of a group" election for single-launch two-phase kernels.  Every workgroup
 // calls it once after it has written its partial results with store_agent(); exactly one call per
 // group of `total` workgroups returns true, and that workgroup may then read all partials of

@@ -32,6 +32,7 @@ struct GemmArgs {
   int rows_per_wg;     // GEMV kernels: weight rows per workgroup (multiple of 8)
   int ksplit;          // skinny MFMA kernel: workgroups that share one output tile, each reducing 1/ksplit of d
   void* ws;            // their fp32 partial tiles (ksplit > 1)
+  int ticket_slot;     // which set of ticket counters a split reduction uses (one per stream, see common.hpp)
   int vec_epilogue;    // large-M kernel: 8-column runs of the output (and of `hidden`) are contiguous and 16-byte aligned
   // EPI_LOGITS, large-M kernel only: when `stats` is set every wavefront also reduces its 16-row x 128-column
   // pieces of the logits to RowParts (arg-max key; soft-max statistics when stats_k2 > 0) for medusa_accept_fused

@@ -33,10 +33,9 @@ __device__ __forceinline__ float silu_fast(float u) {
   return u * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * u));
 }
 
-// Ticket counters of the split reduction (one per output tile and head); zero between launches.
-// Shared by all calls on a GPU: calls that overlap on different streams would race.
+// Ticket counters of the split reduction (one per output tile and head), per stream slot; zero between launches.
 constexpr int kMaxBigSplitTiles = 4096;
-__device__ unsigned int g_big_ticket[kMaxBigSplitTiles];
+__device__ unsigned int g_big_ticket[kTicketSlots][kMaxBigSplitTiles];
 
 // SPLIT: grid.z workgroups share an output tile, each reducing a contiguous 1/grid.z of d; they park
 // their fp32 partial tiles in the workspace and the one that finishes last adds them up in split
@@ -193,7 +192,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_bf16_kernel(GemmArgs a, int m
           const uint64_t v = (uint64_t)__float_as_uint(acc[t][j][2 * rp]) | ((uint64_t)__float_as_uint(acc[t][j][2 * rp + 1]) << 32);
           store_agent(part + (size_t)split * PART + ((t * NT + j) * 2 + rp) * 256 + tid, v);
         }
-    if (!last_workgroup_of(&g_big_ticket[tile], (unsigned int)n_split)) return;
+    if (!last_workgroup_of(&g_big_ticket[a.ticket_slot][tile], (unsigned int)n_split)) return;
     // sum in split order; half a tile of one split is requested at a time (the other half of the
     // register file holds the sums)
 #pragma unroll

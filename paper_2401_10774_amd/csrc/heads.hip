@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256) void gemv_f32_kernel(GemmArgs a) {
   }
 }
 
-__device__ unsigned int g_gemm_ticket[kMaxSplitTiles];
+__device__ unsigned int g_gemm_ticket[kTicketSlots][kMaxSplitTiles];
 
 // Tail shared by the MFMA kernels of this file.  On entry every thread holds, for each of its
 // MT x NT accumulator fragments, rows m0 + (wm*MT + t)*16 + 4*(lane/16)..+3 of column
@@ -180,7 +180,7 @@ __device__ __forceinline__ void finish_tile(const GemmArgs& a, floatx4_t (&acc)[
           const uint64_t v = (uint64_t)__float_as_uint(acc[t][j][2 * rp]) | ((uint64_t)__float_as_uint(acc[t][j][2 * rp + 1]) << 32);
           store_agent(part + (size_t)split * PART + ((t * NT + j) * 2 + rp) * 256 + tid, v);
         }
-    if (!last_workgroup_of(&g_gemm_ticket[tile], (unsigned int)n_split)) return;
+    if (!last_workgroup_of(&g_gemm_ticket[a.ticket_slot][tile], (unsigned int)n_split)) return;
     // Sum in split order.  Every load is a round trip to the memory side of the L2 (where the other
     // workgroups' stores are visible), so as many as the registers hold are issued before the first
     // sum: the whole tile of ZB splits at a time, which is all of them for the usual split counts.
@@ -919,6 +919,7 @@ template <int EPI>
 int launch_gemm(const GemmArgs& a_in, int dtype, hipStream_t stream) {
   GemmArgs a = a_in;
   a.ksplit = 1;
+  a.ticket_slot = ticket_slot(stream);
   a.rows_per_wg = gemv_rows_per_wg(a.N, a.K, dtype == MEDUSA_BF16 ? a.M : 1);
   const int kGemvRowsPerWg = a.rows_per_wg;
   const dim3 block(256);

@@ -9,9 +9,8 @@
 
 namespace {
 
-// Ticket counter of the "last workgroup" election; zero between launches.  Shared by all calls
-// on a GPU: calls that overlap on different streams would race.
-__device__ unsigned int g_commit_ticket;
+// Ticket counter of the "last workgroup" election, per stream slot; zero between launches.
+__device__ unsigned int g_commit_ticket[kTicketSlots];
 
 // grid (NL*B, path_stride), 256 threads.  One workgroup moves one accepted row (path slot) of all KV
 // heads of one (layer, sequence), K and V; workgroups of slots beyond accept_len have nothing to move.
@@ -20,7 +19,7 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(u32x4_t* __restrict__ k_
                                                         const int32_t* __restrict__ path_nodes, int path_stride,
                                                         const int32_t* __restrict__ accept_len,
                                                         const int32_t* prefix_len, int32_t* prefix_len_out, int B,
-                                                        int Hkv, int T, int Lcap, int vec_per_row, int in_place) {
+                                                        int Hkv, int T, int Lcap, int vec_per_row, int in_place, int slot) {
   const int lb = blockIdx.x;                  // l*B + b
   const int j = blockIdx.y;                   // path slot
   const int b = lb % B;
@@ -57,7 +56,7 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(u32x4_t* __restrict__ k_
         if (ok[u]) (which[u] ? v_cache : k_cache)[dst_i[u]] = val[u];
     }
   }
-  if (in_place ? !last_workgroup_of(&g_commit_ticket, gridDim.x * gridDim.y) : (blockIdx.x | blockIdx.y) != 0) return;
+  if (in_place ? !last_workgroup_of(&g_commit_ticket[slot], gridDim.x * gridDim.y) : (blockIdx.x | blockIdx.y) != 0) return;
   for (int bb = threadIdx.x; bb < B; bb += 256) {
     const int aa = min(max(accept_len[bb], 0), path_stride);
     prefix_len_out[bb] = min(max(prefix_len[bb], 0) + aa, Lcap);
@@ -113,7 +112,7 @@ extern "C" int kv_commit(void* k_cache, void* v_cache, const void* k_tree, const
   hipLaunchKernelGGL(kv_commit_kernel, dim3(NL * B, path_stride), dim3(256), 0, stream, (u32x4_t*)k_cache, (u32x4_t*)v_cache,
                      (const u32x4_t*)k_tree, (const u32x4_t*)v_tree, path_nodes, path_stride, accept_len, prefix_len,
                      prefix_len_out ? prefix_len_out : prefix_len, B, Hkv, T, Lcap, (int)(row_bytes / 16),
-                     (int)(!prefix_len_out || prefix_len_out == prefix_len));
+                     (int)(!prefix_len_out || prefix_len_out == prefix_len), ticket_slot(stream));
   MEDUSA_LAUNCH_CHECK();
   return MEDUSA_OK;
 }

@@ -15,9 +15,8 @@ constexpr int kMaxChunks = 16;      // upper bound of workgroups per logits row 
 constexpr int kMaxS = MEDUSA_MAX_TOPK;
 constexpr int kMaxBatch = 4096;
 
-// Ticket counters of the "last workgroup of a sequence" election; zero between launches.
-// Shared by all calls on a GPU: calls that overlap on different streams would race.
-__device__ unsigned int g_topk_ticket[kMaxBatch];
+// Ticket counters of the "last workgroup of a sequence" election, per stream slot; zero between launches.
+__device__ unsigned int g_topk_ticket[kTicketSlots][kMaxBatch];
 
 // Insert key into a descending list of compile-time length S (registers only).
 template <int S>
@@ -56,7 +55,7 @@ __global__ __launch_bounds__(256) void topk_tree_kernel(const float* __restrict_
                                                         uint64_t* __restrict__ part, const TreeTables* __restrict__ tree,
                                                         const int32_t* __restrict__ prefix_len,
                                                         int32_t* __restrict__ topk_ids, int32_t* __restrict__ tree_tokens,
-                                                        int32_t* __restrict__ position_ids, int K) {
+                                                        int32_t* __restrict__ position_ids, int K, int slot) {
   __shared__ uint64_t cand[4][S];
   __shared__ int32_t flat[1 + MEDUSA_MAX_HEADS * kMaxS];
   const int chunks = gridDim.x;                     // (K = tree->K comes as an argument: the row decode below needs it at once)
@@ -110,7 +109,7 @@ __global__ __launch_bounds__(256) void topk_tree_kernel(const float* __restrict_
   }
 
   // ---- the sequence's last workgroup merges the chunk winners and fills the tree ------------
-  if (!last_workgroup_of(&g_topk_ticket[b], (unsigned)(chunks * (K + 1)))) return;
+  if (!last_workgroup_of(&g_topk_ticket[slot][b], (unsigned)(chunks * (K + 1)))) return;
   // Everything needed from memory is requested before the first use: the tree-table entries of this
   // thread's node, the prefix length, and the chunk winners of the rows this wavefront merges
   // (row hh goes to wavefront hh % 4), so that the merge costs one round trip, not one per row.
@@ -204,7 +203,7 @@ extern "C" int medusa_topk_tree(const float* medusa_logits, const float* lm_logi
   const int Sc = S <= 1 ? 1 : (S <= 2 ? 2 : (S <= 4 ? 4 : (S <= 8 ? 8 : 16)));
 #define MEDUSA_TOPK(S_)                                                                                         \
   hipLaunchKernelGGL(topk_tree_kernel<S_>, grid, block, 0, stream, medusa_logits, lm_logits, V, K_heads, part, \
-                     tree->dev, prefix_len, topk_ids, tree_tokens, position_ids, K)
+                     tree->dev, prefix_len, topk_ids, tree_tokens, position_ids, K, ticket_slot(stream))
   switch (Sc) {
     case 1: MEDUSA_TOPK(1); break;
     case 2: MEDUSA_TOPK(2); break;

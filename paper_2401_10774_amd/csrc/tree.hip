@@ -8,6 +8,8 @@
 #include <new>
 #include <vector>
 
+#include <mutex>
+
 #include "common.hpp"
 
 namespace {
@@ -140,6 +142,22 @@ int build(std::vector<Node>& cand, int K, medusa_tree_t** out) {
 }
 
 }  // namespace
+
+// Stream -> ticket slot (see common.hpp).  A handle that is reused after its stream was destroyed keeps
+// its slot, which is harmless.
+int ticket_slot(hipStream_t stream) {
+  static std::mutex mu;
+  static hipStream_t seen[kTicketSlots];
+  static int n_seen = 0;
+  std::lock_guard<std::mutex> lock(mu);
+  for (int i = 0; i < n_seen; ++i)
+    if (seen[i] == stream) return i;
+  if (n_seen < kTicketSlots) {
+    seen[n_seen] = stream;
+    return n_seen++;
+  }
+  return kTicketSlots - 1;
+}
 
 extern "C" const char* medusa_status_string(int status) {
   switch (status) {
