@@ -156,3 +156,12 @@ def test_chain_fp32_tiny():
     lengths = [[3, 1, 2], [1, 3, 3], [2, 2, 1], [3, 3, 3]]
     seen = run_chain("greedy-f32", cfg, 4, [0, 1, 1, 0], plant_lengths=lengths)
     assert seen == {1, 2, 3}
+
+
+def test_chain_7b_shapes_three_steps():
+    """The 7B-shaped workload itself (d = 4096, V = 32000, 32 heads x 128, 64-node tree, prefix 1024) over
+    three chained steps on two cache layers: the launch configuration the benchmark times, with the
+    in-place commit the benchmark avoids."""
+    cfg = scaled_config("C2", NL=2)
+    seen = run_chain("7B", cfg, 3, [0, 1, 0], plant_lengths=[[4], [1], [5]])
+    assert seen == {1, 4, 5}
