@@ -232,6 +232,9 @@ def main():
             "traffic_measured_at_commit": None if traffic is None else traffic["commit"],
         },
         "kernels": kernels,
+        "kernels_note": "call durations between two events on the stream, in instrumented steps after the timed region (W1, W2: "
+                        "inside it); an event pair adds about 2 us to a call -- the profiler's kernel durations are in "
+                        "profiles/bench_kernel_traces.md",
         "mean_accept_len": round(float(accept_len.mean()), 3),
     }
 

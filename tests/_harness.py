@@ -45,13 +45,22 @@ def record(case: str, stage: str, err: float) -> None:
         pass
 
 
-def check_close(case: str, stage: str, got, ref, dtype: str, kind: str = None, rounded_output: bool = False) -> float:
+def resid_bound(dtype: str, d: int) -> float:
+    """Derived bound for logits behind the residual block at hidden size d: a storage rounding that falls the
+    other way moves a logit by 2^-8 |w r|, which is about 2^-8 / sqrt(d) of a row whose d terms add up at
+    random, and a row maximum sits about four such deviations out; a handful of such roundings per row."""
+    return BOUND[dtype]["resid"] if dtype != "bf16" else max(BOUND[dtype]["resid"], 1e-4 + 2.0 ** -8 * 4.0 / d ** 0.5)
+
+
+def check_close(case: str, stage: str, got, ref, dtype: str, kind: str = None, rounded_output: bool = False,
+                bound: float = None) -> float:
     """Assert the stated bound and the derived one, and record the achieved error."""
     kind = kind or ("rounded" if rounded_output else ("resid" if stage == "heads" else "logits"))
+    bound = BOUND[dtype][kind] if bound is None else bound
     err = row_rel_err(got, ref)
     record(case, stage, err)
     assert err <= TOL[dtype], f"{case} {stage}: {err:.3e} exceeds the stated bound {TOL[dtype]:.0e}"
-    assert err <= BOUND[dtype][kind], f"{case} {stage}: {err:.3e} exceeds the derived bound {BOUND[dtype][kind]:.1e} ({kind})"
+    assert err <= bound, f"{case} {stage}: {err:.3e} exceeds the derived bound {bound:.1e} ({kind})"
     return err
 
 

@@ -6,7 +6,7 @@ import torch
 import paper_2401_10774_amd as M
 from oracle import medusa_oracle as O
 from workloads import draw_normal, get_config, make_step_inputs
-from _harness import TOL, bits, check_close, row_rel_err, to_dev, to_host_bits, to_host_f64
+from _harness import TOL, bits, check_close, resid_bound, row_rel_err, to_dev, to_host_bits, to_host_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -20,7 +20,7 @@ def run_case(dtype, M_rows, d, V, K, with_w1, seed):
     ref_logits, ref_resid = O.medusa_heads_ref(h, w1, w2, dtype)
     case = f"heads {dtype} M={M_rows} d={d} V={V} K={K}"
     err = check_close(case, "logits behind the residual block" if with_w1 else "logits", to_host_f64(logits), ref_logits, dtype,
-                      kind="resid" if with_w1 else "logits")
+                      kind="resid" if with_w1 else "logits", bound=resid_bound(dtype, d) if with_w1 else None)
     if with_w1:
         check_close(case, "residual", to_host_f64(resid), ref_resid, dtype, kind="rounded2")
     return err
