@@ -325,6 +325,7 @@ def bench_block(args, cfg):
     from paper_2401_10774_amd.block import SimplifiedBlock
 
     inter = {4096: 11008, 5120: 13824}.get(cfg.d, ((cfg.d * 8 // 3 + 255) // 256) * 256)      # Llama-family widths
+    M.medusa_set_cache_resident_bytes(0)       # the weight sets rotate: every matrix comes from HBM, the library is told so
     dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     es = 2 if cfg.dtype == "bf16" else 4
     tree = M.MedusaTree(branching=cfg.branching)
@@ -426,6 +427,7 @@ def bench_speed_model(args, cfg):
     gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
     rnd = lambda *shp, std=1.0: (torch.randn(shp, generator=gen, device="cuda", dtype=torch.float32) * std).to(dt)
     n_sets = 6
+    M.medusa_set_cache_resident_bytes(0)       # the weight sets rotate: every matrix comes from HBM
     qkv = [rnd((Hq + 2 * Hkv) * D, h, std=h ** -0.5) for _ in range(n_sets)]      # one allocation per set (fused at batch 1)
     wsets = [dict(wq=qkv[i][:Hq * D], wk=qkv[i][Hq * D:(Hq + Hkv) * D], wv=qkv[i][(Hq + Hkv) * D:],
                   wu=rnd(inter, Hq * D, std=h ** -0.5), wg=rnd(inter, Hq * D, std=h ** -0.5), wd=rnd(h, inter, std=inter ** -0.5))

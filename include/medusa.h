@@ -391,10 +391,11 @@ int medusa_set_cache_resident_bytes(size_t bytes);
  * the library would launch for a bf16 product of M activation rows with K weight matrices of
  * N rows x d columns (medusa_heads, tree_linear), with or without a workspace.
  * plan6 (host, 6 ints, written): [0] kind: 0 wave-per-row GEMV, 1 skinny MFMA tiles, 2 128 x 128
- * tiles, 3 large tiles;  [1] kind 1: 128 (else 64) weight rows per workgroup, kind 3: 192 (else 128)
- * activation rows per tile;  [2] kind 1: the long-run kernel for cold weights;  [3] kind 1/2: groups
- * of 16 activation rows per row block (1..8);  [4] row blocks;  [5] workgroups that share one tile's
- * reduction (1 = unsplit; > 1 only with a workspace).
+ * tiles, 3 large tiles;  [1] kind 1: weight rows per workgroup (32..128), kind 3: activation rows per
+ * tile (128 or 192), else 0;  [2] kind 1: the kernel for weights that come from HBM (1 KB runs per
+ * weight row, straight into an LDS ring);  [3] kind 1/2: groups of 16 activation rows per row block
+ * (1..8);  [4] row blocks;  [5] workgroups that share one tile's reduction (1 = unsplit; > 1 only
+ * with a workspace).
  * Returns MEDUSA_EINVAL for a null pointer or a non-positive size.
  * -------------------------------------------------------------------------------- */
 int medusa_gemm_plan(int M, int N, int d, int K, int have_workspace, int* plan6);

@@ -591,7 +591,8 @@ def medusa_gemm_plan(M: int, N: int, d: int, K: int = 1, have_workspace: bool = 
     out = (ctypes.c_int * 6)()
     _check(lib().medusa_gemm_plan(int(M), int(N), int(d), int(K), int(bool(have_workspace)), out), "medusa_gemm_plan")
     kinds = ("gemv", "skinny", "square", "big")
-    return {"kind": kinds[out[0]], "wide": bool(out[1]), "runs": bool(out[2]), "mt": out[3], "m_blocks": out[4], "ksplit": out[5]}
+    return {"kind": kinds[out[0]], "tile": out[1], "wide": (out[0] == 1 and out[1] == 128) or (out[0] == 3 and out[1] == 192), "ring": bool(out[2]), "mt": out[3],
+            "m_blocks": out[4], "ksplit": out[5]}
 
 
 def tree_rope(q: torch.Tensor, k: torch.Tensor, position_ids: torch.Tensor, theta: float = 10000.0, stream=None) -> None:

@@ -173,17 +173,48 @@ __device__ __forceinline__ float rows_sum(float x) {
   return __uint_as_float(b.x) + __uint_as_float(b.y);
 }
 
-__device__ __forceinline__ bool last_workgroup_of(unsigned int* counter, unsigned int total) {
-  __shared__ unsigned int s_ticket;
+// Workgroup barrier that waits for this wavefront's LDS accesses only.  __syncthreads() also carries
+// a fence that waits for every global load in flight, which would empty the ring of K/V steps below
+// once per step.  The "memory" clobber keeps the compiler from moving memory operations across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// 16 bytes per lane from global memory straight into LDS (global_load_lds_dwordx4): lane l's bytes land
+// at lds_base + 16 l; lds_base is wavefront-uniform and travels in M0.  An assembly statement on
+// purpose: where the compiler sees such a load it also decides where to wait for it, and it waits for
+// every load in flight before the first LDS read it cannot tell apart from the destination -- once
+// per step, which again empties the ring.  Completion is tracked by hand with the load counter.
+// STREAM marks data read once (weights of a skinny GEMM): the load carries the non-temporal hint.
+template <bool STREAM = false>
+__device__ __forceinline__ void load_to_lds_b128(const void* gptr, unsigned char* lds_base) {
+  const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_base);
+  if (STREAM) asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off nt" : : "s"(m0), "v"(gptr) : "memory", "m0");
+  else asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(m0), "v"(gptr) : "memory", "m0");
+}
+// Wait until at most N of this wavefront's vector-memory loads are outstanding (they complete in order).
+template <int N>
+__device__ __forceinline__ void wait_loads_outstanding() {
+  static_assert(N >= 0 && N <= 63, "the counter has six bits");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// Election of the workgroup that arrives last among `total` that share `counter` (zero before the first
+// arrives, zero again after the last): every caller's earlier stores are complete before it takes
+// its ticket.  Called by all threads of the workgroup; true in every thread of the last one.
+// `s_ticket` is a word of LDS no thread of the workgroup uses for anything else during the call.
+__device__ __forceinline__ bool last_workgroup_of(unsigned int* counter, unsigned int total, unsigned int* s_ticket) {
   __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wavefront's loads and stores are complete
   __syncthreads();
   if (threadIdx.x == 0) {
     const unsigned int t = atomicAdd(counter, 1u);
     if (t == total - 1) atomicExch(counter, 0u);
-    s_ticket = t;
+    *s_ticket = t;
   }
   __syncthreads();
-  return s_ticket == total - 1;
+  return *s_ticket == total - 1;
+}
+__device__ __forceinline__ bool last_workgroup_of(unsigned int* counter, unsigned int total) {
+  __shared__ unsigned int s_ticket;
+  return last_workgroup_of(counter, total, &s_ticket);
 }
 
 // Order-preserving key for (logit, token id): a larger key means a larger logit, or an equal

@@ -542,95 +542,102 @@ __global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// bf16, 4 < M <= 80, 128-column tiles: the skinny kernel above with the weights fetched in 1 KB runs.
+// bf16, 4 < M <= 80, weights that come from HBM: the weights of a tile are fetched in 1 KB runs and
+// nothing passes through registers on its way to LDS.
 //
 // Cold weights stream from HBM at 4.4 TB/s when a workgroup asks for 256 bytes of each of its 128
-// rows at a time, at 5.3 TB/s for 1 KB of 32 rows (measured with a plain read kernel).  So the
-// reduction advances in super-stages of 512 elements, and within one the tile's four groups of 32
-// weight rows take turns: a sub-stage is 32 rows x 1 KB of weights, one wavefront instruction per
-// row.  The activation rows of a super-stage (16*MT x 1 KB) sit in a single LDS slab; each
-// wavefront copies the fragments of its 128-element slice into registers at the first sub-stage
-// and keeps them for all four, which frees the slab for the next super-stage's rows: they arrive
-// in three pieces, stored during sub-stages 1 to 3.  Everything else -- wavefronts split the
-// reduction, swizzled unpadded LDS rows (chunk c of row r in slot c ^ (r%16) of its 256-byte
-// group), PD register stages, one barrier per sub-stage, sum over the wavefronts at the end --
-// is as above.  grid (ceil(N/128), K, ceil(M/BM)), 256 threads, dynamic LDS (MT*16 + 64) KB.
+// rows at a time, at 5.3 TB/s for 1 KB of 32 rows (measured with a plain read kernel), so the
+// reduction advances in super-stages of 512 elements, and within one the tile's NTW column fragments
+// (16 weight rows x 1 KB each) take turns: sub-stage u = NTW S + j is fragment j of super-stage S.
+// Weights and activation rows go from global memory straight into LDS (global_load_lds_dwordx4, one
+// instruction = one row's 1 KB run): the weights into a ring of NR buffers of one sub-stage each, so
+// that NR - 1 sub-stages are in flight whatever the register budget; the activation rows of a
+// super-stage (16 MT x 1 KB) into a single slab.  Each wavefront copies the fragments of its
+// 128-element slice of the slab into registers at j = 0 and keeps them for the super-stage, which
+// frees the slab for the next one's rows, requested at j = 1.  As in the kernel above the
+// wavefronts split the reduction, not the tile, and their partial tiles are added through LDS at the
+// end.  The swizzle of the LDS rows (chunk c of row r in slot c ^ (r%16) of its 256-byte group: fragment
+// reads free of bank conflicts) is applied on the global side: the lane that fills slot p fetches
+// chunk p ^ (r%16).
+// Per sub-stage and wavefront: wait until its own loads of sub-stage u have landed (the load counter:
+// loads complete in order, so "at most n outstanding" with n = the loads issued after them), barrier,
+// request sub-stage u + NR - 1 into the buffer sub-stage u - 1 has just left, read the four weight
+// fragments of the wavefront's slice, 4 MT MFMAs.  The loads are invisible to the compiler (see
+// load_to_lds_b128), and so is their completion.
+// Elements past d in the last super-stage: the weights' chunk index is clamped (any finite value
+// does), the activation fragments are zeroed in registers.
+// Narrower tiles (NTW = 6, 4, 3, 2 fragments) exist so that an output of a few thousand columns
+// still gives every CU a workgroup; the price is the activation rows, which every workgroup fetches.
+// Cold 32000 x 4096 matrix on MI355X, against the register-staged kernel this one replaced: M = 5..16
+// 48 -> 44 us (6.0 TB/s), M = 65 52.5 -> 49; 32000 x 5120: M = 16 59 -> 50, M = 65 76 -> 66.
+// grid (ceil(N/(16 NTW)), K, ceil(M/BM)), 256 threads, dynamic LDS (16 MT + 16 NR) KB.
 // ---------------------------------------------------------------------------------------
-template <int MT, int PD, int EPI>
-__global__ __launch_bounds__(256) void gemm_runs_bf16_kernel(GemmArgs a) {
-  constexpr int NTW = 8, NT = 2, NG = 4;               // column fragments per tile / per wavefront in the end, column groups
-  constexpr int BM = 16 * MT, BN = 128;
-  constexpr int XQ = MT * 4;                           // activation chunks per thread and super-stage
-  constexpr int XC = (XQ + 2) / 3;                     // ... per piece (three pieces)
-  constexpr int WC = 8;                                // weight chunks per thread and sub-stage
-  constexpr int LPT = WC + XC;
-  constexpr int SLAB = BM * 1024, WBUF = 32 * 1024;
+template <int MT, int NTW, int NR, int EPI, bool SPLIT = false>
+__global__ __launch_bounds__(256) void gemm_ring_bf16_kernel(GemmArgs a) {
+  constexpr int BM = 16 * MT, BN = 16 * NTW;
+  constexpr int XL = MT * 4;                           // activation rows (load instructions) per wavefront and super-stage
+  constexpr int WL = 4;                                // weight rows per wavefront and sub-stage
+  constexpr int SLAB = BM * 1024, SUB = 16 * 1024;
   constexpr bool HM = kHeadMajor<EPI>;
-  static_assert(PD == 2 || PD == 4, "the loop is unrolled by the four column groups");
+  static_assert(NTW >= 2 && NTW <= 8, "the activation rows of the next super-stage are requested at j = 1");
+  static_assert(NR >= 3 && NR <= 8, "the count of loads issued after a sub-stage's own assumes 3..8 buffers");
+  static_assert(WL * (NR - 2) + XL <= 63, "load counter");
+  static_assert(4 * MT * NTW <= 16 * (MT + NR), "the four partial tiles must fit the LDS the loop used");
+  static_assert(EPI != EPI_SWIGLU || NTW % 2 == 0, "gate and up fragments come in pairs");
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_dyn[];
-  unsigned char* lds = lds_dyn;                        // [slab][weight buffer 0][weight buffer 1]
+  unsigned char* lds = lds_dyn;                        // [slab][ring of NR weight buffers]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i16 = lane & 15, q4 = lane >> 4;
   const int k = blockIdx.y;
-  const int m_tile = blockIdx.z;
+  // Split reduction (a template switch, as above): ksplit workgroups share a tile, each taking a
+  // contiguous share of the super-stages (at least one: the host's business).
+  const int n_split = SPLIT ? a.ksplit : 1, m_tile = blockIdx.z / n_split, split = blockIdx.z - m_tile * n_split;
   const int n0 = blockIdx.x * BN, m0 = m_tile * BM;
   const unsigned char* Wt = (const unsigned char*)((const uint16_t*)a.W + ((size_t)k * a.N + n0) * a.d);
   const unsigned char* Xb = (const unsigned char*)a.X;
-  const int c64 = lane;                                // this thread's 16-byte chunk of a 1 KB run
   const int n_super = (a.d + 511) >> 9;
+  const int s_first = (int)((long)n_super * split / n_split);
+  const int n_mine = (int)((long)n_super * (split + 1) / n_split) - s_first, total = n_mine * NTW;
   const int c_last = ((a.d - (n_super - 1) * 512) >> 3) - 1;   // last valid chunk of the last super-stage
-  // every workgroup starts the reduction at a different super-stage and wraps around (see the kernel above)
-  const int rot = (int)((blockIdx.x * 3u) % (unsigned)n_super);
-  auto rotated = [&](int S) { const int Sr = min(S, n_super - 1) + rot; return Sr >= n_super ? Sr - n_super : Sr; };
+  // every workgroup starts its share of the reduction at a different super-stage and wraps around (see the kernel above)
+  const int rot = (int)((blockIdx.x * 3u) % (unsigned)n_mine);
+  auto rotated = [&](int S) { const int Sr = S + rot; return s_first + (Sr >= n_mine ? Sr - n_mine : Sr); };
 
-  // Byte offsets of the rows this thread fetches (from the tile's first weight row; from X).
-  const int w_last = a.N - 1 - n0;                     // last weight row of the matrix, relative to the tile
+  // Rows this wavefront fetches: weight rows 16 j + 4 i + wave of the tile, activation rows 4 q + wave
+  // of the block; either way the row's index mod 16 is 4 i' + wave (i' = i, q%4), and the chunk
+  // this lane fetches for slot `lane` of such a row is cidx[i'].
+  const int w_last = a.N - 1 - n0;
   const uint32_t w_pitch = (uint32_t)a.d * 2u;
-  uint32_t xoff[XQ];                                   // activation row q*4 + wave
+  int cidx[4];
 #pragma unroll
-  for (int q = 0; q < XQ; ++q) xoff[q] = (uint32_t)(x_row_offset<HM>(a, min(m0 + q * 4 + wave, a.M - 1), k) * 2);
-  // LDS offset of this thread's chunk within a 1 KB row whose index is r (mod 16): rows q*4 + wave
-  // and it*4 + wave have r%16 = (4*(q%4) + wave), so the slot depends on q%4 only
-  auto slot_of = [&](int r) { return ((c64 & ~15) | ((c64 ^ r) & 15)) << 4; };
+  for (int i = 0; i < 4; ++i) cidx[i] = (lane & ~15) | ((lane ^ (4 * i + wave)) & 15);
+  uint32_t xoff[XL];
+#pragma unroll
+  for (int q = 0; q < XL; ++q) xoff[q] = (uint32_t)(x_row_offset<HM>(a, min(m0 + q * 4 + wave, a.M - 1), k) * 2);
 
-  u32x4_t regs[PD][LPT];
-  // Requests of sub-stage u = 4*S + g: the weights of column group g, super-stage S, and -- for
-  // g = 2, 3, 0 -- piece 0, 1, 2 of the activation rows of super-stage S+1, S+1, S.
-  auto gload = [&](int S, int g, u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
+  auto issue_w = [&](int S, int j, int buf) __attribute__((always_inline)) {
     const int Sw = rotated(S);
-    const int cw = Sw == n_super - 1 ? min(c64, c_last) : c64;
-    const uint32_t so_w = (uint32_t)(Sw * 1024 + cw * 16);
+    unsigned char* dst = lds + SLAB + buf * SUB + wave * 1024;
 #pragma unroll
-    for (int it = 0; it < WC; ++it) r[it] = *(const u32x4_t*)(Wt + ((uint32_t)min(g * 32 + it * 4 + wave, w_last) * w_pitch + so_w));
-    if (g != 1) {
-      const int p = g == 0 ? 2 : g - 2;
-      const int Sx = rotated(g == 0 ? S : S + 1);
-      const int cx = Sx == n_super - 1 ? min(c64, c_last) : c64;
-      const uint32_t so_x = (uint32_t)(x_col_offset<HM>(a, Sx * 512 + (cx & ~7) * 8) * 2) + (cx & 7) * 16;
-#pragma unroll
-      for (int i = 0; i < XC; ++i) {
-        const int q = p * XC + i < XQ ? p * XC + i : XQ - 1;
-        r[WC + i] = *(const u32x4_t*)(Xb + (xoff[q] + so_x));
-      }
+    for (int i = 0; i < WL; ++i) {
+      const int c = Sw == n_super - 1 ? min(cidx[i], c_last) : cidx[i];
+      const uint32_t off = (uint32_t)min(j * 16 + i * 4 + wave, w_last) * w_pitch + (uint32_t)(Sw * 1024 + c * 16);
+      load_to_lds_b128<true>(Wt + off, dst + i * 4096);
     }
   };
-  // ... and their stores: weights to buffer u%2, the activation piece to the slab (zeros beyond d)
-  auto lstore = [&](int S, int g, const u32x4_t (&r)[LPT]) __attribute__((always_inline)) {
-    unsigned char* wb = lds + SLAB + (g & 1) * WBUF + wave * 1024;
+  auto issue_x = [&](int S) __attribute__((always_inline)) {
+    const int Sx = rotated(S);
+    uint32_t so[4];
 #pragma unroll
-    for (int it = 0; it < WC; ++it) *(u32x4_t*)(wb + it * 4096 + slot_of(it * 4 + wave)) = r[it];
-    if (g != 1) {
-      const int p = g == 0 ? 2 : g - 2;
-      const int Sl = g == 0 ? S : S + 1, Sx = rotated(Sl);     // (a super-stage past the end is never used: zeros)
-      const uint32_t keep = (uint32_t) - (int)(Sl < n_super && (Sx < n_super - 1 || c64 <= c_last));
-#pragma unroll
-      for (int i = 0; i < XC; ++i) {
-        const int q = p * XC + i < XQ ? p * XC + i : XQ - 1;
-        *(u32x4_t*)(lds + (q * 4 + wave) * 1024 + slot_of(q * 4 + wave)) = r[WC + i] & keep;
-      }
+    for (int i = 0; i < 4; ++i) {
+      const int c = Sx == n_super - 1 ? min(cidx[i], c_last) : cidx[i];
+      so[i] = (uint32_t)(x_col_offset<HM>(a, Sx * 512 + (c & ~7) * 8) * 2) + (c & 7) * 16;
     }
+#pragma unroll
+    for (int q = 0; q < XL; ++q) load_to_lds_b128<false>(Xb + (xoff[q] + so[q & 3]), lds + (q * 4 + wave) * 1024);
   };
+
   floatx4_t acc[MT][NTW];
 #pragma unroll
   for (int t = 0; t < MT; ++t)
@@ -643,80 +650,135 @@ __global__ __launch_bounds__(256) void gemm_runs_bf16_kernel(GemmArgs a) {
     const int c = wave * 16 + ks * 4 + q4;
     fr_off[ks] = i16 * 1024 + (((c & ~15) | ((c ^ i16) & 15)) << 4);
   }
-  bf16x8_t xf[MT][4], wf[NT][4];
+  bf16x8_t xf[MT][4], wf[4];
 
-  // Prologue: the activation rows of super-stage 0 and the weights of sub-stage 0 into LDS,
-  // sub-stages 1..PD-1 requested.
+  // Everything this wavefront has loaded so far the ordinary way must have arrived before the first
+  // hand-counted load, or the counts below would include it.
+  wait_loads_outstanding<0>();
+  issue_x(0);
+  // sub-stages 0 .. NR-2
   {
-    const int S0 = rotated(0);
-    const int cx = S0 == n_super - 1 ? min(c64, c_last) : c64;
-    const uint32_t so_x = (uint32_t)(x_col_offset<HM>(a, S0 * 512 + (cx & ~7) * 8) * 2) + (cx & 7) * 16;
-    const uint32_t keep = (uint32_t) - (int)(S0 < n_super - 1 || c64 <= c_last);
-    u32x4_t x0[XQ];
+    int Sp = 0, jp = 0;
 #pragma unroll
-    for (int q = 0; q < XQ; ++q) x0[q] = *(const u32x4_t*)(Xb + (xoff[q] + so_x));
-    gload(0, 0, regs[0]);
-#pragma unroll
-    for (int q = 0; q < XQ; ++q) *(u32x4_t*)(lds + (q * 4 + wave) * 1024 + slot_of(q * 4 + wave)) = x0[q] & keep;
-    lstore(0, 0, regs[0]);
+    for (int u = 0; u < NR - 1; ++u) {
+      if (u < total) issue_w(Sp, jp, u);               // (a reduction shorter than the ring: every wait below is for everything)
+      if (++jp == NTW) { jp = 0; ++Sp; }
+    }
   }
+  int buf = 0;                                         // buffer of sub-stage u
+  int Sn = (NR - 1) / NTW, jn = (NR - 1) % NTW;        // super-stage and fragment of sub-stage u + NR - 1
+  for (int S = 0; S < n_mine; ++S) {
+    const bool last_super = rotated(S) == n_super - 1;
 #pragma unroll
-  for (int u = 1; u < PD; ++u) gload(u / NG, u % NG, regs[u]);
-  __syncthreads();
-
-  constexpr int NMF = MT * NT * 4;
-  for (int S = 0; S < n_super; ++S) {
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      // On entry of sub-stage u = 4*S + g its weights are in buffer g%2 and register stage u%PD is free
-      // (its contents, sub-stage u, were stored during the previous sub-stage).
-      if (g == 0) {
+    for (int j = 0; j < NTW; ++j) {
+      const int u = S * NTW + j;
+      // Loads issued after this sub-stage's own: the weights of sub-stages u+1 .. u+NR-2 and, for
+      // j = 2 .. NR-1, the activation rows of the next super-stage (issued at j = 1, before that
+      // step's weights).  At j = 0 the slab must be complete as well: its rows were requested NTW - 1
+      // sub-stages ago.  Near the end fewer loads exist: wait for everything then.
+      constexpr int kAfter0 = WL * (NR - 2 < NTW - 1 ? NR - 2 : NTW - 1);
+      if (u + NR - 2 >= total) wait_loads_outstanding<0>();
+      else if (j == 0) wait_loads_outstanding<kAfter0>();
+      else if (j >= 2 && j <= NR - 1 && S + 1 < n_mine) wait_loads_outstanding<WL * (NR - 2) + XL>();
+      else wait_loads_outstanding<WL * (NR - 2)>();
+      lds_barrier();
+      if (j == 1 && S + 1 < n_mine) issue_x(S + 1);
+      if (u + NR - 1 < total) {
+        issue_w(Sn, jn, buf == 0 ? NR - 1 : buf - 1);
+        if (++jn == NTW) { jn = 0; ++Sn; }
+      }
+      if (j == 0) {
 #pragma unroll
         for (int t = 0; t < MT; ++t)
 #pragma unroll
-          for (int ks = 0; ks < 4; ++ks) xf[t][ks] = *(const bf16x8_t*)(lds + t * 16384 + fr_off[ks]);
+          for (int ks = 0; ks < 4; ++ks) {
+            bf16x8_t f = *(const bf16x8_t*)(lds + t * 16384 + fr_off[ks]);
+            if (last_super && wave * 16 + ks * 4 + q4 > c_last) f = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+            xf[t][ks] = f;
+          }
       }
-      const unsigned char* wb = lds + SLAB + (g & 1) * WBUF;
+      const unsigned char* wb = lds + SLAB + buf * SUB;
 #pragma unroll
-      for (int f = 0; f < NT; ++f)
+      for (int ks = 0; ks < 4; ++ks) wf[ks] = *(const bf16x8_t*)(wb + fr_off[ks]);
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) wf[f][ks] = *(const bf16x8_t*)(wb + f * 16384 + fr_off[ks]);
-      gload(S + (g + PD) / NG, (g + PD) % NG, regs[g % PD]);     // sub-stage u + PD
+      for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-      for (int f = 0; f < NT; ++f)
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-          for (int t = 0; t < MT; ++t)
-            acc[t][g * NT + f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[t][ks], wf[f][ks], acc[t][g * NT + f], 0, 0, 0);
-      lstore(S + (g + 1) / NG, (g + 1) % NG, regs[(g + 1) % PD]);
-      __syncthreads();
+        for (int t = 0; t < MT; ++t)
+          acc[t][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[t][ks], wf[ks], acc[t][j], 0, 0, 0);
+      buf = buf == NR - 1 ? 0 : buf + 1;
     }
   }
 
-  // Add the four wavefronts' partial tiles, RT groups of 16 rows at a time (as in the kernel above).
-  constexpr int RT = (SLAB + 2 * WBUF) / (4 * NTW * 1024) < MT ? (SLAB + 2 * WBUF) / (4 * NTW * 1024) : MT;
-  floatx4_t fin[MT][NT];
+  // Add the four wavefronts' partial tiles: each writes its fragments (one 16-byte slot per lane), then
+  // collects the four partials of the units it owns -- a unit is one fragment (one gate/up pair of
+  // fragments for the SwiGLU epilogue), dealt out round-robin.  With a split reduction the sums go to
+  // the workspace ([tile][split][unit slot][fragment of the unit][register pair][thread], 8 bytes per
+  // thread and store, write-through); the workgroup that arrives last adds them in split order.
+  constexpr int F = MT * NTW, PER = EPI == EPI_SWIGLU ? 2 : 1, UNITS = F / PER, UPR = NTW / PER, NU = (UNITS + 3) / 4;
+  __syncthreads();
 #pragma unroll
-  for (int t0 = 0; t0 < MT; t0 += RT) {
-    __syncthreads();
+  for (int t = 0; t < MT; ++t)
 #pragma unroll
-    for (int t = t0; t < t0 + RT && t < MT; ++t)
+    for (int j = 0; j < NTW; ++j) *(floatx4_t*)(lds + (((wave * F + t * NTW + j) * 64 + lane) << 4)) = acc[t][j];
+  __syncthreads();
+  floatx4_t fin[NU][PER];
 #pragma unroll
-      for (int j = 0; j < NTW; ++j)
-        *(floatx4_t*)(lds + ((((t - t0) * 4 + wave) * NTW + j) * 64 + lane) * 16) = acc[t][j];
-    __syncthreads();
+  for (int n = 0; n < NU; ++n) {
+    const int unit = min(n * 4 + wave, UNITS - 1);       // (a surplus slot repeats the last unit and is never stored)
+    const int t = unit / UPR, jj = unit - t * UPR;
 #pragma unroll
-    for (int t = t0; t < t0 + RT && t < MT; ++t)
+    for (int e = 0; e < PER; ++e) {
+      const int f = t * NTW + jj * PER + e;
+      floatx4_t sum = *(const floatx4_t*)(lds + (((0 * F + f) * 64 + lane) << 4));
 #pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        floatx4_t sum = *(const floatx4_t*)(lds + ((((t - t0) * 4 + 0) * NTW + wave * NT + j) * 64 + lane) * 16);
-#pragma unroll
-        for (int w = 1; w < 4; ++w) sum += *(const floatx4_t*)(lds + ((((t - t0) * 4 + w) * NTW + wave * NT + j) * 64 + lane) * 16);
-        fin[t][j] = sum;
-      }
+      for (int w = 1; w < 4; ++w) sum += *(const floatx4_t*)(lds + (((w * F + f) * 64 + lane) << 4));
+      fin[n][e] = sum;
+    }
   }
-  finish_tile<MT, NT, EPI, false>(a, fin, k, m_tile, 0, 1, n0, m0, 0, wave);
+  if (SPLIT && n_split > 1) {
+    const unsigned int tile = (k * gridDim.x + blockIdx.x) * (gridDim.z / n_split) + m_tile;
+    constexpr int PART = NU * PER * 2 * 256;             // 8-byte words per partial tile
+    uint64_t* part = (uint64_t*)a.ws + (size_t)tile * n_split * PART;
+#pragma unroll
+    for (int n = 0; n < NU; ++n)
+#pragma unroll
+      for (int e = 0; e < PER; ++e)
+#pragma unroll
+        for (int rp = 0; rp < 2; ++rp) {
+          const uint64_t v = (uint64_t)__float_as_uint(fin[n][e][2 * rp]) | ((uint64_t)__float_as_uint(fin[n][e][2 * rp + 1]) << 32);
+          store_agent(part + (size_t)split * PART + ((n * PER + e) * 2 + rp) * 256 + tid, v);
+        }
+    // (the ticket word lives in the dynamic LDS, which the sums above have left: this kernel has no static LDS to spare)
+    if (!last_workgroup_of(&g_gemm_ticket[a.ticket_slot][tile], (unsigned int)n_split, (unsigned int*)lds)) return;
+    // every load is a round trip to the memory side of the L2: all splits of a slot are requested together
+    constexpr int SLOTS = NU * PER * 2;
+#pragma unroll
+    for (int sl = 0; sl < SLOTS; ++sl) {
+      uint64_t v[8];
+#pragma unroll
+      for (int z = 0; z < 8; ++z)
+        if (z < n_split) v[z] = load_agent(part + (size_t)z * PART + sl * 256 + tid);
+      float lo = 0.f, hi = 0.f;
+#pragma unroll
+      for (int z = 0; z < 8; ++z)
+        if (z < n_split) {
+          lo += __uint_as_float((uint32_t)v[z]);
+          hi += __uint_as_float((uint32_t)(v[z] >> 32));
+        }
+      fin[sl / (PER * 2)][(sl / 2) % PER][2 * (sl & 1)] = lo;
+      fin[sl / (PER * 2)][(sl / 2) % PER][2 * (sl & 1) + 1] = hi;
+    }
+  }
+#pragma unroll
+  for (int n = 0; n < NU; ++n) {
+    const int unit = n * 4 + wave;
+    if (unit >= UNITS) break;
+    const int t = unit / UPR, jj = unit - t * UPR;
+    floatx4_t one[1][PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) one[0][e] = fin[n][e];
+    finish_tile<1, PER, EPI, false>(a, one, k, m_tile, 0, 1, n0, m0, t, jj);
+  }
 }
 
 // Which kernel a bf16 GEMM of M rows goes to, and in what shape.
@@ -734,13 +796,14 @@ __global__ __launch_bounds__(256) void gemm_runs_bf16_kernel(GemmArgs a) {
 struct GemmPlan {
   enum { GEMV, SKINNY, SQUARE, BIG } kind;
   bool wide;
-  bool runs;            // 128-column skinny tiles: the kernel that fetches the weights in 1 KB runs
+  bool ring;            // skinny tiles of 16*ntw columns: the kernel for cold weights (1 KB runs straight into an LDS ring)
+  int ntw;              // skinny: column fragments (16 weight rows each) per workgroup
   int mt, m_blocks, ksplit;
 };
 // Weight matrices up to this many bytes are taken to stay in the last-level cache between calls.
 size_t g_llc_bytes = (size_t)256 << 20;
 GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) {
-  GemmPlan p = {GemmPlan::GEMV, false, false, 1, 1, 1};
+  GemmPlan p = {GemmPlan::GEMV, false, false, 8, 1, 1, 1};
   if (M <= 4) return p;
   p.m_blocks = ceil_div(M, 128);
   if (M > 80) {
@@ -847,9 +910,26 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
     }
   }
   p.wide = p.mt <= 5 && (long)ceil_div(N, 128) * K * p.m_blocks >= 200;   // (128-column tiles exist for up to 80 rows)
-  // Cold weights want long runs per row (15-19 % faster at M = 8..64, 10 % at 65..80); weights that
-  // the last-level cache holds want the short-stage kernel (3-8 % faster there).
-  p.runs = p.wide && (size_t)K * N * d * sizeof(uint16_t) > g_llc_bytes;
+  p.ntw = p.wide ? 8 : 4;
+  // Weights that come from HBM (larger than what the last-level cache keeps between calls) and up to
+  // 80 rows per block: the ring kernel, unsplit, with the tile width that prices lowest -- rounds of
+  // 256 workgroups x (column fragments + the activation rows every workgroup fetches, which cost about
+  // a quarter of their bytes, + one fragment's worth of start and end) -- among those that give at
+  // least 160 workgroups.  Narrower outputs keep the split reduction below.
+  if (p.mt <= 5 && (size_t)K * N * d * sizeof(uint16_t) > g_llc_bytes) {
+    double best = 1e30;
+    static const int widths[4] = {8, 6, 4, 3};
+    for (int wi = 0; wi < 4; ++wi) {
+      const long t = (long)ceil_div(N, 16 * widths[wi]) * K * p.m_blocks;
+      if (t < 160) continue;
+      const double cost = (double)((t + 255) / 256) * (widths[wi] + 0.25 * p.mt + 1.0);
+      if (cost < best) { best = cost; p.ntw = widths[wi]; p.ring = true; }
+    }
+    if (p.ring) {
+      p.wide = p.ntw == 8;
+      return p;
+    }
+  }
   // Split the reduction only when the unsplit kernel would leave most of the chip idle (under 160
   // tiles): into the largest power of two of workgroups per tile that leaves each at least 16 steps
   // and the launch at most ~640 workgroups.  Measured at M = 65 (us, splits 1/2/4/8):
@@ -867,6 +947,28 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
     }
     return p;
   }
+  // Cold weights, up to 80 rows per block: the ring kernel with its reduction split, on 128- or 64-column
+  // tiles, over 2, 4 or 8 workgroups per tile, at most one workgroup per CU in all and at least one
+  // 512-element super-stage each.  Priced in units of one sub-stage (16 rows x 1 KB, about 0.75 us):
+  // the longest share of super-stages x (column fragments + a quarter of the row groups, as above),
+  // five for start, election and end, and the partial tiles the last workgroup fetches alone --
+  // splits x tile bytes, at what one CU can pull.  N = 4096, d = 11008, M = 65 on MI355X: 64 columns
+  // x 4 splits 31 us, 128 x 8 40 us, 128 x 4 49 us (the kernel this replaced: 34.5 us).
+  if (p.mt <= 5 && (size_t)K * N * d * sizeof(uint16_t) > g_llc_bytes) {
+    const int n_super = (d + 511) / 512;
+    double best = 1e30;
+    for (int w = 8; w >= 4; w -= 4)
+      for (int ks = 2; ks <= 8; ks *= 2) {
+        const long t = (long)ceil_div(N, 16 * w) * K * p.m_blocks;
+        if (t * ks > 256 || ks > n_super) continue;
+        const double cost = (double)ceil_div(n_super, ks) * (w + 0.25 * p.mt) + 5.0 + ks * p.mt * w / 16.0;
+        if (cost < best) { best = cost; p.ntw = w; p.ksplit = ks; p.ring = true; }
+      }
+    if (p.ring) {
+      p.wide = p.ntw == 8;
+      return p;
+    }
+  }
   long cap = 640 / tiles;
   const long by_steps = (d / 64) / 16;
   cap = cap < by_steps ? cap : by_steps;
@@ -881,6 +983,8 @@ size_t gemm_ws_bytes(int M, int N, int d, int K) {
     return (size_t)8 * ceil_div(ceil_div(N, 256), 8) * ceil_div(M, rows) * K * p.ksplit * rows * 256 * sizeof(float);
   }
   if (p.kind != GemmPlan::SKINNY || p.ksplit <= 1) return 0;
+  if (p.ring)                                               // per workgroup: ceil(mt*ntw/4) fragments per thread
+    return (size_t)ceil_div(N, 16 * p.ntw) * K * p.m_blocks * p.ksplit * ceil_div(p.mt * p.ntw, 4) * 4 * 256 * sizeof(float);
   const int frags = p.mt * (p.wide ? 2 : 1);                // accumulator fragments per thread
   return (size_t)ceil_div(N, p.wide ? 128 : 64) * K * p.m_blocks * p.ksplit * frags * 4 * 256 * sizeof(float);
 }
@@ -898,6 +1002,8 @@ int gemv_rows_per_wg(int N, int K, int M) {
 
 // Register stages of the skinny kernel: three while its MT + NTW chunks per thread and stage leave room.
 constexpr int skinny_depth(int mt, int ntw) { return mt + ntw <= 13 ? 3 : 2; }
+// Weight buffers of the ring kernel: what 160 KB of LDS hold beside the activation slab, at most 8.
+constexpr int ring_depth(int mt) { return mt >= 5 ? 5 : (10 - mt > 8 ? 8 : 10 - mt); }
 
 // The skinny kernel's LDS tile exceeds the 64 KB a kernel gets by default: raise the limit once per
 // kernel and device.
@@ -908,7 +1014,7 @@ int launch_skinny(dim3 grid, size_t lds, hipStream_t stream, const GemmArgs& a) 
   MEDUSA_HIP_TRY(hipGetDevice(&dev));
   if (dev < 0 || dev >= 64) return MEDUSA_EUNSUPPORTED;
   if (!raised[dev]) {
-    MEDUSA_HIP_TRY(hipFuncSetAttribute((const void*)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024));   // the largest tile of these kernels
+    MEDUSA_HIP_TRY(hipFuncSetAttribute((const void*)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));   // the largest tile of these kernels
     raised[dev] = true;
   }
   hipLaunchKernelGGL(Kernel, grid, dim3(256), lds, stream, a);
@@ -953,7 +1059,7 @@ int launch_gemm(const GemmArgs& a_in, int dtype, hipStream_t stream) {
     constexpr bool kCanSplit = EPI == EPI_PLAIN || EPI == EPI_GATED;
     const bool split = kCanSplit && a.ksplit > 1;
     if (!split) a.ksplit = 1;
-    const dim3 grid(ceil_div(a.N, wide ? 128 : 64), a.K, plan.m_blocks * a.ksplit);
+    const dim3 grid(ceil_div(a.N, plan.kind == GemmPlan::SKINNY ? 16 * plan.ntw : 128), a.K, plan.m_blocks * a.ksplit);
     if (plan.kind == GemmPlan::SQUARE) {
       hipLaunchKernelGGL((gemm_lds_bf16_kernel<2, 2, 4, 4, 64, 2, EPI, false>), grid, block, 0, stream, a);
       MEDUSA_LAUNCH_CHECK();
@@ -964,12 +1070,23 @@ int launch_gemm(const GemmArgs& a_in, int dtype, hipStream_t stream) {
     // N = d = 4096).  Unsplit, LDS time decides and the kernel whose wavefronts split the reduction wins.
 #define MEDUSA_SKINNY(MT_)                                                                                                     \
   case MT_:                                                                                                                    \
-    if (split) {                                                                                                               \
+    if (split && plan.ring) {                                                                                                  \
+      constexpr int MR = MT_ <= 5 ? MT_ : 5, NR = ring_depth(MR);                                                        \
+      const size_t ring_lds = (size_t)(NR + MR) * 16384;                                                                       \
+      if (plan.ntw == 8) rc = launch_skinny<gemm_ring_bf16_kernel<MR, 8, NR, EPI, kCanSplit>>(grid, ring_lds, stream, a);      \
+      else rc = launch_skinny<gemm_ring_bf16_kernel<MR, 4, NR, EPI, kCanSplit>>(grid, ring_lds, stream, a);                    \
+    } else if (split) {                                                                                                        \
       if (!wide) hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 1, 64, 4, EPI, kCanSplit>), grid, block, 0, stream, a);   \
       else hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 2, 64, 4, EPI, kCanSplit>), grid, block, 0, stream, a);         \
+    } else if (plan.ring) {                                                                                                    \
+      constexpr int MR = MT_ <= 5 ? MT_ : 5, NR = ring_depth(MR);                                                              \
+      const size_t ring_lds = (size_t)(NR + MR) * 16384;                                                                       \
+      if (plan.ntw == 8) rc = launch_skinny<gemm_ring_bf16_kernel<MR, 8, NR, EPI>>(grid, ring_lds, stream, a);                 \
+      else if (plan.ntw == 6) rc = launch_skinny<gemm_ring_bf16_kernel<MR, 6, NR, EPI>>(grid, ring_lds, stream, a);            \
+      else if (plan.ntw == 4) rc = launch_skinny<gemm_ring_bf16_kernel<MR, 4, NR, EPI>>(grid, ring_lds, stream, a);            \
+      else rc = launch_skinny<gemm_ring_bf16_kernel<MR, 3, NR, EPI>>(grid, ring_lds, stream, a);                               \
     } else {                                                                                                                   \
-      if (!wide) rc = launch_skinny<gemm_skinny_bf16_kernel<MT_, 4, skinny_depth(MT_, 4), EPI>>(grid, lds, stream, a);  \
-      else if (plan.runs) rc = launch_skinny<gemm_runs_bf16_kernel<(MT_ <= 5 ? MT_ : 5), (MT_ <= 2 ? 4 : 2), EPI>>(grid, (size_t)(plan.mt * 16 + 64) * 1024, stream, a); \
+      if (!wide) rc = launch_skinny<gemm_skinny_bf16_kernel<MT_, 4, skinny_depth(MT_, 4), EPI>>(grid, lds, stream, a);         \
       else rc = launch_skinny<gemm_skinny_bf16_kernel<(MT_ <= 5 ? MT_ : 5), 8, skinny_depth(MT_, 8), EPI>>(grid, lds, stream, a); \
     }                                                                                                                          \
     break;
@@ -1193,13 +1310,29 @@ extern "C" int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int 
   // 128-column tiles (gate and up fragments of a column block side by side in a wavefront), row blocks
   // of at most 80 rows, never split: tuned for the tree-token range, correct for any M
   const int m_blocks = ceil_div(a.M, 80), mt = ceil_div(ceil_div(a.M, m_blocks), 16);
-  const dim3 grid(ceil_div(a.N, 128), 1, m_blocks);
-  const bool runs = (size_t)a.N * a.d * sizeof(uint16_t) > g_llc_bytes;
+  // cold weights: the ring kernel, with the tile width (whole gate/up pairs) priced as in plan_gemm
+  int ntw = 8;
+  const bool ring = (size_t)a.N * a.d * sizeof(uint16_t) > g_llc_bytes;
+  if (ring) {
+    double best = 1e30;
+    for (int w = 8; w >= 2; w -= 2) {
+      const long t = (long)ceil_div(a.N, 16 * w) * m_blocks;
+      const double cost = (double)((t + 255) / 256) * (w + 0.25 * mt + 1.0);
+      if ((t >= 160 || w == 8) && cost < best) { best = cost; ntw = w; }
+    }
+  }
+  const dim3 grid(ceil_div(a.N, 16 * ntw), 1, m_blocks);
   int rc = MEDUSA_OK;
 #define MEDUSA_SWIGLU(MT_)                                                                                                \
   case MT_:                                                                                                               \
-    if (runs) rc = launch_skinny<gemm_runs_bf16_kernel<MT_, (MT_ <= 2 ? 4 : 2), EPI_SWIGLU>>(grid, (size_t)(MT_ * 16 + 64) * 1024, stream, a); \
-    else rc = launch_skinny<gemm_skinny_bf16_kernel<MT_, 8, skinny_depth(MT_, 8), EPI_SWIGLU>>(grid, (size_t)2 * (MT_ + 8) * 4096, stream, a); \
+    if (ring) {                                                                                                           \
+      constexpr int NR = ring_depth(MT_);                                                                                 \
+      const size_t ring_lds = (size_t)(NR + MT_) * 16384;                                                                 \
+      if (ntw == 8) rc = launch_skinny<gemm_ring_bf16_kernel<MT_, 8, NR, EPI_SWIGLU>>(grid, ring_lds, stream, a);         \
+      else if (ntw == 6) rc = launch_skinny<gemm_ring_bf16_kernel<MT_, 6, NR, EPI_SWIGLU>>(grid, ring_lds, stream, a);    \
+      else if (ntw == 4) rc = launch_skinny<gemm_ring_bf16_kernel<MT_, 4, NR, EPI_SWIGLU>>(grid, ring_lds, stream, a);    \
+      else rc = launch_skinny<gemm_ring_bf16_kernel<MT_, 2, NR, EPI_SWIGLU>>(grid, ring_lds, stream, a);                  \
+    } else rc = launch_skinny<gemm_skinny_bf16_kernel<MT_, 8, skinny_depth(MT_, 8), EPI_SWIGLU>>(grid, (size_t)2 * (MT_ + 8) * 4096, stream, a); \
     break;
   switch (mt) { MEDUSA_SWIGLU(1) MEDUSA_SWIGLU(2) MEDUSA_SWIGLU(3) MEDUSA_SWIGLU(4) MEDUSA_SWIGLU(5) default: return MEDUSA_EUNSUPPORTED; }
 #undef MEDUSA_SWIGLU
@@ -1212,7 +1345,7 @@ extern "C" int medusa_gemm_plan(int M, int N, int d, int K, int have_workspace, 
   if (!plan6 || M < 1 || N < 1 || d < 1 || K < 1) return MEDUSA_EINVAL;
   const bool wide_offsets = (size_t)N * d >= ((size_t)1 << 31) || (size_t)M * d + (size_t)K * d + d >= ((size_t)1 << 31);
   const GemmPlan p = plan_gemm(M, N, d, K, have_workspace != 0, wide_offsets);
-  plan6[0] = (int)p.kind; plan6[1] = p.wide; plan6[2] = p.runs; plan6[3] = p.mt; plan6[4] = p.m_blocks; plan6[5] = p.ksplit;
+  plan6[0] = (int)p.kind; plan6[1] = p.kind == GemmPlan::SKINNY ? 16 * p.ntw : (p.kind == GemmPlan::BIG ? (p.wide ? 192 : 128) : 0); plan6[2] = p.ring; plan6[3] = p.mt; plan6[4] = p.m_blocks; plan6[5] = p.ksplit;
   return MEDUSA_OK;
 }
 

@@ -140,21 +140,6 @@ __global__ __launch_bounds__(256) void tree_attn_plain_kernel(AttnArgs a) {
 
 typedef short short4_t __attribute__((ext_vector_type(4)));
 
-// Workgroup barrier that waits for this wavefront's LDS accesses only.  __syncthreads() also carries
-// a fence that waits for every global load in flight, which would empty the ring of K/V steps below
-// once per step.  The "memory" clobber keeps the compiler from moving memory operations across it.
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-// 16 bytes per lane from global memory straight into LDS (global_load_lds_dwordx4): lane l's bytes land
-// at lds_base + 16 l; lds_base is wavefront-uniform and travels in M0.  An assembly statement on
-// purpose: where the compiler sees such a load it also decides where to wait for it, and it waits for
-// every load in flight before the first LDS read it cannot tell apart from the destination -- once
-// per step, which again empties the ring.  Completion is tracked by hand (wait_loads in the kernel).
-__device__ __forceinline__ void load_to_lds_b128(const void* gptr, unsigned char* lds_base) {
-  const uint32_t m0 = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_base);
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(m0), "v"(gptr) : "memory", "m0");
-}
-
 // Four bf16 of a transposed tile: within each group of 16 lanes, lane j of the group receives
 // element (j % 4) of the 8-byte rows addressed by lanes j/4, j/4 + 4, j/4 + 8, j/4 + 12 of the
 // group (ds_read_b64_tr_b16).  With lane r addressing V[key0 + r/4][d0 + 4*(r%4) .. +3], lane j

@@ -49,15 +49,16 @@ def test_bf16_odd_step_counts(M_rows, d, V, K):
     run_case("bf16", M_rows, d, V, K, False, 80 + M_rows)
 
 
-# The 128-column skinny tiles have a second kernel for weights that come from HBM rather than from
-# the last-level cache (1 KB runs per weight row, super-stages of 512 elements).  The library picks
-# it for weight matrices above a size threshold; with the threshold at zero the same shapes as
-# above -- row groups 1..5, ragged last tile, one to several super-stages, partial last one -- run
-# through it.
+# Weights that come from HBM rather than from the last-level cache have a kernel of their own (1 KB runs
+# per weight row straight into an LDS ring, super-stages of 512 elements, tiles of 48 to 128 columns).
+# The library picks it for weight matrices above a size threshold; with the threshold at zero the
+# same shapes as above -- row groups 1..5, ragged last tile, one to several super-stages, partial
+# last one, every tile width (250 / 200 / 200 / 201 workgroups) -- run through it.
 @pytest.mark.parametrize("M_rows,d,V,K", [(70, 192, 12800, 2), (120, 448, 12900, 2), (33, 704, 25700, 1),
                                           (5, 512, 25600, 1), (17, 1024, 6400, 4), (48, 1600, 12803, 2),
-                                          (64, 64, 25600, 1), (80, 2560, 25601, 1)])
-def test_bf16_long_run_kernel(M_rows, d, V, K):
+                                          (64, 64, 25600, 1), (80, 2560, 25601, 1),
+                                          (65, 1088, 19190, 1), (40, 576, 12790, 1), (75, 512, 9640, 1)])
+def test_bf16_cold_weights_kernel(M_rows, d, V, K):
     M.medusa_set_cache_resident_bytes(0)
     try:
         run_case("bf16", M_rows, d, V, K, False, 90 + M_rows)
