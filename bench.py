@@ -142,8 +142,7 @@ def main():
     plant_accepted_paths(step, tensors, tree, cfg)
     # Between two verification steps a decoder streams its whole backbone, so nothing of this step's
     # weights is left in the 256 MB last-level cache.  The timed loop reproduces that: the W1 stack and
-    # the LM head rotate over copies (W2, 1 GB, and the KV layers, which rotate too, evict themselves),
-    # and the library is told to plan for weights that come from HBM.
+    # the LM head rotate over copies (W2, 1 GB, and the KV layers, which rotate too, evict themselves).
     w1_bytes = tensors["w1"].numel() * tensors["w1"].element_size()
     lm_bytes = tensors["w_lm"].numel() * tensors["w_lm"].element_size()
     n_w1 = max(2, min(4, int(math.ceil(600e6 / w1_bytes))))
@@ -152,7 +151,6 @@ def main():
     every = max(1, args.event_every)
 
     def timed_loop(cold):
-        M.medusa_set_cache_resident_bytes(0 if cold else 256 << 20)
         for i in range(W):
             step.run(i % cfg.NL, wset=i if cold else 0)
         timed = [i for i in range(K) if i % every == 0]
@@ -174,7 +172,6 @@ def main():
     ms_per_step, w1_ms, kern_ms, n_timed = timed_loop(cold=True)
     accept_len = step.accept_out[0].cpu().numpy()
     warm_ms, _, _, _ = timed_loop(cold=False)
-    M.medusa_set_cache_resident_bytes(0)
 
     mean_prefix = float(np.mean(x["prefix_len"]))
     parts = step.algorithmic_bytes(mean_prefix, float(accept_len.mean()))
@@ -185,7 +182,6 @@ def main():
     dom_bytes = parts["heads_w2"]
     dom_gbs = dom_bytes / (kern_ms * 1e-3) / 1e9
     kernels = per_call_timings(step, cfg, parts, w1_ms, kern_ms)
-    M.medusa_set_cache_resident_bytes(256 << 20)
     traffic = measured_traffic(cfg.name)
 
     out = {
@@ -325,7 +321,6 @@ def bench_block(args, cfg):
     from paper_2401_10774_amd.block import SimplifiedBlock
 
     inter = {4096: 11008, 5120: 13824}.get(cfg.d, ((cfg.d * 8 // 3 + 255) // 256) * 256)      # Llama-family widths
-    M.medusa_set_cache_resident_bytes(0)       # the weight sets rotate: every matrix comes from HBM, the library is told so
     dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     es = 2 if cfg.dtype == "bf16" else 4
     tree = M.MedusaTree(branching=cfg.branching)
@@ -427,7 +422,6 @@ def bench_speed_model(args, cfg):
     gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
     rnd = lambda *shp, std=1.0: (torch.randn(shp, generator=gen, device="cuda", dtype=torch.float32) * std).to(dt)
     n_sets = 6
-    M.medusa_set_cache_resident_bytes(0)       # the weight sets rotate: every matrix comes from HBM
     qkv = [rnd((Hq + 2 * Hkv) * D, h, std=h ** -0.5) for _ in range(n_sets)]      # one allocation per set (fused at batch 1)
     wsets = [dict(wq=qkv[i][:Hq * D], wk=qkv[i][Hq * D:(Hq + Hkv) * D], wv=qkv[i][(Hq + Hkv) * D:],
                   wu=rnd(inter, Hq * D, std=h ** -0.5), wg=rnd(inter, Hq * D, std=h ** -0.5), wd=rnd(h, inter, std=inter ** -0.5))

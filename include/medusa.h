@@ -376,17 +376,6 @@ int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int B, int T, i
                        int y_heads, int dtype, medusa_stream_t stream);
 
 /* ----------------------------------------------------------------------------------
- * Tuning knob (no counterpart in the paper).  The MFMA kernels of medusa_heads and tree_linear
- * for 5..80 rows come in two forms: one is faster when the weight matrix is still in the GPU's
- * last-level cache from the previous call (an LM head of up to 256 MB that is re-read every step,
- * with only non-temporal streams in between), the other when it comes from HBM.  Matrices of up to
- * `bytes` bytes are taken to be cache-resident.  Default 256 MiB; 0 = always assume cold weights
- * (e.g. when a whole backbone streams through between two calls).  Process-wide, not thread-safe.
- * Results are within the same tolerance either way (the summation order differs).
- * -------------------------------------------------------------------------------- */
-int medusa_set_cache_resident_bytes(size_t bytes);
-
-/* ----------------------------------------------------------------------------------
  * Diagnostic (no counterpart in the paper; host only, touches no GPU): which kernel arrangement
  * the library would launch for a bf16 product of M activation rows with K weight matrices of
  * N rows x d columns (medusa_heads, tree_linear), with or without a workspace.

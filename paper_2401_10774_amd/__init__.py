@@ -19,7 +19,6 @@ from .binding import (
     medusa_carry_over,
     medusa_heads,
     medusa_gemm_plan,
-    medusa_set_cache_resident_bytes,
     medusa_topk_tree,
     tree_attention,
     tree_attention_static,
@@ -34,7 +33,7 @@ from .binding import (
 
 __all__ = [
     "MedusaError", "MedusaTree", "kv_commit", "lib", "library_path", "medusa_accept", "medusa_accept_sampled", "medusa_accept_fused", "medusa_verify_fused_available", "medusa_verify_logits",
-    "medusa_accept_workspace_bytes", "medusa_carry_over", "medusa_heads", "medusa_gemm_plan", "medusa_set_cache_resident_bytes", "medusa_topk_tree", "tree_attention",
+    "medusa_accept_workspace_bytes", "medusa_carry_over", "medusa_heads", "medusa_gemm_plan", "medusa_topk_tree", "tree_attention",
     "tree_attention_workspace_bytes", "tree_attention_static", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "interleave_gate_up",
     "tree_linear_workspace_bytes", "tree_rope",
 ]

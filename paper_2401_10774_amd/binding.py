@@ -30,7 +30,7 @@ EXPORTED_SYMBOLS = (
     "medusa_accept", "medusa_accept_sampled", "medusa_verify_stats_bytes", "medusa_verify_fused_available",
     "medusa_verify_logits", "medusa_accept_fused", "kv_commit", "medusa_carry_over", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "tree_rope",
     "medusa_heads_timed",
-    "medusa_set_cache_resident_bytes", "medusa_gemm_plan",
+    "medusa_gemm_plan",
 )
 
 
@@ -90,7 +90,6 @@ def lib() -> ctypes.CDLL:
         L.tree_linear_segments.argtypes = [c_void_p] * 4 + [c_int] * 7 + [c_size_t, c_int, c_void_p, c_size_t, c_void_p]
         L.tree_rope.argtypes = [c_void_p] * 3 + [c_int] * 5 + [c_float, c_int, c_void_p]
         L.medusa_heads_timed.argtypes = [c_void_p] * 5 + [c_int] * 5 + [c_void_p] * 4
-        L.medusa_set_cache_resident_bytes.argtypes = [ctypes.c_size_t]
         L.medusa_gemm_plan.argtypes = [c_int] * 5 + [ctypes.POINTER(c_int)]
         for name in EXPORTED_SYMBOLS:
             fn = getattr(L, name)
@@ -577,12 +576,6 @@ def tree_linear_swiglu(x: torch.Tensor, w_gu: torch.Tensor, B: int, T: int, y: O
     _check(lib().tree_linear_swiglu(x.data_ptr(), w_gu.data_ptr(), y.data_ptr(), B, T, d_in, d_out, x_heads, y_heads, code,
                                     _stream(stream)), "tree_linear_swiglu")
     return y
-
-
-def medusa_set_cache_resident_bytes(nbytes: int) -> None:
-    """Weight matrices of up to `nbytes` are taken to stay in the last-level cache between calls
-    (default 256 MiB; 0 = always cold).  Selects between two forms of the 5..80-row MFMA kernels."""
-    _check(lib().medusa_set_cache_resident_bytes(int(nbytes)), "medusa_set_cache_resident_bytes")
 
 
 def medusa_gemm_plan(M: int, N: int, d: int, K: int = 1, have_workspace: bool = True) -> dict:

@@ -800,8 +800,6 @@ struct GemmPlan {
   int ntw;              // skinny: column fragments (16 weight rows each) per workgroup
   int mt, m_blocks, ksplit;
 };
-// Weight matrices up to this many bytes are taken to stay in the last-level cache between calls.
-size_t g_llc_bytes = (size_t)256 << 20;
 GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) {
   GemmPlan p = {GemmPlan::GEMV, false, false, 8, 1, 1, 1};
   if (M <= 4) return p;
@@ -909,14 +907,15 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
       p.mt = ceil_div(ceil_div(M, p.m_blocks), 16);
     }
   }
-  p.wide = p.mt <= 5 && (long)ceil_div(N, 128) * K * p.m_blocks >= 200;   // (128-column tiles exist for up to 80 rows)
-  p.ntw = p.wide ? 8 : 4;
-  // Weights that come from HBM (larger than what the last-level cache keeps between calls) and up to
-  // 80 rows per block: the ring kernel, unsplit, with the tile width that prices lowest -- rounds of
-  // 256 workgroups x (column fragments + the activation rows every workgroup fetches, which cost about
-  // a quarter of their bytes, + one fragment's worth of start and end) -- among those that give at
-  // least 160 workgroups.  Narrower outputs keep the split reduction below.
-  if (p.mt <= 5 && (size_t)K * N * d * sizeof(uint16_t) > g_llc_bytes) {
+  p.wide = false;
+  p.ntw = 4;                                                // (the register-staged kernels below: 64-column tiles)
+  // Up to 80 rows per block: the ring kernel, unsplit, with the tile width that prices lowest -- rounds
+  // of 256 workgroups x (column fragments + the activation rows every workgroup fetches, which cost
+  // about a quarter of their bytes, + one fragment's worth of start and end) -- among those that give
+  // at least 160 workgroups.  Narrower outputs get a split reduction below.  (Measured against the
+  // register-staged kernels at M = 16..80 on 7B and 13B projection shapes and the LM head: 7-30 %
+  // faster on weights from HBM, equal within 3 % on weights the last-level cache holds.)
+  if (p.mt <= 5) {
     double best = 1e30;
     static const int widths[4] = {8, 6, 4, 3};
     for (int wi = 0; wi < 4; ++wi) {
@@ -936,38 +935,44 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
   // N = 4096, d = 4096: 25/24/18/19;  N = 4096, d = 11008: 67/54/36/35;  N = 5120, d = 13824: 83/65/57/54;
   // N = 11008, d = 4096: 32/37/36/45;  N = 13824, d = 5120: 41/48/53/63;  and with two or three row
   // blocks at N = d = 4096 (splits 1/2/4): M = 192 (128 tiles) 30/28/27, M = 260 (192 tiles) 31/38/42.
-  const long tiles = (long)ceil_div(N, p.wide ? 128 : 64) * K * p.m_blocks;
+  const long tiles = (long)ceil_div(N, 64) * K * p.m_blocks;
   if (!have_ws || tiles >= 160) {
     // Unsplit.  With seven or eight row groups per workgroup the kernel runs out of registers for its
     // prefetch: one more row block then, if the launch stays within one workgroup per CU (M = 256,
     // N = d = 4096: 38 -> 31 us; N = 4096, d = 11008: 91 -> 75; but N = 11008, d = 4096: 78 -> 91).
-    if (!p.wide && p.mt >= 7 && tiles / p.m_blocks * (p.m_blocks + 1) <= 256) {
+    if (p.mt >= 7 && tiles / p.m_blocks * (p.m_blocks + 1) <= 256) {
       p.m_blocks += 1;
       p.mt = ceil_div(ceil_div(M, p.m_blocks), 16);
     }
     return p;
   }
-  // Cold weights, up to 80 rows per block: the ring kernel with its reduction split, on 128- or 64-column
-  // tiles, over 2, 4 or 8 workgroups per tile, at most one workgroup per CU in all and at least one
-  // 512-element super-stage each.  Priced in units of one sub-stage (16 rows x 1 KB, about 0.75 us):
-  // the longest share of super-stages x (column fragments + a quarter of the row groups, as above),
-  // five for start, election and end, and the partial tiles the last workgroup fetches alone --
-  // splits x tile bytes, at what one CU can pull.  N = 4096, d = 11008, M = 65 on MI355X: 64 columns
-  // x 4 splits 31 us, 128 x 8 40 us, 128 x 4 49 us (the kernel this replaced: 34.5 us).
-  if (p.mt <= 5 && (size_t)K * N * d * sizeof(uint16_t) > g_llc_bytes) {
+  // Up to 80 rows per block and a reduction long enough to give every workgroup three 512-element
+  // super-stages: the ring kernel with its reduction split, on 128-, 96- or 64-column tiles, over 2, 4
+  // or 8 workgroups per tile, at most one workgroup per CU in all.  Priced in units of one sub-stage
+  // (16 rows x 1 KB, about 0.75 us): the longest share of super-stages x (column fragments + a quarter
+  // of the row groups, as above), five for start, election and end, and the partial tiles the last
+  // workgroup fetches alone -- splits x tile bytes, at what one CU can pull.  N = 4096, d = 11008,
+  // M = 65 on MI355X: 64 columns x 4 splits 31 us, 128 x 8 40 us, 128 x 4 49 us (the register-staged
+  // kernel below: 34.5 us).  Shorter shares never fill the ring: N = d = 4096 runs 21.5 us this way,
+  // 18.6 us below.
+  if (p.mt <= 5) {
     const int n_super = (d + 511) / 512;
     double best = 1e30;
-    for (int w = 8; w >= 4; w -= 4)
+    int share = 0;
+    for (int w = 8; w >= 4; w -= 2)
       for (int ks = 2; ks <= 8; ks *= 2) {
         const long t = (long)ceil_div(N, 16 * w) * K * p.m_blocks;
         if (t * ks > 256 || ks > n_super) continue;
         const double cost = (double)ceil_div(n_super, ks) * (w + 0.25 * p.mt) + 5.0 + ks * p.mt * w / 16.0;
-        if (cost < best) { best = cost; p.ntw = w; p.ksplit = ks; p.ring = true; }
+        if (cost < best) { best = cost; p.ntw = w; p.ksplit = ks; share = n_super / ks; }
       }
-    if (p.ring) {
+    if (share >= 3) {
+      p.ring = true;
       p.wide = p.ntw == 8;
       return p;
     }
+    p.ntw = 4;
+    p.ksplit = 1;
   }
   long cap = 640 / tiles;
   const long by_steps = (d / 64) / 16;
@@ -985,8 +990,7 @@ size_t gemm_ws_bytes(int M, int N, int d, int K) {
   if (p.kind != GemmPlan::SKINNY || p.ksplit <= 1) return 0;
   if (p.ring)                                               // per workgroup: ceil(mt*ntw/4) fragments per thread
     return (size_t)ceil_div(N, 16 * p.ntw) * K * p.m_blocks * p.ksplit * ceil_div(p.mt * p.ntw, 4) * 4 * 256 * sizeof(float);
-  const int frags = p.mt * (p.wide ? 2 : 1);                // accumulator fragments per thread
-  return (size_t)ceil_div(N, p.wide ? 128 : 64) * K * p.m_blocks * p.ksplit * frags * 4 * 256 * sizeof(float);
+  return (size_t)ceil_div(N, 64) * K * p.m_blocks * p.ksplit * p.mt * 4 * 256 * sizeof(float);   // mt accumulator fragments per thread
 }
 
 // Weight rows per GEMV workgroup: 16 measured best on MI355X at 7B shapes (8, 32 and 64 were
@@ -1053,7 +1057,6 @@ int launch_gemm(const GemmArgs& a_in, int dtype, hipStream_t stream) {
       a.ksplit = plan.ksplit;
       return launch_gemm_big(a, EPI, plan.wide, stream);
     }
-    const bool wide = plan.wide;
     a.ksplit = plan.ksplit;
     // split reductions exist for the epilogues tree_linear uses (medusa_heads passes no workspace)
     constexpr bool kCanSplit = EPI == EPI_PLAIN || EPI == EPI_GATED;
@@ -1074,10 +1077,10 @@ int launch_gemm(const GemmArgs& a_in, int dtype, hipStream_t stream) {
       constexpr int MR = MT_ <= 5 ? MT_ : 5, NR = ring_depth(MR);                                                        \
       const size_t ring_lds = (size_t)(NR + MR) * 16384;                                                                       \
       if (plan.ntw == 8) rc = launch_skinny<gemm_ring_bf16_kernel<MR, 8, NR, EPI, kCanSplit>>(grid, ring_lds, stream, a);      \
+      else if (plan.ntw == 6) rc = launch_skinny<gemm_ring_bf16_kernel<MR, 6, NR, EPI, kCanSplit>>(grid, ring_lds, stream, a); \
       else rc = launch_skinny<gemm_ring_bf16_kernel<MR, 4, NR, EPI, kCanSplit>>(grid, ring_lds, stream, a);                    \
     } else if (split) {                                                                                                        \
-      if (!wide) hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 1, 64, 4, EPI, kCanSplit>), grid, block, 0, stream, a);   \
-      else hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 2, 64, 4, EPI, kCanSplit>), grid, block, 0, stream, a);         \
+      hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 1, 64, 4, EPI, kCanSplit>), grid, block, 0, stream, a);              \
     } else if (plan.ring) {                                                                                                    \
       constexpr int MR = MT_ <= 5 ? MT_ : 5, NR = ring_depth(MR);                                                              \
       const size_t ring_lds = (size_t)(NR + MR) * 16384;                                                                       \
@@ -1086,11 +1089,10 @@ int launch_gemm(const GemmArgs& a_in, int dtype, hipStream_t stream) {
       else if (plan.ntw == 4) rc = launch_skinny<gemm_ring_bf16_kernel<MR, 4, NR, EPI>>(grid, ring_lds, stream, a);            \
       else rc = launch_skinny<gemm_ring_bf16_kernel<MR, 3, NR, EPI>>(grid, ring_lds, stream, a);                               \
     } else {                                                                                                                   \
-      if (!wide) rc = launch_skinny<gemm_skinny_bf16_kernel<MT_, 4, skinny_depth(MT_, 4), EPI>>(grid, lds, stream, a);         \
-      else rc = launch_skinny<gemm_skinny_bf16_kernel<(MT_ <= 5 ? MT_ : 5), 8, skinny_depth(MT_, 8), EPI>>(grid, lds, stream, a); \
+      rc = launch_skinny<gemm_skinny_bf16_kernel<MT_, 4, skinny_depth(MT_, 4), EPI>>(grid, lds, stream, a);                    \
     }                                                                                                                          \
     break;
-    const size_t lds = (size_t)2 * (plan.mt + (wide ? 8 : 4)) * 4096;
+    const size_t lds = (size_t)2 * (plan.mt + 4) * 4096;
     int rc = MEDUSA_OK;
     switch (plan.mt) {
       MEDUSA_SKINNY(1) MEDUSA_SKINNY(2) MEDUSA_SKINNY(3) MEDUSA_SKINNY(4) MEDUSA_SKINNY(5) MEDUSA_SKINNY(6)
@@ -1310,10 +1312,9 @@ extern "C" int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int 
   // 128-column tiles (gate and up fragments of a column block side by side in a wavefront), row blocks
   // of at most 80 rows, never split: tuned for the tree-token range, correct for any M
   const int m_blocks = ceil_div(a.M, 80), mt = ceil_div(ceil_div(a.M, m_blocks), 16);
-  // cold weights: the ring kernel, with the tile width (whole gate/up pairs) priced as in plan_gemm
+  // the ring kernel, with the tile width (whole gate/up pairs) priced as in plan_gemm
   int ntw = 8;
-  const bool ring = (size_t)a.N * a.d * sizeof(uint16_t) > g_llc_bytes;
-  if (ring) {
+  {
     double best = 1e30;
     for (int w = 8; w >= 2; w -= 2) {
       const long t = (long)ceil_div(a.N, 16 * w) * m_blocks;
@@ -1324,16 +1325,14 @@ extern "C" int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int 
   const dim3 grid(ceil_div(a.N, 16 * ntw), 1, m_blocks);
   int rc = MEDUSA_OK;
 #define MEDUSA_SWIGLU(MT_)                                                                                                \
-  case MT_:                                                                                                               \
-    if (ring) {                                                                                                           \
-      constexpr int NR = ring_depth(MT_);                                                                                 \
-      const size_t ring_lds = (size_t)(NR + MT_) * 16384;                                                                 \
-      if (ntw == 8) rc = launch_skinny<gemm_ring_bf16_kernel<MT_, 8, NR, EPI_SWIGLU>>(grid, ring_lds, stream, a);         \
-      else if (ntw == 6) rc = launch_skinny<gemm_ring_bf16_kernel<MT_, 6, NR, EPI_SWIGLU>>(grid, ring_lds, stream, a);    \
-      else if (ntw == 4) rc = launch_skinny<gemm_ring_bf16_kernel<MT_, 4, NR, EPI_SWIGLU>>(grid, ring_lds, stream, a);    \
-      else rc = launch_skinny<gemm_ring_bf16_kernel<MT_, 2, NR, EPI_SWIGLU>>(grid, ring_lds, stream, a);                  \
-    } else rc = launch_skinny<gemm_skinny_bf16_kernel<MT_, 8, skinny_depth(MT_, 8), EPI_SWIGLU>>(grid, (size_t)2 * (MT_ + 8) * 4096, stream, a); \
-    break;
+  case MT_: {                                                                                                             \
+    constexpr int NR = ring_depth(MT_);                                                                                   \
+    const size_t ring_lds = (size_t)(NR + MT_) * 16384;                                                                   \
+    if (ntw == 8) rc = launch_skinny<gemm_ring_bf16_kernel<MT_, 8, NR, EPI_SWIGLU>>(grid, ring_lds, stream, a);           \
+    else if (ntw == 6) rc = launch_skinny<gemm_ring_bf16_kernel<MT_, 6, NR, EPI_SWIGLU>>(grid, ring_lds, stream, a);      \
+    else if (ntw == 4) rc = launch_skinny<gemm_ring_bf16_kernel<MT_, 4, NR, EPI_SWIGLU>>(grid, ring_lds, stream, a);      \
+    else rc = launch_skinny<gemm_ring_bf16_kernel<MT_, 2, NR, EPI_SWIGLU>>(grid, ring_lds, stream, a);                    \
+  } break;
   switch (mt) { MEDUSA_SWIGLU(1) MEDUSA_SWIGLU(2) MEDUSA_SWIGLU(3) MEDUSA_SWIGLU(4) MEDUSA_SWIGLU(5) default: return MEDUSA_EUNSUPPORTED; }
 #undef MEDUSA_SWIGLU
   if (rc != MEDUSA_OK) return rc;
@@ -1349,9 +1348,5 @@ extern "C" int medusa_gemm_plan(int M, int N, int d, int K, int have_workspace, 
   return MEDUSA_OK;
 }
 
-extern "C" int medusa_set_cache_resident_bytes(size_t bytes) {
-  g_llc_bytes = bytes;
-  return MEDUSA_OK;
-}
 
 

@@ -148,7 +148,8 @@ def test_gemm_plans_are_launchable():
                     assert ws or p["ksplit"] == 1, what
                     assert not p["wide"] or p["mt"] <= 5, what
                     assert p["tile"] in (48, 64, 96, 128), what
-                    assert not p["ring"] or (p["mt"] <= 5 and p["ksplit"] == 1), what
+                    assert not p["ring"] or p["mt"] <= 5, what
+                    assert not (p["ring"] and p["ksplit"] > 1) or (d + 511) // 512 // p["ksplit"] >= 3, what
                     assert p["ring"] or p["tile"] in (64, 128), what
                     if p["ksplit"] > 1:
                         assert (d // 64) // p["ksplit"] >= 1, what

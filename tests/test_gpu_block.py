@@ -120,25 +120,23 @@ def test_linear_segments(dtype, B, T, d_in, heads, dh, segments, x_heads):
         assert lib.tree_linear_segments(*args(7, y[0].numel())) != 0             # no whole heads per segment
 
 
-def test_linear_bf16_cold_weights_kernel():
-    # up to 80 rows, weights declared cold: the kernel that fetches 1 KB runs into an LDS ring, with the
-    # gated epilogue, head-major activations on both sides and tiles of 128, 96, 64 and 48 columns
-    M.medusa_set_cache_resident_bytes(0)
-    try:
-        linear_case("bf16", 1, 65, 192, 25600, 0, 0, True, 430)
-        linear_case("bf16", 2, 33, 256, 25600, 2, 200, False, 431)
-        linear_case("bf16", 1, 10, 1024, 25610, 8, 0, True, 432)
-        linear_case("bf16", 1, 65, 576, 19200, 0, 150, True, 433)        # 96 columns per workgroup
-        linear_case("bf16", 1, 70, 1024, 12800, 8, 100, False, 434)      # 64
-        linear_case("bf16", 1, 33, 320, 9600, 0, 0, True, 435)           # 48
-        # narrow outputs: the same kernel with its reduction split over workgroups
-        for rows, d_in, d_out, want in ((16, 11776, 4352, (128, 4)), (65, 2752, 4096, (64, 4)), (16, 4096, 1024, (64, 8)),
-                                        (40, 1536, 520, (64, 2))):
-            plan = M.medusa_gemm_plan(rows, d_out, d_in, 1, True)
-            assert plan["ring"] and (plan["tile"], plan["ksplit"]) == want, plan
-            linear_case("bf16", 1, rows, d_in, d_out, 0, 0, d_in == 4096, 436 + rows)
-    finally:
-        M.medusa_set_cache_resident_bytes(256 << 20)
+def test_linear_bf16_ring_kernel():
+    # up to 80 rows: the kernel that fetches 1 KB runs into an LDS ring, with the gated epilogue,
+    # head-major activations on both sides and tiles of 128, 96, 64 and 48 columns
+    linear_case("bf16", 1, 65, 192, 25600, 0, 0, True, 430)
+    linear_case("bf16", 2, 33, 256, 25600, 2, 200, False, 431)
+    linear_case("bf16", 1, 10, 1024, 25610, 8, 0, True, 432)
+    linear_case("bf16", 1, 65, 576, 19200, 0, 150, True, 433)        # 96 columns per workgroup
+    linear_case("bf16", 1, 70, 1024, 12800, 8, 100, False, 434)      # 64
+    linear_case("bf16", 1, 33, 320, 9600, 0, 0, True, 435)           # 48
+    # narrow outputs over a long reduction: the same kernel with its reduction split over workgroups;
+    # a short reduction stays with the register-staged split kernel
+    for rows, d_in, d_out, want in ((16, 3072, 4224, (True, 64, 2)), (65, 6144, 2176, (True, 64, 4)), (40, 12288, 256, (True, 64, 8)),
+                                    (65, 6144, 4224, (True, 96, 4)), (16, 11776, 6272, (True, 128, 4)),
+                                    (65, 2752, 4096, (False, 64, 2)), (16, 4096, 1024, (False, 64, 4))):
+        plan = M.medusa_gemm_plan(rows, d_out, d_in, 1, True)
+        assert (plan["ring"], plan["tile"], plan["ksplit"]) == want, plan
+        linear_case("bf16", 1, rows, d_in, d_out, 0, 0, d_in == 4096, 436 + rows)
 
 
 def interleave16(wg, wu):
@@ -170,12 +168,8 @@ def test_linear_swiglu_bf16(B, T, d_in, d_out, x_heads, y_heads, cold):
     assert torch.equal(w_gu, M.interleave_gate_up(to_dev(wg), to_dev(wu)))
     if M_rows > 100 and d_out >= 2560:
         assert M.medusa_gemm_plan(M_rows, 2 * d_out, d_in, 1, False)["kind"] == "big"      # (the case is here for that kernel)
-    M.medusa_set_cache_resident_bytes(0 if cold else 256 << 20)
-    try:
-        y = M.tree_linear_swiglu(xd, w_gu, B, T, y_heads=y_heads)
-        torch.cuda.synchronize()
-    finally:
-        M.medusa_set_cache_resident_bytes(256 << 20)
+    y = M.tree_linear_swiglu(xd, w_gu, B, T, y_heads=y_heads)
+    torch.cuda.synchronize()
     got = to_host_f64(y)
     if y_heads:
         got = got.transpose(0, 2, 1, 3).reshape(M_rows, d_out)

@@ -49,21 +49,17 @@ def test_bf16_odd_step_counts(M_rows, d, V, K):
     run_case("bf16", M_rows, d, V, K, False, 80 + M_rows)
 
 
-# Weights that come from HBM rather than from the last-level cache have a kernel of their own (1 KB runs
-# per weight row straight into an LDS ring, super-stages of 512 elements, tiles of 48 to 128 columns).
-# The library picks it for weight matrices above a size threshold; with the threshold at zero the
-# same shapes as above -- row groups 1..5, ragged last tile, one to several super-stages, partial
-# last one, every tile width (250 / 200 / 200 / 201 workgroups) -- run through it.
+# Up to 80 rows per block with 160 tiles or more: the kernel that fetches 1 KB runs per weight row
+# straight into an LDS ring (super-stages of 512 elements, tiles of 48 to 128 columns).  Row groups
+# 1..5, ragged last tile, one to several super-stages, partial last one, every tile width
+# (250 / 200 / 200 / 201 workgroups in the last four cases).
 @pytest.mark.parametrize("M_rows,d,V,K", [(70, 192, 12800, 2), (120, 448, 12900, 2), (33, 704, 25700, 1),
                                           (5, 512, 25600, 1), (17, 1024, 6400, 4), (48, 1600, 12803, 2),
                                           (64, 64, 25600, 1), (80, 2560, 25601, 1),
                                           (65, 1088, 19190, 1), (40, 576, 12790, 1), (75, 512, 9640, 1)])
-def test_bf16_cold_weights_kernel(M_rows, d, V, K):
-    M.medusa_set_cache_resident_bytes(0)
-    try:
-        run_case("bf16", M_rows, d, V, K, False, 90 + M_rows)
-    finally:
-        M.medusa_set_cache_resident_bytes(256 << 20)
+def test_bf16_ring_kernel(M_rows, d, V, K):
+    assert M.medusa_gemm_plan(M_rows, V, d, K, False)["ring"] or M_rows > 80
+    run_case("bf16", M_rows, d, V, K, False, 90 + M_rows)
 
 
 @pytest.mark.parametrize("M_rows", [1, 3, 4, 10])
