@@ -542,8 +542,8 @@ __global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// bf16, 4 < M <= 80, weights that come from HBM: the weights of a tile are fetched in 1 KB runs and
-// nothing passes through registers on its way to LDS.
+// bf16, 4 < M <= 80 per row block (the ring kernel): the weights of a tile are fetched in 1 KB runs
+// and nothing passes through registers on its way to LDS.
 //
 // Cold weights stream from HBM at 4.4 TB/s when a workgroup asks for 256 bytes of each of its 128
 // rows at a time, at 5.3 TB/s for 1 KB of 32 rows (measured with a plain read kernel), so the
@@ -786,17 +786,20 @@ __global__ __launch_bounds__(256) void gemm_ring_bf16_kernel(GemmArgs a) {
 //   M > 80     128 x 128 tiles (wavefronts 2 x 2, unsplit) or the large-tile kernel (gemm_big.hip)
 //              with 128 or 192 x 256 tiles, whichever a small cost model prices lowest (below); if
 //              none of them has enough tiles, as for fewer rows:
-//   otherwise  a skinny arrangement: row blocks of 16*mt <= 128 activation rows, 128 weight rows per
-//              workgroup when that alone gives 200 workgroups (and mt <= 5), else 64; unsplit: the
-//              kernel whose wavefronts split the reduction; with under 160 tiles and a workspace:
-//              the kernel whose wavefronts split the weight rows, its reduction split over 2-8
-//              workgroups (at M = 356 and 1040 the skinny arrangement was up to 1.5x faster than
-//              128 x 128 tiles below 200 of those and up to 1.6x slower above; splitting the
-//              128 x 128 kernel's reduction never paid for its 64 KB partials).
+//   otherwise  a skinny arrangement: row blocks of 16*mt <= 128 activation rows.  Up to 80 rows per
+//              block (mt <= 5): the ring kernel -- unsplit on tiles of 128, 96, 64 or 48 columns when
+//              one of these widths gives 160 workgroups, else, with a workspace and a reduction long
+//              enough, split over 2-8 workgroups per tile.  Everything else: the register-staged
+//              kernels on 64-column tiles -- unsplit, the one whose wavefronts split the reduction;
+//              with under 160 tiles and a workspace, the one whose wavefronts split the weight
+//              rows, its reduction split over 2-8 workgroups (at M = 356 and 1040 the skinny
+//              arrangement was up to 1.5x faster than 128 x 128 tiles below 200 of those and up to
+//              1.6x slower above; splitting the 128 x 128 kernel's reduction never paid for its
+//              64 KB partials).
 struct GemmPlan {
   enum { GEMV, SKINNY, SQUARE, BIG } kind;
-  bool wide;
-  bool ring;            // skinny tiles of 16*ntw columns: the kernel for cold weights (1 KB runs straight into an LDS ring)
+  bool wide;            // skinny: 128-column tiles; large tiles: 192 activation rows
+  bool ring;            // skinny: the ring kernel (1 KB runs per weight row straight into an LDS ring)
   int ntw;              // skinny: column fragments (16 weight rows each) per workgroup
   int mt, m_blocks, ksplit;
 };
