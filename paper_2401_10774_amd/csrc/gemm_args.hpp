@@ -30,6 +30,7 @@ struct GemmArgs {
   int y_seg_heads;     // > 0: the head-major output is several tensors [B][y_heads][y_T][y_dh], y_seg_stride elements apart,
   long y_seg_stride;   //      each taking y_seg_heads (= y_heads) consecutive heads of the N columns (Q, K, V of one projection call)
   int rows_per_wg;     // GEMV kernels: weight rows per workgroup (multiple of 8)
+  int m_blocks;        // ring kernel: row blocks (its grid.x interleaves them with the column tiles, see there)
   int ksplit;          // skinny MFMA kernel: workgroups that share one output tile, each reducing 1/ksplit of d
   void* ws;            // their fp32 partial tiles (ksplit > 1)
   int ticket_slot;     // which set of ticket counters a split reduction uses (one per stream, see common.hpp)

@@ -592,8 +592,16 @@ __global__ __launch_bounds__(256) void gemm_ring_bf16_kernel(GemmArgs a) {
   const int k = blockIdx.y;
   // Split reduction (a template switch, as above): ksplit workgroups share a tile, each taking a
   // contiguous share of the super-stages (at least one: the host's business).
-  const int n_split = SPLIT ? a.ksplit : 1, m_tile = blockIdx.z / n_split, split = blockIdx.z - m_tile * n_split;
-  const int n0 = blockIdx.x * BN, m0 = m_tile * BM;
+  const int n_split = SPLIT ? a.ksplit : 1, split = SPLIT ? (int)blockIdx.z : 0;
+  // Row blocks of one column tile get workgroup ids 8 apart, which the hardware places on one die: the
+  // first block's weights come from HBM, the others find them in that die's L2.  (With ids a whole
+  // row of column tiles apart they land on different dies whenever the column tiles are no multiple
+  // of 8, and every block streams the weights from HBM: N = 11008, 2 x 65 rows 44 against 34 us.)
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int col_tile = a.m_blocks > 1 ? (slot / a.m_blocks) * 8 + xcd : (int)blockIdx.x;
+  const int m_tile = a.m_blocks > 1 ? slot % a.m_blocks : 0;
+  const int n0 = col_tile * BN, m0 = m_tile * BM;
+  if (n0 >= a.N) return;                               // (the whole workgroup, before any barrier)
   const unsigned char* Wt = (const unsigned char*)((const uint16_t*)a.W + ((size_t)k * a.N + n0) * a.d);
   const unsigned char* Xb = (const unsigned char*)a.X;
   const int n_super = (a.d + 511) >> 9;
@@ -601,7 +609,7 @@ __global__ __launch_bounds__(256) void gemm_ring_bf16_kernel(GemmArgs a) {
   const int n_mine = (int)((long)n_super * (split + 1) / n_split) - s_first, total = n_mine * NTW;
   const int c_last = ((a.d - (n_super - 1) * 512) >> 3) - 1;   // last valid chunk of the last super-stage
   // every workgroup starts its share of the reduction at a different super-stage and wraps around (see the kernel above)
-  const int rot = (int)((blockIdx.x * 3u) % (unsigned)n_mine);
+  const int rot = (int)(((unsigned)col_tile * 3u) % (unsigned)n_mine);
   auto rotated = [&](int S) { const int Sr = S + rot; return s_first + (Sr >= n_mine ? Sr - n_mine : Sr); };
 
   // Rows this wavefront fetches: weight rows 16 j + 4 i + wave of the tile, activation rows 4 q + wave
@@ -736,7 +744,7 @@ __global__ __launch_bounds__(256) void gemm_ring_bf16_kernel(GemmArgs a) {
     }
   }
   if (SPLIT && n_split > 1) {
-    const unsigned int tile = (k * gridDim.x + blockIdx.x) * (gridDim.z / n_split) + m_tile;
+    const unsigned int tile = k * gridDim.x + blockIdx.x;
     constexpr int PART = NU * PER * 2 * 256;             // 8-byte words per partial tile
     uint64_t* part = (uint64_t*)a.ws + (size_t)tile * n_split * PART;
 #pragma unroll
@@ -796,6 +804,12 @@ __global__ __launch_bounds__(256) void gemm_ring_bf16_kernel(GemmArgs a) {
 //              arrangement was up to 1.5x faster than 128 x 128 tiles below 200 of those and up to
 //              1.6x slower above; splitting the 128 x 128 kernel's reduction never paid for its
 //              64 KB partials).
+// Workgroups along x of a ring kernel launch: the column tiles, or -- with several row blocks -- groups of
+// 8 column tiles x row blocks (see the kernel), the last group padded.
+inline int ring_grid_x(int N, int ntw, int m_blocks) {
+  const int cols = ceil_div(N, 16 * ntw);
+  return m_blocks > 1 ? 8 * ceil_div(cols, 8) * m_blocks : cols;
+}
 struct GemmPlan {
   enum { GEMV, SKINNY, SQUARE, BIG } kind;
   bool wide;            // skinny: 128-column tiles; large tiles: 192 activation rows
@@ -912,23 +926,56 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
   }
   p.wide = false;
   p.ntw = 4;                                                // (the register-staged kernels below: 64-column tiles)
-  // Up to 80 rows per block: the ring kernel, unsplit, with the tile width that prices lowest -- rounds
-  // of 256 workgroups x (column fragments + the activation rows every workgroup fetches, which cost
-  // about a quarter of their bytes, + one fragment's worth of start and end) -- among those that give
-  // at least 160 workgroups.  Narrower outputs get a split reduction below.  (Measured against the
-  // register-staged kernels at M = 16..80 on 7B and 13B projection shapes and the LM head: 7-30 %
-  // faster on weights from HBM, equal within 3 % on weights the last-level cache holds.)
-  if (p.mt <= 5) {
+  // The ring kernel takes up to 80 rows per block, or up to 160 rows as two blocks (the blocks of a
+  // weight tile run side by side on one die and share its trip from HBM; with three or four blocks the
+  // register-staged kernels below measured faster: N = 5120, d = 13824, M = 200 90 against 105 us).
+  // Candidates, priced in units of one sub-stage (16 rows x 1 KB, roughly 0.6 us):
+  //   unsplit, on tiles of 128, 96, 64 or 48 columns that give at least 160 workgroups: super-stages x
+  //     rounds of 256 workgroups x (column fragments + the activation rows every workgroup fetches,
+  //     which cost about a quarter of their bytes), + 2 for start and end;
+  //   with a workspace, the reduction split over 2, 4 or 8 workgroups per tile of 128, 96 or 64 columns,
+  //     at most one workgroup per CU in all: the longest share of super-stages x the same, + 5 for
+  //     start, election and end, + the partial tiles the last workgroup fetches alone (splits x tile
+  //     bytes, at what one CU can pull).  If the cheapest split leaves a workgroup under three
+  //     super-stages the ring never fills (N = d = 4096: 21.5 us, 18.6 us below): no split candidate then.
+  // Measured at M = 65 on MI355X: N = 12288, d = 4096 as 256 tiles of 48 columns 27.6 us (register-staged:
+  // 35.7); N = 4096, d = 11008 as 64 columns x 4 splits 31 us, 128 x 8 40, 128 x 4 49 (register-staged
+  // split: 34.5); at M = 97..160 the same matrix as 2 blocks x 64 columns x 2 splits 40-44 us (unsplit on
+  // 48 columns 47-54, register-staged 41-55).  Against the register-staged kernels at M = 16..80 on 7B
+  // and 13B projection shapes and the LM head: 7-30 % faster on weights from HBM, equal within 3 % on
+  // weights the last-level cache holds.
+  const int ring_blocks = p.mt <= 5 ? p.m_blocks : ceil_div(M, 80), ring_mt = ceil_div(ceil_div(M, ring_blocks), 16);
+  if (ring_blocks <= 2 || p.mt <= 5) {
+    const int n_super = (d + 511) / 512;
+    const double per_stage = 0.25 * ring_mt;
     double best = 1e30;
+    int ntw = 0, ks_best = 1;
     static const int widths[4] = {8, 6, 4, 3};
     for (int wi = 0; wi < 4; ++wi) {
-      const long t = (long)ceil_div(N, 16 * widths[wi]) * K * p.m_blocks;
+      const long t = (long)ceil_div(N, 16 * widths[wi]) * K * ring_blocks;
       if (t < 160) continue;
-      const double cost = (double)((t + 255) / 256) * (widths[wi] + 0.25 * p.mt + 1.0);
-      if (cost < best) { best = cost; p.ntw = widths[wi]; p.ring = true; }
+      const double cost = (double)n_super * (double)((t + 255) / 256) * (widths[wi] + per_stage) + 2.0;
+      if (cost < best) { best = cost; ntw = widths[wi]; ks_best = 1; }
     }
-    if (p.ring) {
-      p.wide = p.ntw == 8;
+    if (have_ws) {
+      double best_split = 1e30;
+      int s_ntw = 0, s_ks = 0;
+      for (int w = 8; w >= 4; w -= 2)
+        for (int ks = 2; ks <= 8; ks *= 2) {
+          const long t = (long)ceil_div(N, 16 * w) * K * ring_blocks;
+          if (t * ks > 256 || ks > n_super) continue;
+          const double cost = (double)ceil_div(n_super, ks) * (w + per_stage) + 5.0 + ks * ring_mt * w / 16.0;
+          if (cost < best_split) { best_split = cost; s_ntw = w; s_ks = ks; }
+        }
+      if (s_ks > 1 && n_super / s_ks >= 3 && best_split < best) { best = best_split; ntw = s_ntw; ks_best = s_ks; }
+    }
+    if (ntw) {
+      p.ring = true;
+      p.ntw = ntw;
+      p.wide = ntw == 8;
+      p.ksplit = ks_best;
+      p.m_blocks = ring_blocks;
+      p.mt = ring_mt;
       return p;
     }
   }
@@ -949,34 +996,6 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
     }
     return p;
   }
-  // Up to 80 rows per block and a reduction long enough to give every workgroup three 512-element
-  // super-stages: the ring kernel with its reduction split, on 128-, 96- or 64-column tiles, over 2, 4
-  // or 8 workgroups per tile, at most one workgroup per CU in all.  Priced in units of one sub-stage
-  // (16 rows x 1 KB, about 0.75 us): the longest share of super-stages x (column fragments + a quarter
-  // of the row groups, as above), five for start, election and end, and the partial tiles the last
-  // workgroup fetches alone -- splits x tile bytes, at what one CU can pull.  N = 4096, d = 11008,
-  // M = 65 on MI355X: 64 columns x 4 splits 31 us, 128 x 8 40 us, 128 x 4 49 us (the register-staged
-  // kernel below: 34.5 us).  Shorter shares never fill the ring: N = d = 4096 runs 21.5 us this way,
-  // 18.6 us below.
-  if (p.mt <= 5) {
-    const int n_super = (d + 511) / 512;
-    double best = 1e30;
-    int share = 0;
-    for (int w = 8; w >= 4; w -= 2)
-      for (int ks = 2; ks <= 8; ks *= 2) {
-        const long t = (long)ceil_div(N, 16 * w) * K * p.m_blocks;
-        if (t * ks > 256 || ks > n_super) continue;
-        const double cost = (double)ceil_div(n_super, ks) * (w + 0.25 * p.mt) + 5.0 + ks * p.mt * w / 16.0;
-        if (cost < best) { best = cost; p.ntw = w; p.ksplit = ks; share = n_super / ks; }
-      }
-    if (share >= 3) {
-      p.ring = true;
-      p.wide = p.ntw == 8;
-      return p;
-    }
-    p.ntw = 4;
-    p.ksplit = 1;
-  }
   long cap = 640 / tiles;
   const long by_steps = (d / 64) / 16;
   cap = cap < by_steps ? cap : by_steps;
@@ -992,7 +1011,7 @@ size_t gemm_ws_bytes(int M, int N, int d, int K) {
   }
   if (p.kind != GemmPlan::SKINNY || p.ksplit <= 1) return 0;
   if (p.ring)                                               // per workgroup: ceil(mt*ntw/4) fragments per thread
-    return (size_t)ceil_div(N, 16 * p.ntw) * K * p.m_blocks * p.ksplit * ceil_div(p.mt * p.ntw, 4) * 4 * 256 * sizeof(float);
+    return (size_t)ring_grid_x(N, p.ntw, p.m_blocks) * K * p.ksplit * ceil_div(p.mt * p.ntw, 4) * 4 * 256 * sizeof(float);
   return (size_t)ceil_div(N, 64) * K * p.m_blocks * p.ksplit * p.mt * 4 * 256 * sizeof(float);   // mt accumulator fragments per thread
 }
 
@@ -1065,7 +1084,10 @@ int launch_gemm(const GemmArgs& a_in, int dtype, hipStream_t stream) {
     constexpr bool kCanSplit = EPI == EPI_PLAIN || EPI == EPI_GATED;
     const bool split = kCanSplit && a.ksplit > 1;
     if (!split) a.ksplit = 1;
-    const dim3 grid(ceil_div(a.N, plan.kind == GemmPlan::SKINNY ? 16 * plan.ntw : 128), a.K, plan.m_blocks * a.ksplit);
+    a.m_blocks = plan.m_blocks;
+    const dim3 grid = plan.kind == GemmPlan::SKINNY && plan.ring
+                          ? dim3(ring_grid_x(a.N, plan.ntw, plan.m_blocks), a.K, a.ksplit)
+                          : dim3(ceil_div(a.N, plan.kind == GemmPlan::SKINNY ? 16 * plan.ntw : 128), a.K, plan.m_blocks * a.ksplit);
     if (plan.kind == GemmPlan::SQUARE) {
       hipLaunchKernelGGL((gemm_lds_bf16_kernel<2, 2, 4, 4, 64, 2, EPI, false>), grid, block, 0, stream, a);
       MEDUSA_LAUNCH_CHECK();
@@ -1325,7 +1347,8 @@ extern "C" int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int 
       if ((t >= 160 || w == 8) && cost < best) { best = cost; ntw = w; }
     }
   }
-  const dim3 grid(ceil_div(a.N, 16 * ntw), 1, m_blocks);
+  a.m_blocks = m_blocks;
+  const dim3 grid(ring_grid_x(a.N, ntw, m_blocks), 1, 1);
   int rc = MEDUSA_OK;
 #define MEDUSA_SWIGLU(MT_)                                                                                                \
   case MT_: {                                                                                                             \
