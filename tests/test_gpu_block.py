@@ -129,10 +129,14 @@ def test_linear_bf16_ring_kernel():
     linear_case("bf16", 1, 65, 576, 19200, 0, 150, True, 433)        # 96 columns per workgroup
     linear_case("bf16", 1, 70, 1024, 12800, 8, 100, False, 434)      # 64
     linear_case("bf16", 1, 33, 320, 9600, 0, 0, True, 435)           # 48
+    assert M.medusa_gemm_plan(130, 6400, 1024, 1, True)["m_blocks"] == 2
+    linear_case("bf16", 2, 65, 1024, 6400, 8, 50, False, 445)        # two row blocks (interleaved with the column tiles), head-major both sides
+    linear_case("bf16", 1, 150, 3072, 4224, 0, 0, True, 446)         # two row blocks, ragged second one, 88 column tiles (no multiple of 8)
     # narrow outputs over a long reduction: the same kernel with its reduction split over workgroups;
     # a short reduction stays with the register-staged split kernel
     for rows, d_in, d_out, want in ((16, 3072, 4224, (True, 64, 2)), (65, 6144, 2176, (True, 64, 4)), (40, 12288, 256, (True, 64, 8)),
                                     (65, 6144, 4224, (True, 96, 4)), (16, 11776, 6272, (True, 128, 4)),
+                                    (97, 11008, 4096, (True, 64, 2)), (97, 6144, 2048, (True, 64, 2)),      # ... with two and four row blocks
                                     (65, 2752, 4096, (False, 64, 2)), (16, 4096, 1024, (False, 64, 4))):
         plan = M.medusa_gemm_plan(rows, d_out, d_in, 1, True)
         assert (plan["ring"], plan["tile"], plan["ksplit"]) == want, plan
