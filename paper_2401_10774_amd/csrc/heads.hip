@@ -6,9 +6,11 @@
 //   * M <= 4  (bf16): one wavefront per weight row, 16-byte non-temporal loads that cover
 //                     1 KB of the row per instruction, packed bf16 dot products on the
 //                     vector ALUs, activations resident in LDS.
-//   * M  > 4  (bf16): 16x16x32 bf16 MFMA tiles fed from a double-buffered LDS tile that is
-//                     filled with full-line loads several reduction steps ahead; up to 80
-//                     activation rows x 128 weight rows per workgroup (128 x 128 for M > 80).
+//   * M  > 4  (bf16): 16x16x32 bf16 MFMA tiles.  Up to 80 activation rows per row block: 1 KB runs
+//                     of 48-128 weight rows go from global memory straight into an LDS ring (the
+//                     ring kernel); larger row blocks and short split reductions: a double-buffered
+//                     LDS tile filled through registers several reduction steps ahead; from about
+//                     a hundred rows on, 128 x 128 tiles or the large tiles of gemm_big.hip.
 //   * fp32          : plain FMA version of the first scheme (small configurations only).
 // The residual block's epilogue applies SiLU, adds h and rounds once to the storage type.
 #include "gemm_args.hpp"
@@ -1032,8 +1034,8 @@ constexpr int skinny_depth(int mt, int ntw) { return mt + ntw <= 13 ? 3 : 2; }
 // Weight buffers of the ring kernel: what 160 KB of LDS hold beside the activation slab, at most 8.
 constexpr int ring_depth(int mt) { return mt >= 5 ? 5 : (10 - mt > 8 ? 8 : 10 - mt); }
 
-// The skinny kernel's LDS tile exceeds the 64 KB a kernel gets by default: raise the limit once per
-// kernel and device.
+// The skinny kernels' LDS tiles exceed the 64 KB a kernel gets by default (the ring kernel takes all
+// 160 KB of a CU): raise the limit once per kernel and device.
 template <void (*Kernel)(GemmArgs)>
 int launch_skinny(dim3 grid, size_t lds, hipStream_t stream, const GemmArgs& a) {
   static bool raised[64] = {};
