@@ -56,6 +56,10 @@ def parse_args():
     ap.add_argument("--block", action="store_true",
                     help="time the simplified decoder block of App. G on the tree tokens instead of the verification "
                          "step (its own JSON line; the headline metric stays the verification step)")
+    ap.add_argument("--forward", action="store_true",
+                    help="time the whole verification pass with a stack of --layers simplified decoder blocks in place "
+                         "of the single attention call (heads -> top-k/tree -> blocks -> LM head -> acceptance -> commit)")
+    ap.add_argument("--layers", type=int, default=0, help="--forward: decoder blocks in the stack (default: the workload's layer count)")
     ap.add_argument("--speed-model", action="store_true",
                     help="measure the simplified block at 1..112 candidate tokens and print the appendix's simulated "
                          "speedup for this GPU (its own JSON line)")
@@ -112,6 +116,9 @@ def main():
         return
     if args.speed_model:
         bench_speed_model(args, cfg)
+        return
+    if args.forward:
+        bench_forward(args, cfg)
         return
 
     t0 = time.time()
@@ -400,6 +407,94 @@ def bench_block(args, cfg):
         "block_hbm": {"algorithmic_bytes": total, "achieved_GBps": round(total / ms / 1e6, 1),
                       "frac_of_peak": round(total / ms / 1e6 / HBM_PEAK_GBS, 4)},
         "block_flops": {"useful_TFLOPs": round(flops / ms / 1e9, 1)},
+    }), flush=True)
+
+
+def bench_forward(args, cfg):
+    """One step = one whole verification pass of a backbone-shaped stack: medusa_heads, top-k and tree,
+    NL simplified decoder blocks on the tree tokens (each streaming its own weights, attending its own
+    cache layer and leaving the tree tokens' K and V for the commit), the LM head on the last block's
+    output, acceptance, and the commit of all NL layers.  Synthetic weights; no embedding, norms or
+    residual stream (out of scope), so the accept lengths are those of random logits."""
+    import numpy as np
+    import torch
+
+    import paper_2401_10774_amd as M
+    from paper_2401_10774_amd.forward import TreeBackbone, alloc_qkv
+    from paper_2401_10774_amd.step import VerificationStep
+    from workloads import make_step_inputs, scaled_config
+
+    NL = args.layers or cfg.NL
+    if NL != cfg.NL:
+        cfg = scaled_config(cfg.name, NL=NL)
+    inter = {4096: 11008, 5120: 13824}.get(cfg.d, ((cfg.d * 8 // 3 + 255) // 256) * 256)
+    dt, es = torch.bfloat16, 2
+    if cfg.dtype != "bf16":
+        print("bench.py --forward: bf16 workloads only", file=sys.stderr)
+        sys.exit(2)
+    tree = M.MedusaTree(branching=cfg.branching)
+    B, T, h, Hq, Hkv, D, V = cfg.B, tree.T, cfg.d, cfg.Hq, cfg.Hkv, cfg.D, cfg.V
+    x = make_step_inputs(cfg, names=[n for n in ("h_last", "hidden_tree", "w1", "w2", "w_lm", "k_cache", "v_cache", "prefix_len")])
+
+    def dev(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+        return torch.from_numpy(a).cuda()
+
+    tensors = {k: dev(v) for k, v in x.items()}
+    q, k_tree, v_tree = alloc_qkv(NL, B, Hq, Hkv, T, D, dt)
+    tensors["q"], tensors["k_tree"], tensors["v_tree"] = q[0], k_tree, v_tree
+    step = VerificationStep(tensors, tree, cfg.accept, cfg.temperature, cfg.eps, cfg.delta)
+    step.prepare()
+    step.commit_out_of_place()
+    gen = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    rnd = lambda *shape, std=1.0: (torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32) * std).to(dt)
+    weights = []
+    for _ in range(NL):
+        wg, wu = rnd(inter, Hq * D, std=(Hq * D) ** -0.5), rnd(inter, Hq * D, std=(Hq * D) ** -0.5)
+        weights.append({"w_qkv": rnd((Hq + 2 * Hkv) * D, h, std=h ** -0.5), "w_gu": M.interleave_gate_up(wg, wu),
+                        "wd": rnd(h, inter, std=inter ** -0.5)})
+        if not (B * T <= 160 or M.medusa_gemm_plan(B * T, 2 * inter, Hq * D, 1, False)["kind"] == "big"):
+            weights[-1]["wu"], weights[-1]["wg"] = wu, wg
+        del wg, wu
+    bb = TreeBackbone(tree, B, h, Hq, Hkv, D, inter, cfg.Lcap, weights, q, k_tree, v_tree, tensors["k_cache"], tensors["v_cache"],
+                      tensors["prefix_len"], step.position_ids)
+    x0 = rnd(B * T, h)
+    hidden_rows = tensors["hidden_tree"].view(B * T, h)
+    backbone = lambda: bb.run(x0, hidden_rows)
+    K, W = args.steps, args.warmup
+    for _ in range(W):
+        step.run(backbone=backbone)
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(K):
+        step.run(backbone=backbone)
+    stop.record()
+    torch.cuda.synchronize()
+    ms = start.elapsed_time(stop) / K
+    accept_len = step.accept_out[0].cpu().numpy()
+    finite = bool(torch.isfinite(step.verify_logits).all())
+    mean_L = float(np.mean(x["prefix_len"]))
+    M_rows = B * T
+    layer_w = ((Hq + 2 * Hkv) * D * h + 2 * inter * Hq * D + h * inter) * es
+    layer_act = (M_rows * h + M_rows * (Hq + 2 * Hkv) * D * 3 + M_rows * Hq * D * 2 + 2 * M_rows * inter + M_rows * h) * es
+    layer_kv = int(2 * B * Hkv * mean_L * D * es)
+    step_parts = step.algorithmic_bytes(mean_L, float(accept_len.mean()))
+    total = NL * (layer_w + layer_act + layer_kv) + step_parts["total"] - step_parts["attention"]
+    print(json.dumps({
+        "metric": "verification passes/s of a backbone-shaped stack (heads, tree, NL simplified blocks, LM head, acceptance, commit)",
+        "value": round(1e3 / ms, 2), "unit": "passes/s", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name} shapes, {NL} layers: B={B} T={T} h={h} inter={inter} heads={Hq}/{Hkv}x{D} V={V} "
+                               f"prefix=[{cfg.L_min},{cfg.L_max}]",
+                   "note": "every layer has its own weights (no rotation needed: the stack is larger than any cache); no "
+                           "embedding, norms, output projection or residual stream"},
+        "pass_hbm": {"algorithmic_bytes": int(total), "achieved_GBps": round(total / ms / 1e6, 1),
+                     "frac_of_peak": round(total / ms / 1e6 / HBM_PEAK_GBS, 4)},
+        "mean_accept_len": round(float(accept_len.mean()), 3), "logits_finite": finite,
+        "tokens_per_s_at_accept_len": {"measured (random weights)": round(float(accept_len.mean()) * 1e3 / ms, 1),
+                                       "3.0 (the paper's trained heads, for scale)": round(3.0 * 1e3 / ms, 1)},
     }), flush=True)
 
 

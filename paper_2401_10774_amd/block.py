@@ -43,18 +43,28 @@ class SimplifiedBlock:
         self.ws_lin = _b._scratch(need, device)
         self._plans = {}
 
-    def _calls(self, x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale, w_gu=None):
-        key = tuple(t.data_ptr() for t in (x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids)) + (
-            scale, None if w_gu is None else w_gu.data_ptr())
+    def _calls(self, x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale, w_gu=None, qkv=None, out=None):
+        key = tuple(None if t is None else t.data_ptr() for t in (x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids)) + (
+            scale, None if w_gu is None else w_gu.data_ptr(), None if qkv is None else tuple(t.data_ptr() for t in qkv),
+            None if out is None else out.data_ptr())
         plan = self._plans.get(key)
         if plan is not None:
             return plan
         dt = self.q.dtype
         B, T, h, Hq, Hkv, D, inter = self.B, self.T, self.h, self.Hq, self.Hkv, self.D, self.inter
+        q_buf, k_buf, v_buf = (self.q, self.k, self.v) if qkv is None else qkv
+        out_buf = self.out if out is None else out
+        if qkv is not None:
+            _b._dev(q_buf, "q", dtype=dt, shape=(B, Hq, T, D))
+            _b._dev(k_buf, "k", dtype=dt, shape=(B, Hkv, T, D))
+            _b._dev(v_buf, "v", dtype=dt, shape=(B, Hkv, T, D))
+        if out is not None:
+            _b._dev(out_buf, "out", dtype=dt, shape=(B * T, h))
         _b._dev(x, "x", dtype=dt, shape=(B * T, h))
         for name, w, shape in (("wq", wq, (Hq * D, h)), ("wk", wk, (Hkv * D, h)), ("wv", wv, (Hkv * D, h)),
                                ("wu", wu, (inter, Hq * D)), ("wg", wg, (inter, Hq * D)), ("wd", wd, (h, inter))):
-            _b._dev(w, name, dtype=dt, shape=shape)
+            if w is not None or name not in ("wu", "wg"):        # (w_u and w_g may be left out when w_gu serves)
+                _b._dev(w, name, dtype=dt, shape=shape)
         _b._dev(k_cache, "k_cache", dtype=dt, shape=(B, Hkv, self.Lcap, D))
         _b._dev(v_cache, "v_cache", dtype=dt, shape=(B, Hkv, self.Lcap, D))
         _b._dev(prefix_len, "prefix_len", dtype=torch.int32, shape=(B,))
@@ -65,23 +75,31 @@ class SimplifiedBlock:
             "tree_linear", L.tree_linear, (p(xin), p(w), None if mul is None else p(mul), p(y), B, T, d_in, d_out, xh, yh,
                                            code, p(self.ws_lin), nb(self.ws_lin)))
         nbytes = lambda t: t.numel() * t.element_size()
-        seg = lambda w, y, d_out, yh, n_seg: (
-            "tree_linear_segments", L.tree_linear_segments, (p(x), p(w), None, p(y), B, T, h, d_out, 0, yh, n_seg, y[0].numel(),
+        # several head-major outputs of one projection call: segment s lands `stride` elements after segment s - 1
+        seg = lambda w, y, stride, d_out, yh, n_seg: (
+            "tree_linear_segments", L.tree_linear_segments, (p(x), p(w), None, p(y), B, T, h, d_out, 0, yh, n_seg, stride,
                                                              code, p(self.ws_lin), nb(self.ws_lin)))
         kv_adjacent = wv.data_ptr() == wk.data_ptr() + nbytes(wk)
         qkv_adjacent = kv_adjacent and wk.data_ptr() == wq.data_ptr() + nbytes(wq)
-        if self.qkv is not None and qkv_adjacent:      # one sequence: q, k, v are head ranges of one head-major tensor
+        es = q_buf.element_size()
+        kv_stride = (v_buf.data_ptr() - k_buf.data_ptr()) // es      # caller-owned q, k, v: equally spaced tensors can share a call
+        qk_stride = (k_buf.data_ptr() - q_buf.data_ptr()) // es
+        if qkv is None and self.qkv is not None and qkv_adjacent:      # one sequence: q, k, v are head ranges of one head-major tensor
             qkv_calls = [lin(x, wq, None, self.qkv, h, (Hq + 2 * Hkv) * D, 0, Hq + 2 * Hkv)]
-        elif B > 1 and Hq == Hkv and qkv_adjacent:     # a batch: three tensors, one call over the stacked weight rows
-            qkv_calls = [seg(wq, self.qkv3, 3 * Hq * D, Hq, 3)]
-        elif B > 1 and Hq != Hkv and kv_adjacent:
-            qkv_calls = [lin(x, wq, None, self.q, h, Hq * D, 0, Hq), seg(wk, self.kv2, 2 * Hkv * D, Hkv, 2)]
+        elif qkv is None and B > 1 and Hq == Hkv and qkv_adjacent:     # a batch: three tensors, one call over the stacked weight rows
+            qkv_calls = [seg(wq, self.qkv3, self.qkv3[0].numel(), 3 * Hq * D, Hq, 3)]
+        elif qkv is None and B > 1 and Hq != Hkv and kv_adjacent:
+            qkv_calls = [lin(x, wq, None, self.q, h, Hq * D, 0, Hq), seg(wk, self.kv2, self.kv2[0].numel(), 2 * Hkv * D, Hkv, 2)]
+        elif qkv is not None and Hq == Hkv and qkv_adjacent and qk_stride == kv_stride and kv_stride >= k_buf.numel():
+            qkv_calls = [seg(wq, q_buf, kv_stride, 3 * Hq * D, Hq, 3)]
+        elif qkv is not None and kv_adjacent and kv_stride >= k_buf.numel():
+            qkv_calls = [lin(x, wq, None, q_buf, h, Hq * D, 0, Hq), seg(wk, k_buf, kv_stride, 2 * Hkv * D, Hkv, 2)]
         else:
-            qkv_calls = [lin(x, wq, None, self.q, h, Hq * D, 0, Hq), lin(x, wk, None, self.k, h, Hkv * D, 0, Hkv),
-                         lin(x, wv, None, self.v, h, Hkv * D, 0, Hkv)]
+            qkv_calls = [lin(x, wq, None, q_buf, h, Hq * D, 0, Hq), lin(x, wk, None, k_buf, h, Hkv * D, 0, Hkv),
+                         lin(x, wv, None, v_buf, h, Hkv * D, 0, Hkv)]
         plan = qkv_calls + [
-            ("tree_rope", L.tree_rope, (p(self.q), p(self.k), p(position_ids), B, Hq, Hkv, T, D, float(self.theta), code)),
-            ("tree_attention", L.tree_attention, (p(self.q), p(self.k), p(self.v), p(k_cache), p(v_cache), p(prefix_len),
+            ("tree_rope", L.tree_rope, (p(q_buf), p(k_buf), p(position_ids), B, Hq, Hkv, T, D, float(self.theta), code)),
+            ("tree_attention", L.tree_attention, (p(q_buf), p(k_buf), p(v_buf), p(k_cache), p(v_cache), p(prefix_len),
                                                   self.tree.handle, p(self.attn), B, Hq, Hkv, D, self.Lcap, float(scale),
                                                   code, p(self.ws), nb(self.ws))),
         ]
@@ -93,19 +111,26 @@ class SimplifiedBlock:
             plan.append(("tree_linear_swiglu", L.tree_linear_swiglu, (p(self.attn), p(w_gu), p(self.act), B, T, Hq * D, inter,
                                                                       Hq, 0, code)))
         else:
+            if wu is None or wg is None:
+                raise _b.MedusaError("this row count takes two projection calls: w_u and w_g are needed")
             plan += [lin(self.attn, wu, None, self.up, Hq * D, inter, Hq, 0),
                      lin(self.attn, wg, self.up, self.act, Hq * D, inter, Hq, 0)]
-        plan.append(lin(self.act, wd, None, self.out, inter, h, 0, 0))
+        plan.append(lin(self.act, wd, None, out_buf, inter, h, 0, 0))
         self._plans[key] = plan
         return plan
 
-    def run(self, x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale: float, w_gu=None):
+    def run(self, x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale: float, w_gu=None,
+            qkv=None, out=None):
         """x [B*T, h]; weights out x in; k_cache, v_cache [B, Hkv, Lcap, D] of one layer.  Enqueues the
         block on the current stream and returns its output [B*T, h]; intermediates stay in
-        self.q/k/v/attn/up/act."""
+        self.q/k/v/attn/up/act.  ``qkv`` = (q, k, v), caller-owned head-major tensors [B, H, T, D] the
+        projections write instead of the block's own (a stack of layers keeps every layer's K and V of
+        the tree tokens for kv_commit; equally spaced tensors over adjacent weights share one call);
+        ``out`` = a caller-owned output [B*T, h] (not x)."""
         stream = torch.cuda.current_stream().cuda_stream
-        for name, fn, args in self._calls(x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale, w_gu):
+        for name, fn, args in self._calls(x, wq, wk, wv, wu, wg, wd, k_cache, v_cache, prefix_len, position_ids, scale, w_gu,
+                                          qkv, out):
             rc = fn(*args, stream)
             if rc != 0:
                 _b._check(rc, name)
-        return self.out
+        return self.out if out is None else out

@@ -139,14 +139,20 @@ class VerificationStep:
         self._plans[key] = (pre, post)
         return self._plans[key]
 
-    def run(self, attn_layer: int = 0, plant=None, wset: int = 0, heads_events=None) -> None:
+    def run(self, attn_layer: int = 0, plant=None, wset: int = 0, heads_events=None, backbone=None) -> None:
         """Enqueue one step on the current stream.  `plant`, if given, may edit the verification logits
         between the LM-head GEMM and acceptance (parity tests use it to force long accepted paths).
         `heads_events`: three raw hipEvent_t handles recorded before, between and after the two kernels
-        of the heads call (medusa_heads_timed) -- a benchmark's way to time them inside a running step."""
+        of the heads call (medusa_heads_timed) -- a benchmark's way to time them inside a running step.
+        `backbone`: a callable that enqueues a stack of decoder blocks on the tree tokens in place of the
+        single tree_attention call (forward.TreeBackbone.run): it reads position_ids, prefix_len and the
+        caches and fills k_tree, v_tree and hidden_tree, which the rest of the step then uses."""
         stream = torch.cuda.current_stream().cuda_stream
         pre, post = self._calls(attn_layer, wset)
         for i, (name, fn, args) in enumerate(pre):
+            if name == "tree_attention" and backbone is not None:
+                backbone()
+                continue
             if i == 0 and heads_events is not None:
                 rc = B_.lib().medusa_heads_timed(*args, stream, *heads_events)
             else:
