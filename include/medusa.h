@@ -375,6 +375,14 @@ int tree_rope(void* q, void* k, const int32_t* position_ids, int B, int Hq, int 
 int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int B, int T, int d_in, int d_out, int x_heads,
                        int y_heads, int dtype, medusa_stream_t stream);
 
+/* The weight layout tree_linear_swiglu reads, made from the two matrices (a one-time copy per weight
+ * pair; no counterpart in the paper):
+ *   w_gate, w_up [d_out, d_in] dtype;  w_gu [2*d_out, d_in] dtype out, laid out as described above.
+ * All device pointers, 16-byte aligned, caller-owned, not overlapping.  d_out a multiple of 16, rows a
+ * multiple of 16 bytes (else MEDUSA_EUNSUPPORTED). */
+int tree_interleave_gate_up(const void* w_gate, const void* w_up, void* w_gu, int d_out, int d_in, int dtype,
+                            medusa_stream_t stream);
+
 /* ----------------------------------------------------------------------------------
  * Diagnostic (no counterpart in the paper; host only, touches no GPU): which kernel arrangement
  * the library would launch for a bf16 product of M activation rows with K weight matrices of

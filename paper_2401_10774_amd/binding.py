@@ -28,7 +28,7 @@ EXPORTED_SYMBOLS = (
     "medusa_topk_tree", "tree_attention_workspace_bytes", "tree_attention", "tree_attention_static",
     "tree_attention_static_scratch_bytes", "medusa_accept_workspace_bytes",
     "medusa_accept", "medusa_accept_sampled", "medusa_verify_stats_bytes", "medusa_verify_fused_available",
-    "medusa_verify_logits", "medusa_accept_fused", "kv_commit", "medusa_carry_over", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "tree_rope",
+    "medusa_verify_logits", "medusa_accept_fused", "kv_commit", "medusa_carry_over", "tree_linear_workspace_bytes", "tree_linear", "tree_linear_segments", "tree_linear_swiglu", "tree_interleave_gate_up", "tree_rope",
     "medusa_heads_timed",
     "medusa_gemm_plan",
 )
@@ -87,6 +87,7 @@ def lib() -> ctypes.CDLL:
         L.tree_linear_workspace_bytes.argtypes = [c_int] * 5
         L.tree_linear.argtypes = [c_void_p] * 4 + [c_int] * 7 + [c_void_p, c_size_t, c_void_p]
         L.tree_linear_swiglu.argtypes = [c_void_p] * 3 + [c_int] * 7 + [c_void_p]
+        L.tree_interleave_gate_up.argtypes = [c_void_p] * 3 + [c_int] * 3 + [c_void_p]
         L.tree_linear_segments.argtypes = [c_void_p] * 4 + [c_int] * 7 + [c_size_t, c_int, c_void_p, c_size_t, c_void_p]
         L.tree_rope.argtypes = [c_void_p] * 3 + [c_int] * 5 + [c_float, c_int, c_void_p]
         L.medusa_heads_timed.argtypes = [c_void_p] * 5 + [c_int] * 5 + [c_void_p] * 4
@@ -544,13 +545,18 @@ def tree_linear_segments(x: torch.Tensor, w: torch.Tensor, B: int, T: int, y: to
     return y
 
 
-def interleave_gate_up(w_gate: torch.Tensor, w_up: torch.Tensor) -> torch.Tensor:
+def interleave_gate_up(w_gate: torch.Tensor, w_up: torch.Tensor, stream=None) -> torch.Tensor:
     """The weight layout tree_linear_swiglu reads: blocks of 16 gate rows followed by the same 16 rows
     of the up projection.  [d_out, d_in] x 2 -> [2*d_out, d_in]; d_out a multiple of 16."""
     d_out, d_in = w_gate.shape
     if w_up.shape != w_gate.shape or d_out % 16 != 0:
         raise MedusaError("gate and up weights must have the same shape, rows a multiple of 16")
-    return torch.stack((w_gate.view(d_out // 16, 16, d_in), w_up.view(d_out // 16, 16, d_in)), dim=1).reshape(2 * d_out, d_in).contiguous()
+    _dev(w_gate, "w_gate", shape=(d_out, d_in))
+    _dev(w_up, "w_up", dtype=w_gate.dtype, shape=(d_out, d_in))
+    w_gu = torch.empty((2 * d_out, d_in), dtype=w_gate.dtype, device=w_gate.device)
+    _check(lib().tree_interleave_gate_up(w_gate.data_ptr(), w_up.data_ptr(), w_gu.data_ptr(), d_out, d_in, _dtype_code(w_gate),
+                                         _stream(stream)), "tree_interleave_gate_up")
+    return w_gu
 
 
 def tree_linear_swiglu(x: torch.Tensor, w_gu: torch.Tensor, B: int, T: int, y: Optional[torch.Tensor] = None,

@@ -59,7 +59,32 @@ __global__ __launch_bounds__(1024) void tree_rope_kernel(RopeArgs a) {
   }
 }
 
+// tree_interleave_gate_up: the weight layout tree_linear_swiglu reads -- rows 32b..32b+15 of the
+// output are rows 16b..16b+15 of w_gate, rows 32b+16..32b+31 the same rows of w_up.  A one-time
+// copy per weight pair: grid (2*d_out), 256 threads, one output row per workgroup in 16-byte pieces.
+__global__ __launch_bounds__(256) void interleave_gate_up_kernel(const u32x4_t* __restrict__ w_gate, const u32x4_t* __restrict__ w_up,
+                                                                 u32x4_t* __restrict__ w_gu, int row_chunks) {
+  const int row = blockIdx.x, blk = row >> 5, r = row & 31;
+  const u32x4_t* src = (r < 16 ? w_gate : w_up) + ((size_t)blk * 16 + (r & 15)) * row_chunks;
+  u32x4_t* dst = w_gu + (size_t)row * row_chunks;
+  for (int c = threadIdx.x; c < row_chunks; c += 256) dst[c] = src[c];
+}
+
 }  // namespace
+
+extern "C" int tree_interleave_gate_up(const void* w_gate, const void* w_up, void* w_gu, int d_out, int d_in, int dtype,
+                                       medusa_stream_t stream_) {
+  if (!w_gate || !w_up || !w_gu) return MEDUSA_EINVAL;
+  if (d_out < 1 || d_in < 1) return MEDUSA_EINVAL;
+  if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;
+  const size_t row_bytes = (size_t)d_in * (dtype == MEDUSA_BF16 ? 2 : 4);
+  if (d_out % 16 != 0 || row_bytes % 16 != 0 || d_out > (1 << 24)) return MEDUSA_EUNSUPPORTED;
+  if ((((uintptr_t)w_gate | (uintptr_t)w_up | (uintptr_t)w_gu) & 15) != 0) return MEDUSA_EUNSUPPORTED;
+  hipLaunchKernelGGL(interleave_gate_up_kernel, dim3(2 * d_out), dim3(256), 0, (hipStream_t)stream_, (const u32x4_t*)w_gate,
+                     (const u32x4_t*)w_up, (u32x4_t*)w_gu, (int)(row_bytes / 16));
+  MEDUSA_LAUNCH_CHECK();
+  return MEDUSA_OK;
+}
 
 extern "C" int tree_rope(void* q, void* k, const int32_t* position_ids, int B, int Hq, int Hkv, int T, int D, float theta,
                          int dtype, medusa_stream_t stream_) {

@@ -106,6 +106,10 @@ def test_argument_checks_happen_on_the_host():
     assert L.kv_commit(p, p, p, None, p, 3, p, p, None, 1, 1, 1, 7, 64, 16, 1, None) == -1
     assert L.medusa_topk_tree(p, None, t.handle, p, 1, 100, 2, p, p, p, p, 1 << 20, None) == -1
     assert L.medusa_topk_tree(p, p, t.handle, p, 1, 100, 1, p, p, p, p, 1 << 20, None) == -1   # fewer heads than levels
+    assert L.tree_interleave_gate_up(p, None, p, 32, 64, 1, None) == -1
+    assert L.tree_interleave_gate_up(p, p, p, 24, 64, 1, None) == -2                            # rows in blocks of 16
+    assert L.tree_interleave_gate_up(p, p, p, 32, 12, 1, None) == -2                            # 24-byte rows
+    assert L.tree_interleave_gate_up(p, p, ctypes.c_void_p(4100), 32, 64, 1, None) == -2        # misaligned
     assert L.tree_attention_workspace_bytes(1, 32, 32, 65, 128, 1152) % 256 == 0
     assert L.tree_attention_workspace_bytes(1, 32, 5, 65, 128, 1152) == 0
     assert L.medusa_accept_workspace_bytes(2, 65, 32000) > 0
