@@ -1091,6 +1091,8 @@ int launch_gemm(const GemmArgs& a_in, int dtype, hipStream_t stream) {
     const dim3 grid = plan.kind == GemmPlan::SKINNY && plan.ring
                           ? dim3(ring_grid_x(a.N, plan.ntw, plan.m_blocks), a.K, a.ksplit)
                           : dim3(ceil_div(a.N, plan.kind == GemmPlan::SKINNY ? 16 * plan.ntw : 128), a.K, plan.m_blocks * a.ksplit);
+    // (every output tile of a split launch has a ticket counter: the planning stays far below their number)
+    if (split && (long)grid.x * grid.y * (plan.ring ? 1 : plan.m_blocks) > kMaxSplitTiles) return MEDUSA_EUNSUPPORTED;
     if (plan.kind == GemmPlan::SQUARE) {
       hipLaunchKernelGGL((gemm_lds_bf16_kernel<2, 2, 4, 4, 64, 2, EPI, false>), grid, block, 0, stream, a);
       MEDUSA_LAUNCH_CHECK();
