@@ -555,12 +555,13 @@ Plan make_plan(int B, int Hq, int Hkv, int T, int Lcap) {
   const int blocks = ceil_div(Lcap + T, kBlkKeys);
   const int base = B * Hkv * p.row_blocks;
   // One workgroup runs per CU.  A single sequence has splits of equal length: one round of at most
-  // 256 workgroups (8192 keys, 32 heads: 8 splits 39.5 us, 6 41.6, 10 53.6, 16 47.3).  A batch is
-  // ragged (the host does not know the lengths): about twice as many workgroups even out the long
-  // sequences (B = 4, 40 heads: 1/2/3/4 splits 50/47/43/47 us; B = 16, 8 KV heads x 3 row blocks:
-  // 138/122/123).  At least four key blocks per split: each split costs a partial write and read
-  // of about 80 keys' worth of bytes.
-  int want = B == 1 ? 256 / base : ceil_div(448, base);
+  // 256 workgroups (8192 keys, 32 heads: 8 splits 39.5 us, 6 41.6, 10 53.6, 16 47.3; 4096 keys: 8
+  // splits 37.7 us, 6 39.7, 5 43.5, 10 52.3).  A batch that gives 160 workgroups by itself is not
+  // split at all -- every split costs its start-up, a partial write and the merge launch, and the
+  // ragged lengths even out over the CUs' queues (B = 4, 40 heads: 1/2/3/4 splits 39/42/42/47 us;
+  // B = 16, 8 KV heads x 3 row blocks: 93/97/105/106) -- smaller batches up to one round.  At least four
+  // key blocks per split: each split costs a partial write and read of about 80 keys' worth of bytes.
+  int want = B == 1 ? 256 / base : (base >= 160 ? 1 : ceil_div(256, base));
   const int cap = blocks / 4 > 1 ? blocks / 4 : 1;
   want = want < 1 ? 1 : (want > cap ? cap : want);
   p.n_splits = ceil_div(blocks, ceil_div(blocks, want));
