@@ -221,8 +221,9 @@ def main():
                                       "note": "same step with one copy of W1 and of the LM head re-read every step "
                                               "(they stay in the last-level cache); not what a decoder sees"}},
         "roofline": {
-            "kernel": "gemv_bf16_kernel<1, EPI_LOGITS> (medusa_heads W2 projection, M=B)" if cfg.dtype == "bf16" and cfg.B <= 4
-                      else "medusa_heads W2 projection",
+            "kernel": ("gemv_bf16_kernel<%d, EPI_LOGITS>" % cfg.B if cfg.dtype == "bf16" and cfg.B <= 2
+                       else "gemm_ring_bf16_kernel<1, 8, 8, EPI_LOGITS>" if cfg.dtype == "bf16" and cfg.B <= 16
+                       else "medusa_heads W2 kernel") + " (medusa_heads W2 projection, M=B)",
             "bound": "hbm",
             "achieved": round(dom_gbs, 1),
             "peak": HBM_PEAK_GBS,

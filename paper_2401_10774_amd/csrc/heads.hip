@@ -3,10 +3,10 @@
 // Both GEMMs are "skinny": M (batch rows, or batch x tree tokens) is tiny next to the
 // d x d and V x d weight matrices, so the weights are streamed from HBM exactly once and
 // the kernels are organised around that stream:
-//   * M <= 4  (bf16): one wavefront per weight row, 16-byte non-temporal loads that cover
+//   * M <= 2  (bf16): one wavefront per weight row, 16-byte non-temporal loads that cover
 //                     1 KB of the row per instruction, packed bf16 dot products on the
-//                     vector ALUs, activations resident in LDS.
-//   * M  > 4  (bf16): 16x16x32 bf16 MFMA tiles.  Up to 80 activation rows per row block: 1 KB runs
+//                     vector ALUs, activations resident in LDS (also three or four rows on small matrices).
+//   * more rows (bf16): 16x16x32 bf16 MFMA tiles.  Up to 80 activation rows per row block: 1 KB runs
 //                     of 48-128 weight rows go from global memory straight into an LDS ring (the
 //                     ring kernel); larger row blocks and short split reductions: a double-buffered
 //                     LDS tile filled through registers several reduction steps ahead; from about
@@ -251,7 +251,7 @@ __device__ __forceinline__ void finish_tile(const GemmArgs& a, floatx4_t (&acc)[
 }
 
 // ---------------------------------------------------------------------------------------
-// bf16, M > 4: LDS-staged MFMA GEMM (v_mfma_f32_16x16x32_bf16).
+// bf16, more rows than the GEMV takes: LDS-staged MFMA GEMM (v_mfma_f32_16x16x32_bf16).
 //
 // Workgroup tile BM x BN = (WM*16*MT activation rows) x (WN*16*NT weight rows), four wavefronts
 // arranged WM x WN, reduction in steps of BK elements (64 = one 128-byte line per row; 128 measured no faster:
@@ -792,7 +792,8 @@ __global__ __launch_bounds__(256) void gemm_ring_bf16_kernel(GemmArgs a) {
 }
 
 // Which kernel a bf16 GEMM of M rows goes to, and in what shape.
-//   M <= 4     wave-per-row GEMV.
+//   M <= 2     wave-per-row GEMV (also three or four rows on a small matrix; not two rows of a long
+//              reduction: see use_gemv).
 //   M > 80     128 x 128 tiles (wavefronts 2 x 2, unsplit) or the large-tile kernel (gemm_big.hip)
 //              with 128 or 192 x 256 tiles, whichever a small cost model prices lowest (below); if
 //              none of them has enough tiles, as for fewer rows:
@@ -808,6 +809,18 @@ __global__ __launch_bounds__(256) void gemm_ring_bf16_kernel(GemmArgs a) {
 //              64 KB partials).
 // Workgroups along x of a ring kernel launch: the column tiles, or -- with several row blocks -- groups of
 // 8 column tiles x row blocks (see the kernel), the last group padded.
+// The wave-per-row GEMV stages its activation rows in LDS, M x d x 2 bytes per workgroup, and its
+// wavefronts repeat every dot product for every row.  One or two rows: nothing streams the weights
+// faster.  Three or four rows: the MFMA kernels win wherever the matrix is more than a few launch
+// latencies long (us, four rows, GEMV against ring kernel: 32000 x 4096 50 / 44; 12288 x 4096 21.8 / 19.5;
+// 4096 x 11008 30.7 / 20.7; 5120 x 13824 52 / 28; W1 and W2 of five heads at d = 5120, V = 32000:
+// 293 / 279; but 1024 x 4096 9.9 / 10.9, 5120 x 5120 16.5 / 17.0).  Two rows of more than 8192
+// elements (32 KB of staging): 5120 x 13824 33 / 28.
+inline bool use_gemv(int M, int N, int d, int K) {
+  if (M <= 1) return true;
+  if (M == 2) return d <= 8192;
+  return M <= 4 && (long)K * N * d <= ((long)8 << 20);
+}
 inline int ring_grid_x(int N, int ntw, int m_blocks) {
   const int cols = ceil_div(N, 16 * ntw);
   return m_blocks > 1 ? 8 * ceil_div(cols, 8) * m_blocks : cols;
@@ -821,7 +834,7 @@ struct GemmPlan {
 };
 GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) {
   GemmPlan p = {GemmPlan::GEMV, false, false, 8, 1, 1, 1};
-  if (M <= 4) return p;
+  if (use_gemv(M, N, d, K)) return p;
   p.m_blocks = ceil_div(M, 128);
   if (M > 80) {
     // Three arrangements compete above 80 rows: 128 x 128 tiles (two workgroups share a CU) and
@@ -866,17 +879,21 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
       // A long reduction into few large tiles (the down projection of a batch of trees: M = 1040,
       // 11008 -> 4096 is 96 tiles of 192 x 256) can be split over 2 or 4 workgroups per tile when there
       // is a workspace.  Each split costs its partial tile (r KB) a write-through, a ticket and an
-      // agent-scope read: about 5 us plus 0.5 us (two splits) or 0.8 us (four) per MB of partial tiles.
-      // A split plan has to beat the best unsplit one (the skinny launch, where it fits one workgroup
-      // per CU, priced from a fit to its measured times) by a tenth, and must fit one round on every
+      // agent-scope read: about 5 us plus 0.3 us per MB of partial tiles (two splits) or 8 us plus 0.4 us per MB (four)
+      // (M = 260..512, 11008 -> 4096 on 128-row tiles x 4 splits: 73-75 us measured, 73-76 priced; M = 161..260,
+      // 13824 -> 5120: 83-86 measured, 88-92 priced; a 192-row tile split four ways runs as if its round took 110 us:
+      // 105 us measured at M = 260, 11008 -> 4096).  A split plan has to beat the best unsplit one (the skinny
+      // launch, where it fits one workgroup per CU, priced from a fit to its measured times; three or more
+      // row blocks of it over a long reduction re-stream the weights and cost more: 11008 -> 4096 at M = 260..384 runs 81-97 us) by a
+      // twentieth, and must fit one round on every
       // die: column tiles go round-robin over the 8 dies of 32 CUs each, rotated from split to split.  Measured on 8 weight shapes x
       // 10 row counts against the unsplit planning: 17 shapes 11-30 % faster (M = 1040, 11008 -> 4096:
       // 195 -> 145 us; M = 512: 100 -> 77; M = 420, 13824 -> 5120: 184 -> 134), none slower.
       if (have_ws && M > 128) {                             // (one row block: the skinny kernels are at their best)
         double unsplit = best;
-        const double skinny_us = scale * (12.0 + 0.05 * M) * (N > 4096 ? N / 4096.0 : 1.0);   // (fit to M = 160..512 at 7B and 13B shapes)
+        const double skinny_us = scale * (12.0 + 0.05 * M) * (N > 4096 ? N / 4096.0 : 1.0) * (p.m_blocks >= 3 && d > 6144 ? 1.15 : 1.0);   // (fit to M = 160..512 at 7B and 13B shapes)
         if (skinny_tiles <= 256 && skinny_us < unsplit) unsplit = skinny_us;
-        double best_split = 0.9 * unsplit;
+        double best_split = 0.95 * unsplit;
         for (int r = 128; r <= 192; r += 64)
           for (int sp = 2; sp <= 4; sp *= 2) {
             const long tiles = (long)ceil_div(M, r) * ceil_div(N, 256) * K;
@@ -891,7 +908,7 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
             per_die *= (long)ceil_div(M, r) * K;
             if (tiles < 32 || per_die > 32 || (d / 64) / sp < 16) continue;
             const double partial_mb = (double)tiles * sp * r * 1024.0 / 1.0e6;
-            const double t = (r == 128 ? 68.0 : 88.0) * scale / sp + 0.6 * w_us + 5.0 + partial_mb * (sp == 2 ? 0.5 : 0.8);
+            const double t = (r == 128 ? 68.0 : sp == 2 ? 88.0 : 110.0) * scale / sp + 0.6 * w_us + (sp == 2 ? 5.0 + 0.3 * partial_mb : 8.0 + 0.4 * partial_mb);
             if (t < best_split) { best_split = t; pick = GemmPlan::BIG; tall = r == 192; big_split = sp; }
           }
       }
@@ -1066,7 +1083,7 @@ int launch_gemm(const GemmArgs& a_in, int dtype, hipStream_t stream) {
     const size_t lds = (size_t)MB * a.d * sizeof(float);
     if (MB == 4) hipLaunchKernelGGL((gemv_f32_kernel<4, EPI>), grid, block, lds, stream, a);
     else hipLaunchKernelGGL((gemv_f32_kernel<1, EPI>), grid, block, lds, stream, a);
-  } else if (a.M <= 4) {
+  } else if (use_gemv(a.M, a.N, a.d, a.K)) {
     int MB = a.M <= 1 ? 1 : (a.M <= 2 ? 2 : 4);
     if ((size_t)a.d * sizeof(uint16_t) > 65536) return MEDUSA_EUNSUPPORTED;   // one activation row must fit the 64 KB staging
     while ((size_t)MB * a.d * sizeof(uint16_t) > 65536) MB >>= 1;   // activations of one m-block live in LDS
