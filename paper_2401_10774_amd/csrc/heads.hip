@@ -6,7 +6,7 @@
 //   * M <= 2  (bf16): one wavefront per weight row, 16-byte non-temporal loads that cover
 //                     1 KB of the row per instruction, packed bf16 dot products on the
 //                     vector ALUs, activations resident in LDS (also three or four rows on small matrices).
-//   * more rows (bf16): 16x16x32 bf16 MFMA tiles.  Up to 80 activation rows per row block: 1 KB runs
+//   * more rows (bf16): 16x16x32 bf16 MFMA tiles.  Up to 96 activation rows per row block: 1 KB runs
 //                     of 48-128 weight rows go from global memory straight into an LDS ring (the
 //                     ring kernel); larger row blocks and short split reductions: a double-buffered
 //                     LDS tile filled through registers several reduction steps ahead; from about
@@ -544,7 +544,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_bf16_kernel(GemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// bf16, 4 < M <= 80 per row block (the ring kernel): the weights of a tile are fetched in 1 KB runs
+// bf16, up to 96 rows per row block (the ring kernel): the weights of a tile are fetched in 1 KB runs
 // and nothing passes through registers on its way to LDS.
 //
 // Cold weights stream from HBM at 4.4 TB/s when a workgroup asks for 256 bytes of each of its 128
@@ -584,7 +584,8 @@ __global__ __launch_bounds__(256) void gemm_ring_bf16_kernel(GemmArgs a) {
   static_assert(NTW >= 2 && NTW <= 8, "the activation rows of the next super-stage are requested at j = 1");
   static_assert(NR >= 3 && NR <= 8, "the count of loads issued after a sub-stage's own assumes 3..8 buffers");
   static_assert(WL * (NR - 2) + XL <= 63, "load counter");
-  static_assert(4 * MT * NTW <= 16 * (MT + NR), "the four partial tiles must fit the LDS the loop used");
+  constexpr int PASSES = 4 * MT * NTW <= 16 * (MT + NR) ? 1 : 2;   // the four partial tiles go through the loop's LDS whole, or in two halves of the row groups
+  static_assert(MT % PASSES == 0 && 4 * (MT / PASSES) * NTW <= 16 * (MT + NR), "half of the four partial tiles must fit the LDS the loop used");
   static_assert(EPI != EPI_SWIGLU || NTW % 2 == 0, "gate and up fragments come in pairs");
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_dyn[];
   unsigned char* lds = lds_dyn;                        // [slab][ring of NR weight buffers]
@@ -724,25 +725,31 @@ __global__ __launch_bounds__(256) void gemm_ring_bf16_kernel(GemmArgs a) {
   // fragments for the SwiGLU epilogue), dealt out round-robin.  With a split reduction the sums go to
   // the workspace ([tile][split][unit slot][fragment of the unit][register pair][thread], 8 bytes per
   // thread and store, write-through); the workgroup that arrives last adds them in split order.
-  constexpr int F = MT * NTW, PER = EPI == EPI_SWIGLU ? 2 : 1, UNITS = F / PER, UPR = NTW / PER, NU = (UNITS + 3) / 4;
-  __syncthreads();
-#pragma unroll
-  for (int t = 0; t < MT; ++t)
-#pragma unroll
-    for (int j = 0; j < NTW; ++j) *(floatx4_t*)(lds + (((wave * F + t * NTW + j) * 64 + lane) << 4)) = acc[t][j];
-  __syncthreads();
+  // (Six row groups x eight fragments are 192 KB of partial tiles: they pass in two halves, row groups 0-2, then 3-5.)
+  constexpr int PER = EPI == EPI_SWIGLU ? 2 : 1, UNITS = MT * NTW / PER, UPR = NTW / PER, NU = (UNITS + 3) / 4;
+  constexpr int MTP = MT / PASSES, F = MTP * NTW;        // row groups and fragments per pass
   floatx4_t fin[NU][PER];
 #pragma unroll
-  for (int n = 0; n < NU; ++n) {
-    const int unit = min(n * 4 + wave, UNITS - 1);       // (a surplus slot repeats the last unit and is never stored)
-    const int t = unit / UPR, jj = unit - t * UPR;
+  for (int pass = 0; pass < PASSES; ++pass) {
+    __syncthreads();
 #pragma unroll
-    for (int e = 0; e < PER; ++e) {
-      const int f = t * NTW + jj * PER + e;
-      floatx4_t sum = *(const floatx4_t*)(lds + (((0 * F + f) * 64 + lane) << 4));
+    for (int t = 0; t < MTP; ++t)
 #pragma unroll
-      for (int w = 1; w < 4; ++w) sum += *(const floatx4_t*)(lds + (((w * F + f) * 64 + lane) << 4));
-      fin[n][e] = sum;
+      for (int j = 0; j < NTW; ++j) *(floatx4_t*)(lds + (((wave * F + t * NTW + j) * 64 + lane) << 4)) = acc[pass * MTP + t][j];
+    __syncthreads();
+#pragma unroll
+    for (int n = 0; n < NU; ++n) {
+      const int unit = min(n * 4 + wave, UNITS - 1);     // (a surplus slot repeats the last unit and is never stored)
+      const int t = unit / UPR, jj = unit - t * UPR;
+      if (PASSES > 1 && t / MTP != pass) continue;
+#pragma unroll
+      for (int e = 0; e < PER; ++e) {
+        const int f = (t - pass * MTP) * NTW + jj * PER + e;
+        floatx4_t sum = *(const floatx4_t*)(lds + (((0 * F + f) * 64 + lane) << 4));
+#pragma unroll
+        for (int w = 1; w < 4; ++w) sum += *(const floatx4_t*)(lds + (((w * F + f) * 64 + lane) << 4));
+        fin[n][e] = sum;
+      }
     }
   }
   if (SPLIT && n_split > 1) {
@@ -794,11 +801,11 @@ __global__ __launch_bounds__(256) void gemm_ring_bf16_kernel(GemmArgs a) {
 // Which kernel a bf16 GEMM of M rows goes to, and in what shape.
 //   M <= 2     wave-per-row GEMV (also three or four rows on a small matrix; not two rows of a long
 //              reduction: see use_gemv).
-//   M > 80     128 x 128 tiles (wavefronts 2 x 2, unsplit) or the large-tile kernel (gemm_big.hip)
+//   M > 96     128 x 128 tiles (wavefronts 2 x 2, unsplit) or the large-tile kernel (gemm_big.hip)
 //              with 128 or 192 x 256 tiles, whichever a small cost model prices lowest (below); if
 //              none of them has enough tiles, as for fewer rows:
-//   otherwise  a skinny arrangement: row blocks of 16*mt <= 128 activation rows.  Up to 80 rows per
-//              block (mt <= 5): the ring kernel -- unsplit on tiles of 128, 96, 64 or 48 columns when
+//   otherwise  a skinny arrangement: row blocks of 16*mt <= 128 activation rows.  Up to 96 rows per
+//              block (mt <= 6): the ring kernel -- unsplit on tiles of 128, 96, 64 or 48 columns when
 //              one of these widths gives 160 workgroups, else, with a workspace and a reduction long
 //              enough, split over 2-8 workgroups per tile.  Everything else: the register-staged
 //              kernels on 64-column tiles -- unsplit, the one whose wavefronts split the reduction;
@@ -836,8 +843,8 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
   GemmPlan p = {GemmPlan::GEMV, false, false, 8, 1, 1, 1};
   if (use_gemv(M, N, d, K)) return p;
   p.m_blocks = ceil_div(M, 128);
-  if (M > 80) {
-    // Three arrangements compete above 80 rows: 128 x 128 tiles (two workgroups share a CU) and
+  if (M > 96) {
+    // Three arrangements compete above 96 rows: 128 x 128 tiles (two workgroups share a CU) and
     // the large-tile kernel with 128 or 192 rows x 256 (one workgroup per CU).  What decides is
     // how evenly the tiles fill 256 CUs, so each candidate is priced with its measured time per
     // round of tiles (us at d = 4096, 7B shapes; the large tiles also wait for the weights'
@@ -945,7 +952,10 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
   }
   p.wide = false;
   p.ntw = 4;                                                // (the register-staged kernels below: 64-column tiles)
-  // The ring kernel takes up to 80 rows per block, or up to 160 rows as two blocks (the blocks of a
+  // The ring kernel takes up to 96 rows per block (six row groups leave the ring four buffers beside the 96 KB
+  // slab, and the four partial tiles pass through LDS in two halves; still far ahead of everything else at
+  // 81..96 rows -- the 89 tokens of the 13B tree: LM head 32000 x 5120 81 -> 64 us, 27648 x 5120 77 -> 59,
+  // 15360 x 5120 45 -> 38 against 128 x 128 tiles or two blocks of 48 rows), or up to 192 rows as two blocks (the blocks of a
   // weight tile run side by side on one die and share its trip from HBM; with three or four blocks the
   // register-staged kernels below measured faster: N = 5120, d = 13824, M = 200 90 against 105 us).
   // Candidates, priced in units of one sub-stage (16 rows x 1 KB, roughly 0.6 us):
@@ -963,8 +973,8 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
   // 48 columns 47-54, register-staged 41-55).  Against the register-staged kernels at M = 16..80 on 7B
   // and 13B projection shapes and the LM head: 7-30 % faster on weights from HBM, equal within 3 % on
   // weights the last-level cache holds.
-  const int ring_blocks = p.mt <= 5 ? p.m_blocks : ceil_div(M, 80), ring_mt = ceil_div(ceil_div(M, ring_blocks), 16);
-  if (ring_blocks <= 2 || p.mt <= 5) {
+  const int ring_blocks = p.mt <= 6 ? p.m_blocks : ceil_div(M, 80), ring_mt = ceil_div(ceil_div(M, ring_blocks), 16);
+  if (ring_blocks <= 2 || p.mt <= 6) {
     const int n_super = (d + 511) / 512;
     const double per_stage = 0.25 * ring_mt;
     double best = 1e30;
@@ -1049,7 +1059,7 @@ int gemv_rows_per_wg(int N, int K, int M) {
 // Register stages of the skinny kernel: three while its MT + NTW chunks per thread and stage leave room.
 constexpr int skinny_depth(int mt, int ntw) { return mt + ntw <= 13 ? 3 : 2; }
 // Weight buffers of the ring kernel: what 160 KB of LDS hold beside the activation slab, at most 8.
-constexpr int ring_depth(int mt) { return mt >= 5 ? 5 : (10 - mt > 8 ? 8 : 10 - mt); }
+constexpr int ring_depth(int mt) { return mt >= 6 ? 4 : mt == 5 ? 5 : (10 - mt > 8 ? 8 : 10 - mt); }
 
 // The skinny kernels' LDS tiles exceed the 64 KB a kernel gets by default (the ring kernel takes all
 // 160 KB of a CU): raise the limit once per kernel and device.
@@ -1121,7 +1131,7 @@ int launch_gemm(const GemmArgs& a_in, int dtype, hipStream_t stream) {
 #define MEDUSA_SKINNY(MT_)                                                                                                     \
   case MT_:                                                                                                                    \
     if (split && plan.ring) {                                                                                                  \
-      constexpr int MR = MT_ <= 5 ? MT_ : 5, NR = ring_depth(MR);                                                        \
+      constexpr int MR = MT_ <= 6 ? MT_ : 6, NR = ring_depth(MR);                                                        \
       const size_t ring_lds = (size_t)(NR + MR) * 16384;                                                                       \
       if (plan.ntw == 8) rc = launch_skinny<gemm_ring_bf16_kernel<MR, 8, NR, EPI, kCanSplit>>(grid, ring_lds, stream, a);      \
       else if (plan.ntw == 6) rc = launch_skinny<gemm_ring_bf16_kernel<MR, 6, NR, EPI, kCanSplit>>(grid, ring_lds, stream, a); \
@@ -1129,7 +1139,7 @@ int launch_gemm(const GemmArgs& a_in, int dtype, hipStream_t stream) {
     } else if (split) {                                                                                                        \
       hipLaunchKernelGGL((gemm_lds_bf16_kernel<1, 4, MT_, 1, 64, 4, EPI, kCanSplit>), grid, block, 0, stream, a);              \
     } else if (plan.ring) {                                                                                                    \
-      constexpr int MR = MT_ <= 5 ? MT_ : 5, NR = ring_depth(MR);                                                              \
+      constexpr int MR = MT_ <= 6 ? MT_ : 6, NR = ring_depth(MR);                                                              \
       const size_t ring_lds = (size_t)(NR + MR) * 16384;                                                                       \
       if (plan.ntw == 8) rc = launch_skinny<gemm_ring_bf16_kernel<MR, 8, NR, EPI>>(grid, ring_lds, stream, a);                 \
       else if (plan.ntw == 6) rc = launch_skinny<gemm_ring_bf16_kernel<MR, 6, NR, EPI>>(grid, ring_lds, stream, a);            \
@@ -1351,14 +1361,14 @@ extern "C" int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int 
   }
   hipStream_t stream = (hipStream_t)stream_;
   // Many rows (a batch of trees): the large-tile kernel, if the planning gives it this shape
-  if (a.M > 80) {
+  if (a.M > 96) {
     const bool wide_offsets = (size_t)a.N * a.d >= ((size_t)1 << 31) || x_extent(a) >= ((size_t)1 << 31);
     const GemmPlan plan = plan_gemm(a.M, a.N, a.d, 1, false, wide_offsets);
     if (plan.kind == GemmPlan::BIG) return launch_gemm_big(a, EPI_SWIGLU, plan.wide, stream);
   }
   // 128-column tiles (gate and up fragments of a column block side by side in a wavefront), row blocks
-  // of at most 80 rows, never split: tuned for the tree-token range, correct for any M
-  const int m_blocks = ceil_div(a.M, 80), mt = ceil_div(ceil_div(a.M, m_blocks), 16);
+  // of at most 96 rows, never split: tuned for the tree-token range, correct for any M
+  const int m_blocks = ceil_div(a.M, 96), mt = ceil_div(ceil_div(a.M, m_blocks), 16);
   // the ring kernel, with the tile width (whole gate/up pairs) priced as in plan_gemm
   int ntw = 8;
   {
@@ -1381,7 +1391,7 @@ extern "C" int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int 
     else if (ntw == 4) rc = launch_skinny<gemm_ring_bf16_kernel<MT_, 4, NR, EPI_SWIGLU>>(grid, ring_lds, stream, a);      \
     else rc = launch_skinny<gemm_ring_bf16_kernel<MT_, 2, NR, EPI_SWIGLU>>(grid, ring_lds, stream, a);                    \
   } break;
-  switch (mt) { MEDUSA_SWIGLU(1) MEDUSA_SWIGLU(2) MEDUSA_SWIGLU(3) MEDUSA_SWIGLU(4) MEDUSA_SWIGLU(5) default: return MEDUSA_EUNSUPPORTED; }
+  switch (mt) { MEDUSA_SWIGLU(1) MEDUSA_SWIGLU(2) MEDUSA_SWIGLU(3) MEDUSA_SWIGLU(4) MEDUSA_SWIGLU(5) MEDUSA_SWIGLU(6) default: return MEDUSA_EUNSUPPORTED; }
 #undef MEDUSA_SWIGLU
   if (rc != MEDUSA_OK) return rc;
   MEDUSA_LAUNCH_CHECK();

@@ -142,18 +142,18 @@ def test_gemm_plans_are_launchable():
                     assert rows > 1, what
                     assert p["kind"] in ("skinny", "square", "big"), what
                     if p["kind"] == "big":
-                        assert rows > 80, what
+                        assert rows > 96, what
                         continue
                     if p["kind"] == "square":       # 128 x 128 tiles
-                        assert rows > 80 and p["ksplit"] == 1 and p["m_blocks"] * 128 >= rows, what
+                        assert rows > 96 and p["ksplit"] == 1 and p["m_blocks"] * 128 >= rows, what
                         continue
                     assert 1 <= p["mt"] <= 8 and p["m_blocks"] >= 1, what
                     assert p["m_blocks"] * p["mt"] * 16 >= rows, what
                     assert p["ksplit"] in (1, 2, 4, 8), what
                     assert ws or p["ksplit"] == 1, what
-                    assert not p["wide"] or p["mt"] <= 5, what
+                    assert not p["wide"] or p["mt"] <= 6, what
                     assert p["tile"] in (48, 64, 96, 128), what
-                    assert not p["ring"] or p["mt"] <= 5, what
+                    assert not p["ring"] or p["mt"] <= 6, what
                     assert not (p["ring"] and p["ksplit"] > 1) or (d + 511) // 512 // p["ksplit"] >= 3, what
                     assert p["ring"] or p["tile"] in (64, 128), what
                     if p["ksplit"] > 1:

@@ -121,7 +121,7 @@ def test_linear_segments(dtype, B, T, d_in, heads, dh, segments, x_heads):
 
 
 def test_linear_bf16_ring_kernel():
-    # up to 80 rows: the kernel that fetches 1 KB runs into an LDS ring, with the gated epilogue,
+    # up to 96 rows per block: the kernel that fetches 1 KB runs into an LDS ring, with the gated epilogue,
     # head-major activations on both sides and tiles of 128, 96, 64 and 48 columns
     linear_case("bf16", 1, 65, 192, 25600, 0, 0, True, 430)
     linear_case("bf16", 2, 33, 256, 25600, 2, 200, False, 431)
@@ -132,11 +132,16 @@ def test_linear_bf16_ring_kernel():
     assert M.medusa_gemm_plan(130, 6400, 1024, 1, True)["m_blocks"] == 2
     linear_case("bf16", 2, 65, 1024, 6400, 8, 50, False, 445)        # two row blocks (interleaved with the column tiles), head-major both sides
     linear_case("bf16", 1, 150, 3072, 4224, 0, 0, True, 446)         # two row blocks, ragged second one, 88 column tiles (no multiple of 8)
+    assert M.medusa_gemm_plan(89, 19200, 576, 1, True)["mt"] == 6
+    linear_case("bf16", 1, 89, 576, 19200, 0, 150, True, 447)        # six row groups (the 89 tokens of the 13B tree), 96 columns, gated, head-major output
+    assert (M.medusa_gemm_plan(192, 5120, 5120, 1, True)["mt"], M.medusa_gemm_plan(192, 5120, 5120, 1, True)["m_blocks"]) == (6, 2)
+    linear_case("bf16", 2, 96, 5120, 5120, 40, 0, False, 448)        # two blocks of six row groups, 48 columns
     # narrow outputs over a long reduction: the same kernel with its reduction split over workgroups;
     # a short reduction stays with the register-staged split kernel
     for rows, d_in, d_out, want in ((16, 3072, 4224, (True, 64, 2)), (65, 6144, 2176, (True, 64, 4)), (40, 12288, 256, (True, 64, 8)),
                                     (65, 6144, 4224, (True, 96, 4)), (16, 11776, 6272, (True, 128, 4)),
                                     (97, 11008, 4096, (True, 64, 2)), (97, 6144, 2048, (True, 64, 2)),      # ... with two and four row blocks
+                                    (96, 11008, 4096, (True, 64, 4)), (178, 11008, 4096, (True, 64, 2)),     # ... with six row groups, one and two blocks
                                     (65, 2752, 4096, (False, 64, 2)), (16, 4096, 1024, (False, 64, 4))):
         plan = M.medusa_gemm_plan(rows, d_out, d_in, 1, True)
         assert (plan["ring"], plan["tile"], plan["ksplit"]) == want, plan
@@ -156,6 +161,7 @@ def interleave16(wg, wu):
 @pytest.mark.parametrize("B,T,d_in,d_out,x_heads,y_heads,cold", [
     (1, 65, 512, 384, 0, 0, False), (1, 65, 512, 384, 4, 0, True), (2, 50, 256, 1008, 0, 3, False),
     (1, 5, 192, 64, 0, 0, False), (1, 1, 128, 48, 0, 0, False), (4, 89, 320, 400, 0, 0, True), (1, 33, 1024, 2064, 8, 0, True),
+    (1, 89, 512, 2576, 0, 0, True), (1, 96, 1024, 2064, 8, 0, False), (2, 89, 320, 400, 0, 4, True),      # six row groups, one and two blocks
     # many rows: the large-tile kernel's epilogue (192- and 128-row tiles, ragged last column tile, both layouts)
     (16, 65, 128, 2688, 0, 0, False), (4, 89, 192, 6928, 3, 0, False), (16, 65, 128, 2560, 2, 20, False),
     (4, 89, 64, 13840, 0, 0, False)])

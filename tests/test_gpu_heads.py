@@ -49,9 +49,9 @@ def test_bf16_odd_step_counts(M_rows, d, V, K):
     run_case("bf16", M_rows, d, V, K, False, 80 + M_rows)
 
 
-# Up to 80 rows per block with 160 tiles or more: the kernel that fetches 1 KB runs per weight row
+# Up to 96 rows per block with 160 tiles or more: the kernel that fetches 1 KB runs per weight row
 # straight into an LDS ring (super-stages of 512 elements, tiles of 48 to 128 columns).  Row groups
-# 1..5, ragged last tile, one to several super-stages, partial last one, every tile width
+# 1..6, ragged last tile, one to several super-stages, partial last one, every tile width
 # (250 / 200 / 200 / 201 workgroups), reductions shorter than the ring (three sub-stages in all), and
 # two row blocks with a ragged second one.
 @pytest.mark.parametrize("M_rows,d,V,K", [(70, 192, 12800, 2), (33, 704, 25700, 1),
@@ -59,7 +59,8 @@ def test_bf16_odd_step_counts(M_rows, d, V, K):
                                           (64, 64, 25600, 1), (80, 2560, 25601, 1),
                                           (65, 1088, 19190, 1), (40, 576, 12790, 1), (75, 512, 9640, 1),
                                           (10, 64, 7700, 1), (10, 192, 7700, 1), (16, 512, 7700, 1),
-                                          (130, 1024, 6400, 1), (155, 1024, 6400, 1)])
+                                          (130, 1024, 6400, 1), (155, 1024, 6400, 1),
+                                          (89, 1024, 6400, 4), (96, 1600, 25600, 1), (81, 192, 12800, 2)])   # six row groups: the partial tiles pass through LDS in two halves
 def test_bf16_ring_kernel(M_rows, d, V, K):
     assert M.medusa_gemm_plan(M_rows, V, d, K, False)["ring"]
     run_case("bf16", M_rows, d, V, K, False, 90 + M_rows)
