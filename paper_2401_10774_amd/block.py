@@ -7,7 +7,7 @@ kernels.  Argument marshalling only -- every operator runs in the HIP library.
 With one sequence, and W_Q, W_K, W_V handed in as consecutive row blocks of one allocation (views
 of a [(Hq + 2 Hkv) D, h] tensor), the three projections are one tree_linear call: its head-major
 output [1, Hq + 2 Hkv, T, D] is q, k and v back to back.  With ``w_gu`` (binding.interleave_gate_up
-of W_g and W_u) given and at most 160 tree tokens in all, X W_u and X W_g are one
+of W_g and W_u) given and at most 192 tree tokens in all (or a batch that the large-tile kernel takes), X W_u and X W_g are one
 tree_linear_swiglu call and ``self.up`` is not produced."""
 from __future__ import annotations
 
@@ -103,9 +103,11 @@ class SimplifiedBlock:
                                                   self.tree.handle, p(self.attn), B, Hq, Hkv, D, self.Lcap, float(scale),
                                                   code, p(self.ws), nb(self.ws))),
         ]
-        # gate and up in one pass: up to 160 rows (one or two row blocks of the ring kernel) and wherever the
-        # planning gives the stacked projection the large-tile kernel; in between two calls are faster
-        fuse_gu = w_gu is not None and (B * T <= 160 or _b.medusa_gemm_plan(B * T, 2 * inter, Hq * D, 1, False)["kind"] == "big")
+        # gate and up in one pass: up to 192 rows (one or two row blocks of the ring kernel) and wherever the
+        # planning gives the stacked projection the large-tile kernel (measured at 7B and 13B shapes, 65 to 260 rows:
+        # one pass always beats two calls, 45 against 61 us at 89 rows, 77 against 109 at 176); more row blocks of
+        # the ring kernel than two are not measured: two calls then
+        fuse_gu = w_gu is not None and (B * T <= 192 or _b.medusa_gemm_plan(B * T, 2 * inter, Hq * D, 1, False)["kind"] == "big")
         if fuse_gu:
             _b._dev(w_gu, "w_gu", dtype=dt, shape=(2 * inter, Hq * D))
             plan.append(("tree_linear_swiglu", L.tree_linear_swiglu, (p(self.attn), p(w_gu), p(self.act), B, T, Hq * D, inter,

@@ -296,6 +296,8 @@ def test_block_bf16_fused_gate_and_up():
     block_case("bf16", (3, 2, 1), 2, 512, 8, 2, 64, 1024, 700, [600, 37], 605, fused_gate_up=True)       # 2 x 16 rows
     block_case("bf16", (2, 2, 1), 1, 512, 4, 4, 128, 768, 400, [300], 606, adjacent_qkv=True, fused_gate_up=True)
     block_case("bf16", (4, 3, 2, 1), 2, 512, 8, 2, 64, 1024, 700, [600, 37], 607, fused_gate_up=True)    # 130 rows: two row blocks
+    block_case("bf16", (4, 3, 2, 1, 1), 1, 512, 8, 2, 64, 1024, 700, [600], 608, fused_gate_up=True)     # 89 rows: one block of six row groups
+    block_case("bf16", (4, 3, 2, 1, 1), 2, 512, 8, 2, 64, 1024, 700, [37, 600], 609, fused_gate_up=True) # 178 rows: two such blocks
 
 
 def test_block_bf16_batch_with_stacked_projection_weights():
