@@ -369,8 +369,8 @@ int tree_rope(void* q, void* k, const int32_t* position_ids, int B, int Hq, int 
  *   y     [B*T, d_out] token-major, or head-major [B, y_heads, T, d_out/y_heads] when y_heads > 0
  * All device pointers, caller-owned.  bf16 only (MEDUSA_EUNSUPPORTED for fp32: two tree_linear calls
  * do the same there); d_in a multiple of 64, d_out a multiple of 16, B*T <= 4096.  Tuned for up to
- * 160 rows (the tree tokens of one or two sequences) and for batches of trees large enough for the large-tile
- * kernel (medusa_gemm_plan(B*T, 2*d_out, d_in, 1, 0) says kind 3); correct, but slower than two
+ * 192 rows (the tree tokens of one or two sequences) and for batches of trees large enough for the large-tile
+ * kernel (medusa_gemm_plan(B*T, 2*d_out, d_in, 1, 0) says kind 3); correct, but not measured against two
  * tree_linear calls, for row counts in between. */
 int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int B, int T, int d_in, int d_out, int x_heads,
                        int y_heads, int dtype, medusa_stream_t stream);
