@@ -132,6 +132,11 @@ def test_linear_bf16_ring_kernel():
     assert M.medusa_gemm_plan(130, 6400, 1024, 1, True)["m_blocks"] == 2
     linear_case("bf16", 2, 65, 1024, 6400, 8, 50, False, 445)        # two row blocks (interleaved with the column tiles), head-major both sides
     linear_case("bf16", 1, 150, 3072, 4224, 0, 0, True, 446)         # two row blocks, ragged second one, 88 column tiles (no multiple of 8)
+    # two rows of a long reduction and three rows of a matrix of some size leave the wave-per-row kernel for this one
+    assert M.medusa_gemm_plan(2, 4096, 11008, 1, True)["ring"] and M.medusa_gemm_plan(2, 4096, 8192, 1, True)["kind"] == "gemv"
+    linear_case("bf16", 1, 2, 11008, 4096, 0, 0, True, 449)
+    assert M.medusa_gemm_plan(3, 12288, 4096, 1, True)["ring"] and M.medusa_gemm_plan(4, 2048, 2048, 1, True)["kind"] == "gemv"
+    linear_case("bf16", 1, 3, 4096, 12288, 32, 96, False, 450)
     assert M.medusa_gemm_plan(89, 19200, 576, 1, True)["mt"] == 6
     linear_case("bf16", 1, 89, 576, 19200, 0, 150, True, 447)        # six row groups (the 89 tokens of the 13B tree), 96 columns, gated, head-major output
     assert (M.medusa_gemm_plan(192, 5120, 5120, 1, True)["mt"], M.medusa_gemm_plan(192, 5120, 5120, 1, True)["m_blocks"]) == (6, 2)
