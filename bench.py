@@ -60,6 +60,7 @@ def parse_args():
                     help="time the whole verification pass with a stack of --layers simplified decoder blocks in place "
                          "of the single attention call (heads -> top-k/tree -> blocks -> LM head -> acceptance -> commit)")
     ap.add_argument("--layers", type=int, default=0, help="--forward: decoder blocks in the stack (default: the workload's layer count)")
+    ap.add_argument("--batch", type=int, default=0, help="--block: sequences in the batch instead of the workload's (C4 with --batch 1: the 13B block on one 89-token tree)")
     ap.add_argument("--speed-model", action="store_true",
                     help="measure the simplified block at 1..112 candidate tokens and print the appendix's simulated "
                          "speedup for this GPU (its own JSON line)")
@@ -112,6 +113,9 @@ def main():
     cfg = get_config(args.config)
     torch.cuda.set_device(0)
     if args.block:
+        if args.batch > 0:
+            import dataclasses
+            cfg = dataclasses.replace(cfg, B=args.batch)
         bench_block(args, cfg)
         return
     if args.speed_model:
