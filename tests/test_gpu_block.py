@@ -355,3 +355,23 @@ def test_block_replays_under_a_hip_graph():
             assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"replay {replay}"
         blk.run(*args)                         # eager work between the replays
         torch.cuda.synchronize()
+
+
+def _random_linear_shapes():
+    """Seeded shapes across the planning's whole range: 1-400 rows, ragged column counts (multiples of 8), reductions
+    that are any multiple of 64 -- partial last super-stages, ragged last tiles, every kernel family."""
+    rng = np.random.default_rng(20240119)
+    shapes = []
+    while len(shapes) < 40:
+        rows = int(rng.choice([1, 2, 3, 4, 5, 16, 33, 65, 80, 81, 89, 96, 97, 128, 130, 161, 192, 200, 260, 356, 400]))
+        d_in = 64 * int(rng.integers(1, 180))
+        d_out = 8 * int(rng.integers(8, 2600))
+        if rows * d_in * d_out > 6e9:                      # keeps the float64 oracle product to about a second
+            continue
+        shapes.append((rows, d_in, d_out, bool(rng.integers(0, 2)), 700 + len(shapes)))
+    return shapes
+
+
+@pytest.mark.parametrize("rows,d_in,d_out,gated,seed", _random_linear_shapes())
+def test_linear_bf16_random_shapes(rows, d_in, d_out, gated, seed):
+    linear_case("bf16", 1, rows, d_in, d_out, 0, 0, gated, seed)

@@ -107,3 +107,25 @@ def test_run_twice_is_bit_identical():
     a, _ = M.medusa_heads(h, None, w2)
     b, _ = M.medusa_heads(h, None, w2)
     assert torch.equal(a, b)
+
+
+def _random_head_shapes():
+    """Seeded shapes over the whole range of medusa_heads: 1-400 rows, 1-5 heads, any vocabulary size (odd ones take
+    the element-wise epilogue), hidden sizes that are any multiple of 64."""
+    rng = np.random.default_rng(240110774)
+    shapes = []
+    while len(shapes) < 24:
+        rows = int(rng.choice([1, 2, 3, 4, 5, 16, 48, 65, 81, 89, 96, 97, 130, 178, 260, 400]))
+        d = 64 * int(rng.integers(1, 90))
+        V = int(rng.integers(1, 33000))
+        K = int(rng.integers(1, 6))
+        with_w1 = bool(rng.integers(0, 2))
+        if rows * K * d * (V + (d if with_w1 else 0)) > 5e9:      # keeps the float64 oracle to about a second
+            continue
+        shapes.append((rows, d, V, K, with_w1, 300 + len(shapes)))
+    return shapes
+
+
+@pytest.mark.parametrize("M_rows,d,V,K,with_w1,seed", _random_head_shapes())
+def test_bf16_random_shapes(M_rows, d, V, K, with_w1, seed):
+    run_case("bf16", M_rows, d, V, K, with_w1, seed)
