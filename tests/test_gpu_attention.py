@@ -85,3 +85,34 @@ def test_run_twice_is_bit_identical():
     a = M.tree_attention(q, kt, kt, kc, kc, pl, gt, 0.088)
     b = M.tree_attention(q, kt, kt, kc, kc, pl, gt, 0.088)
     assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def _random_attention_cases():
+    """Seeded cases over the kernel's launch shapes: random sparse trees of 1-127 nodes (one to several row blocks per
+    KV head group), batches of 1-48 sequences (split, unsplit, and more workgroups than CUs, which are served longest
+    prefix first), grouped-query ratios 1-8, both head sizes, prefixes from empty to the cache's capacity."""
+    rng = np.random.default_rng(1077401)
+    cases = []
+    for i in range(18):
+        nodes = {()}
+        want = 1 + int(rng.integers(0, 127))
+        while len(nodes) < want:
+            p = list(nodes)[int(rng.integers(len(nodes)))]
+            if len(p) < 6:
+                nodes.add(p + (int(rng.integers(0, 10)),))
+        B = int(rng.choice([1, 1, 2, 3, 5, 8, 17, 48]))
+        Hkv = int(rng.choice([1, 2, 4, 8]))
+        G = int(rng.choice([1, 2, 4, 8]))
+        D = int(rng.choice([64, 128]))
+        Lcap = int(rng.choice([64, 300, 1100, 2500]))
+        if B * Hkv * G * len(nodes) * (Lcap + len(nodes)) * D > 3e9:       # keeps the float64 oracle to a few seconds
+            Lcap = 300
+        prefix = [int(rng.choice([0, 1, Lcap, int(rng.integers(0, Lcap + 1))])) for _ in range(B)]
+        cases.append((sorted(n for n in nodes if n), B, Hkv * G, Hkv, D, Lcap, prefix, 900 + i))
+    return cases
+
+
+@pytest.mark.parametrize("nodes,B,Hq,Hkv,D,Lcap,prefix,seed", _random_attention_cases(),
+                         ids=lambda v: None if isinstance(v, list) else str(v))
+def test_bf16_random_trees_and_batches(nodes, B, Hq, Hkv, D, Lcap, prefix, seed):
+    run_case("bf16", None, B, Hq, Hkv, D, Lcap, prefix, seed, nodes=nodes)
