@@ -219,3 +219,33 @@ def test_kv_commit_never_writes_past_the_capacity():
     assert got[0, 1, :, 2:5].min() == 1.0 and got[0, 1, :, 5].max() == 0.0 and got[0, 1, :, :2].max() == 0.0
     assert float(flat_k[n:].abs().max()) == 0.0 and float(flat_v[n:].abs().max()) == 0.0
     assert pl.cpu().numpy().tolist() == [6, 5]                        # saturates at Lcap
+
+
+def _random_integer_stage_cases():
+    """Seeded cases for the integer stages: random sparse trees of 2-127 nodes, batches of 1-40 sequences, vocabulary
+    sizes from a few dozen to 32000, multiples of four or not (the scans read 16 bytes at a time only for the former)."""
+    rng = np.random.default_rng(774011)
+    cases = []
+    while len(cases) < 14:
+        nodes = {()}
+        want = 2 + int(rng.integers(0, 126))
+        while len(nodes) < want:
+            p = list(nodes)[int(rng.integers(len(nodes)))]
+            if len(p) < 5:
+                nodes.add(p + (int(rng.integers(0, 10)),))
+        B = int(rng.choice([1, 2, 5, 16, 40]))
+        V = int(rng.choice([37, 1000, 4099, 32000, int(rng.integers(16, 33000))]))
+        if B * len(nodes) * V > 3e7:
+            continue
+        cases.append((sorted(n for n in nodes if n), B, V, 500 + len(cases)))
+    return cases
+
+
+@pytest.mark.parametrize("nodes,B,V,seed", _random_integer_stage_cases(), ids=lambda v: None if isinstance(v, list) else str(v))
+def test_random_trees_topk_and_greedy_acceptance(nodes, B, V, seed):
+    gt, ot = both_trees(nodes=nodes)
+    heads = draw_normal(seed, 1, (B, ot.K, V), 1.0, "f32")
+    lm = draw_normal(seed, 2, (B, V), 1.0, "f32")
+    check_topk(gt, ot, heads, lm, np.arange(B, dtype=np.int32) * 3)
+    logits, tokens = planted_logits(np.random.default_rng(seed), ot, B, V)
+    check_accept(gt, ot, logits, tokens, "greedy")
