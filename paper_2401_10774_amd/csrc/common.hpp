@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include "medusa.h"
 
 #define MEDUSA_HIP_TRY(expr)                     \

@@ -1065,13 +1065,13 @@ constexpr int ring_depth(int mt) { return mt >= 6 ? 4 : mt == 5 ? 5 : (10 - mt >
 // 160 KB of a CU): raise the limit once per kernel and device.
 template <void (*Kernel)(GemmArgs)>
 int launch_skinny(dim3 grid, size_t lds, hipStream_t stream, const GemmArgs& a) {
-  static bool raised[64] = {};
+  static std::atomic<bool> raised[64];   // (set after the call succeeded; two threads racing here both make the same call)
   int dev = 0;
   MEDUSA_HIP_TRY(hipGetDevice(&dev));
   if (dev < 0 || dev >= 64) return MEDUSA_EUNSUPPORTED;
-  if (!raised[dev]) {
+  if (!raised[dev].load(std::memory_order_acquire)) {
     MEDUSA_HIP_TRY(hipFuncSetAttribute((const void*)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));   // the largest tile of these kernels
-    raised[dev] = true;
+    raised[dev].store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL(Kernel, grid, dim3(256), lds, stream, a);
   return MEDUSA_OK;

@@ -593,14 +593,14 @@ Plan make_plan(int B, int Hq, int Hkv, int T, int Lcap) {
 // The kernel's LDS tiles exceed the 64 KB a kernel gets by default: raise the limit once per kernel and device.
 template <int D, int NT, int KH, int WPT>
 int launch_rows(const AttnArgs& a, hipStream_t stream) {
-  static bool raised[64] = {};
+  static std::atomic<bool> raised[64];   // (set after the call succeeded; two threads racing here both make the same call)
   int dev = 0;
   MEDUSA_HIP_TRY(hipGetDevice(&dev));
   if (dev < 0 || dev >= 64) return MEDUSA_EUNSUPPORTED;
   const size_t lds = (size_t)(KH == 1 ? 4 : 2) * 2 * KH * kBlkKeys * D * 2 + (size_t)NT * 16 * D * 2 + (size_t)16 * NT * 16;   // the ring of steps + the Q tiles + the rows' ancestor masks
-  if (!raised[dev]) {
+  if (!raised[dev].load(std::memory_order_acquire)) {
     MEDUSA_HIP_TRY(hipFuncSetAttribute((const void*)tree_attn_rows_kernel<D, NT, KH, WPT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    raised[dev] = true;
+    raised[dev].store(true, std::memory_order_release);
   }
   const int units = a.B * a.Hkv * a.n_splits;
   const dim3 grid(8 * ceil_div(units, 8) * a.row_blocks), block(64 * NT * WPT);
