@@ -533,7 +533,8 @@ def bench_speed_model(args, cfg):
     trees = {q: (M.MedusaTree(nodes=[]) if q == 1 else M.MedusaTree(accuracy=acc, n_nodes=q - 1)) for q in qs}
     scale = 1.0 / math.sqrt(D)
     experiments = [("batch 1, prefix 1024", 1, 1024), ("batch 4, prefix 1024", 4, 1024), ("batch 16, prefix 1024", 16, 1024),
-                   ("batch 32, prefix 1024", 32, 1024), ("batch 4, prefix 4096", 4, 4096)]
+                   ("batch 32, prefix 1024", 32, 1024), ("batch 4, prefix 256", 4, 256), ("batch 4, prefix 4096", 4, 4096),
+                   ("batch 4, prefix 8192", 4, 8192)]
     results = {}
     for label, B, s_len in experiments:
         Lcap = s_len + 128
