@@ -375,3 +375,23 @@ def _random_linear_shapes():
 @pytest.mark.parametrize("rows,d_in,d_out,gated,seed", _random_linear_shapes())
 def test_linear_bf16_random_shapes(rows, d_in, d_out, gated, seed):
     linear_case("bf16", 1, rows, d_in, d_out, 0, 0, gated, seed)
+
+
+def _random_swiglu_shapes():
+    """Seeded shapes for the fused gate/up projection: one to several row blocks of the ring kernel (1-6 row groups
+    each), the large-tile kernel's epilogue, outputs that are any multiple of 16, reductions any multiple of 64."""
+    rng = np.random.default_rng(20240774)
+    shapes = []
+    while len(shapes) < 14:
+        rows = int(rng.choice([1, 3, 5, 16, 40, 65, 81, 89, 96, 97, 130, 178, 200, 260, 400]))
+        d_in = 64 * int(rng.integers(1, 100))
+        d_out = 16 * int(rng.integers(1, 900))
+        if rows * d_in * d_out > 2.5e9:                    # keeps the float64 oracle products to about a second
+            continue
+        shapes.append((1, rows, d_in, d_out, 0, 0, bool(rng.integers(0, 2))))
+    return shapes
+
+
+@pytest.mark.parametrize("B,T,d_in,d_out,x_heads,y_heads,cold", _random_swiglu_shapes())
+def test_linear_swiglu_bf16_random_shapes(B, T, d_in, d_out, x_heads, y_heads, cold):
+    test_linear_swiglu_bf16(B, T, d_in, d_out, x_heads, y_heads, cold)
