@@ -533,7 +533,7 @@ def bench_speed_model(args, cfg):
     trees = {q: (M.MedusaTree(nodes=[]) if q == 1 else M.MedusaTree(accuracy=acc, n_nodes=q - 1)) for q in qs}
     scale = 1.0 / math.sqrt(D)
     experiments = [("batch 1, prefix 1024", 1, 1024), ("batch 4, prefix 1024", 4, 1024), ("batch 16, prefix 1024", 16, 1024),
-                   ("batch 32, prefix 1024", 32, 1024), ("batch 4, prefix 256", 4, 256), ("batch 4, prefix 4096", 4, 4096),
+                   ("batch 32, prefix 1024", 32, 1024), ("batch 64, prefix 1024", 64, 1024), ("batch 4, prefix 256", 4, 256), ("batch 4, prefix 4096", 4, 4096),
                    ("batch 4, prefix 8192", 4, 8192)]
     results = {}
     for label, B, s_len in experiments:
@@ -541,7 +541,8 @@ def bench_speed_model(args, cfg):
         caches = [(rnd(B, Hkv, Lcap, D), rnd(B, Hkv, Lcap, D)) for _ in range(max(2, min(n_sets, int(1.5e9 // (4 * B * Hkv * Lcap * D)))))]
         pl = torch.full((B,), s_len, dtype=torch.int32, device="cuda")
         lat = {}
-        for q in qs:
+        qs_here = [q for q in qs if B * trees[q].T <= 4096]          # (the library takes up to 4096 tree tokens per call)
+        for q in qs_here:
             tree = trees[q]
             T = tree.T
             blk = SimplifiedBlock(tree, B, h, Hq, Hkv, D, inter, Lcap, dt)
@@ -570,10 +571,10 @@ def bench_speed_model(args, cfg):
                 groups.append(e0.elapsed_time(e1) / 20 * 1e-3)
             lat[q] = sorted(groups)[1]
             del blk
-        rows = S.simulate_speedup(lambda q: lat[q], qs)
-        roof = S.simulate_speedup(lambda q: S.roofline_latency(shape, B, q, s_len, 2.5e15, 8e12), qs)
+        rows = S.simulate_speedup(lambda q: lat[q], qs_here)
+        roof = S.simulate_speedup(lambda q: S.roofline_latency(shape, B, q, s_len, 2.5e15, 8e12), qs_here)
         results[label] = {"best_candidates": S.best_candidates(rows), "best_speedup": round(max(r["speedup"] for r in rows), 3),
-                          "latency_us": {str(q): round(lat[q] * 1e6, 1) for q in qs},
+                          "latency_us": {str(q): round(lat[q] * 1e6, 1) for q in qs_here},
                           "speedup": {str(r["candidates"]): round(r["speedup"], 3) for r in rows},
                           "roofline_best_candidates": S.best_candidates(roof)}
         print(f"[bench] {label}:", file=sys.stderr)
