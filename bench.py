@@ -60,7 +60,7 @@ def parse_args():
                     help="time the whole verification pass with a stack of --layers simplified decoder blocks in place "
                          "of the single attention call (heads -> top-k/tree -> blocks -> LM head -> acceptance -> commit)")
     ap.add_argument("--layers", type=int, default=0, help="--forward: decoder blocks in the stack (default: the workload's layer count)")
-    ap.add_argument("--batch", type=int, default=0, help="--block: sequences in the batch instead of the workload's (C4 with --batch 1: the 13B block on one 89-token tree)")
+    ap.add_argument("--batch", type=int, default=0, help="sequences in the batch instead of the workload's (C4 with --batch 1: the 13B shapes on one 89-token tree)")
     ap.add_argument("--speed-model", action="store_true",
                     help="measure the simplified block at 1..112 candidate tokens and print the appendix's simulated "
                          "speedup for this GPU (its own JSON line)")
@@ -112,10 +112,10 @@ def main():
         sys.exit(1)
     cfg = get_config(args.config)
     torch.cuda.set_device(0)
+    if args.batch > 0:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, B=args.batch)
     if args.block:
-        if args.batch > 0:
-            import dataclasses
-            cfg = dataclasses.replace(cfg, B=args.batch)
         bench_block(args, cfg)
         return
     if args.speed_model:
@@ -193,7 +193,7 @@ def main():
     dom_bytes = parts["heads_w2"]
     dom_gbs = dom_bytes / (kern_ms * 1e-3) / 1e9
     kernels = per_call_timings(step, cfg, parts, w1_ms, kern_ms)
-    traffic = measured_traffic(cfg.name)
+    traffic = None if args.batch > 0 else measured_traffic(cfg.name)      # (the profiled figure belongs to the workload's own batch size)
 
     out = {
         "metric": "verification steps/sec + achieved HBM GB/s vs peak, 7B shapes, 64-node tree",
