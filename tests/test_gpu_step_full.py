@@ -51,8 +51,11 @@ def topk_gap(logits_row, s):
     return float(np.min(v[:-1] - v[1:])) if v.size > 1 else np.inf
 
 
-def run_config(name, nl=None, plant_seed=None, sparse=False, fused_accept=False):
+def run_config(name, nl=None, plant_seed=None, sparse=False, fused_accept=False, batch=None):
     cfg = get_config(name)
+    if batch is not None:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, B=batch)
     dtype = cfg.dtype
     x = make_step_inputs(cfg, nl=nl)
     x["k_cache"] = poison_tail(x["k_cache"], x["prefix_len"])
@@ -166,6 +169,11 @@ def test_c3_optimized_sparse_tree_typical():
 def test_c4_13b_batch4_ragged():
     a = run_config("C4", nl=8, plant_seed=13)
     assert len(set(a.tolist())) >= 2            # ragged accept lengths compacted per sequence
+
+
+def test_c4_13b_one_sequence():
+    """The 13B shapes with one sequence: five heads at one row, the LM head on the 89 tree rows in one row block."""
+    run_config("C4", nl=4, plant_seed=19, batch=1)
 
 
 def test_c5_gqa_batch16_typical():
