@@ -163,14 +163,18 @@ def interleave16(wg, wu):
     return out
 
 
-@pytest.mark.parametrize("B,T,d_in,d_out,x_heads,y_heads,cold", [
-    (1, 65, 512, 384, 0, 0, False), (1, 65, 512, 384, 4, 0, True), (2, 50, 256, 1008, 0, 3, False),
-    (1, 5, 192, 64, 0, 0, False), (1, 1, 128, 48, 0, 0, False), (4, 89, 320, 400, 0, 0, True), (1, 33, 1024, 2064, 8, 0, True),
-    (1, 89, 512, 2576, 0, 0, True), (1, 96, 1024, 2064, 8, 0, False), (2, 89, 320, 400, 0, 4, True),      # six row groups, one and two blocks
+@pytest.mark.parametrize("B,T,d_in,d_out,x_heads,y_heads", [
+    (1, 65, 512, 384, 0, 0), (1, 65, 512, 384, 4, 0), (2, 50, 256, 1008, 0, 3),
+    (1, 5, 192, 64, 0, 0), (1, 1, 128, 48, 0, 0), (4, 89, 320, 400, 0, 0), (1, 33, 1024, 2064, 8, 0),
+    (1, 89, 512, 2576, 0, 0), (1, 96, 1024, 2064, 8, 0), (2, 89, 320, 400, 0, 4),      # six row groups, one and two blocks
     # many rows: the large-tile kernel's epilogue (192- and 128-row tiles, ragged last column tile, both layouts)
-    (16, 65, 128, 2688, 0, 0, False), (4, 89, 192, 6928, 3, 0, False), (16, 65, 128, 2560, 2, 20, False),
-    (4, 89, 64, 13840, 0, 0, False)])
-def test_linear_swiglu_bf16(B, T, d_in, d_out, x_heads, y_heads, cold):
+    (16, 65, 128, 2688, 0, 0), (4, 89, 192, 6928, 3, 0), (16, 65, 128, 2560, 2, 20),
+    (4, 89, 64, 13840, 0, 0)])
+def test_linear_swiglu_bf16(B, T, d_in, d_out, x_heads, y_heads):
+    swiglu_case(B, T, d_in, d_out, x_heads, y_heads)
+
+
+def swiglu_case(B, T, d_in, d_out, x_heads, y_heads):
     seed = 700 + B * T
     M_rows = B * T
     x = draw_normal(seed, 0, (M_rows, d_in), 1.0, "bf16")
@@ -388,10 +392,10 @@ def _random_swiglu_shapes():
         d_out = 16 * int(rng.integers(1, 900))
         if rows * d_in * d_out > 2.5e9:                    # keeps the float64 oracle products to about a second
             continue
-        shapes.append((1, rows, d_in, d_out, 0, 0, bool(rng.integers(0, 2))))
+        shapes.append((1, rows, d_in, d_out, 0, 0))
     return shapes
 
 
-@pytest.mark.parametrize("B,T,d_in,d_out,x_heads,y_heads,cold", _random_swiglu_shapes())
-def test_linear_swiglu_bf16_random_shapes(B, T, d_in, d_out, x_heads, y_heads, cold):
-    test_linear_swiglu_bf16(B, T, d_in, d_out, x_heads, y_heads, cold)
+@pytest.mark.parametrize("B,T,d_in,d_out,x_heads,y_heads", _random_swiglu_shapes())
+def test_linear_swiglu_bf16_random_shapes(B, T, d_in, d_out, x_heads, y_heads):
+    swiglu_case(B, T, d_in, d_out, x_heads, y_heads)
