@@ -541,7 +541,7 @@ def bench_speed_model(args, cfg):
         caches = [(rnd(B, Hkv, Lcap, D), rnd(B, Hkv, Lcap, D)) for _ in range(max(2, min(n_sets, int(1.5e9 // (4 * B * Hkv * Lcap * D)))))]
         pl = torch.full((B,), s_len, dtype=torch.int32, device="cuda")
         lat = {}
-        qs_here = [q for q in qs if B * trees[q].T <= 4096]          # (the library takes up to 4096 tree tokens per call)
+        qs_here = [q for q in qs if B * trees[q].T <= 16384]         # (the library takes up to 16384 tree tokens per call)
         for q in qs_here:
             tree = trees[q]
             T = tree.T

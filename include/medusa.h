@@ -127,7 +127,7 @@ int medusa_tree_tables(const medusa_tree_t* tree, int32_t* parent, int32_t* dept
  *   resid   [M, K, d]     dtype   workspace written by the call: SiLU(W1 h) + h rounded
  *                                 once to dtype; may be NULL iff w1 == NULL
  *   logits  [M, K, V]     fp32    output
- * Limits: 1 <= M <= 4096, 1 <= K <= 8, d a multiple of 8 (bf16: of 64), d <= 16384, V >= 1.
+ * Limits: 1 <= M <= 16384, 1 <= K <= 8, d a multiple of 8 (bf16: of 64), d <= 16384, V >= 1.
  * -------------------------------------------------------------------------------- */
 int medusa_heads(const void* hidden, const void* w1, const void* w2, void* resid, float* logits,
                  int M, int d, int V, int K, int dtype, medusa_stream_t stream);
@@ -329,7 +329,7 @@ int medusa_carry_over(const void* hidden_tree, const float* verify_logits, const
  *        does for few tree tokens and small d_out so that the whole chip streams the weights; with
  *        NULL or too small a workspace the call still works, unsplit and slower.  Calls that use
  *        the workspace must not overlap on one GPU (the workspace is theirs alone while they run).
- * Limits: B*T <= 4096; d_in (and d_in/x_heads) a multiple of 8 (bf16: of 64); d_out a multiple
+ * Limits: B*T <= 16384; d_in (and d_in/x_heads) a multiple of 8 (bf16: of 64); d_out a multiple
  * of y_heads.  All pointers are device pointers; returns MEDUSA_EINVAL / MEDUSA_EUNSUPPORTED
  * without launching anything when a limit is violated.
  * -------------------------------------------------------------------------------- */
@@ -368,7 +368,7 @@ int tree_rope(void* q, void* k, const int32_t* position_ids, int B, int Hq, int 
  *         prepares once per weight pair)
  *   y     [B*T, d_out] token-major, or head-major [B, y_heads, T, d_out/y_heads] when y_heads > 0
  * All device pointers, caller-owned.  bf16 only (MEDUSA_EUNSUPPORTED for fp32: two tree_linear calls
- * do the same there); d_in a multiple of 64, d_out a multiple of 16, B*T <= 4096.  Tuned for up to
+ * do the same there); d_in a multiple of 64, d_out a multiple of 16, B*T <= 16384.  Tuned for up to
  * 192 rows (the tree tokens of one or two sequences) and for batches of trees large enough for the large-tile
  * kernel (medusa_gemm_plan(B*T, 2*d_out, d_in, 1, 0) says kind 3); correct, but not measured against two
  * tree_linear calls, for row counts in between. */

@@ -18,6 +18,7 @@
 namespace {
 
 constexpr int kMaxSplitTiles = 1024;       // output tiles x heads a split reduction may cover
+constexpr int kMaxRows = 16384;            // activation rows per call (a batch of 128 trees of 128 tokens); grids and 32-bit offsets are sized for it
 
 // ---------------------------------------------------------------------------------------
 // bf16, M <= 4 per block of rows: wave-per-row streaming GEMV.
@@ -1172,7 +1173,7 @@ static int heads_impl(const void* hidden, const void* w1, const void* w2, void* 
   if (!hidden || !w2 || !logits || (w1 && !resid)) return MEDUSA_EINVAL;
   if (M < 1 || d < 1 || V < 1 || K < 1) return MEDUSA_EINVAL;
   if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;
-  if (M > 4096 || K > MEDUSA_MAX_HEADS || d > 16384) return MEDUSA_EUNSUPPORTED;
+  if (M > kMaxRows || K > MEDUSA_MAX_HEADS || d > 16384) return MEDUSA_EUNSUPPORTED;
   if (dtype == MEDUSA_BF16 ? (d % 64 != 0) : (d % 8 != 0)) return MEDUSA_EUNSUPPORTED;
   if ((size_t)M * K * V >= (size_t)1 << 40) return MEDUSA_EUNSUPPORTED;
   hipStream_t stream = (hipStream_t)stream_;
@@ -1289,7 +1290,7 @@ extern "C" int tree_linear_segments(const void* x, const void* w, const void* mu
   }
   if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;
   const long M = (long)B * T;
-  if (M > 4096 || d_in > 65536) return MEDUSA_EUNSUPPORTED;
+  if (M > kMaxRows || d_in > 65536) return MEDUSA_EUNSUPPORTED;
   const int gran = dtype == MEDUSA_BF16 ? 64 : 8;       // reduction elements the kernels fetch as one contiguous piece
   if (d_in % gran != 0) return MEDUSA_EUNSUPPORTED;
   if (x_heads > 0 && (d_in % x_heads != 0 || (d_in / x_heads) % gran != 0)) return MEDUSA_EUNSUPPORTED;
@@ -1335,7 +1336,7 @@ extern "C" int tree_linear_swiglu(const void* x, const void* w_gu, void* y, int 
   if (dtype != MEDUSA_F32 && dtype != MEDUSA_BF16) return MEDUSA_EINVAL;
   if (dtype != MEDUSA_BF16) return MEDUSA_EUNSUPPORTED;            // (fp32 callers use two tree_linear calls)
   const long M = (long)B * T;
-  if (M > 4096 || d_in > 65536 || d_out > (1 << 24)) return MEDUSA_EUNSUPPORTED;
+  if (M > kMaxRows || d_in > 65536 || d_out > (1 << 24)) return MEDUSA_EUNSUPPORTED;
   if (d_in % 64 != 0 || d_out % 16 != 0) return MEDUSA_EUNSUPPORTED;
   if (x_heads > 0 && (d_in % x_heads != 0 || (d_in / x_heads) % 64 != 0)) return MEDUSA_EUNSUPPORTED;
   if (y_heads > 0 && d_out % y_heads != 0) return MEDUSA_EINVAL;

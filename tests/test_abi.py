@@ -91,6 +91,8 @@ def test_argument_checks_happen_on_the_host():
     assert L.medusa_heads(p, None, p, None, p, 1, 72, 10, 1, 1, None) == -2       # bf16 needs d % 64 == 0
     assert L.medusa_heads(p, None, p, None, p, 1, 64, 10, 9, 1, None) == -2       # K > 8
     assert L.medusa_heads(p, None, p, None, p, 1, 64, 10, 1, 7, None) == -1       # unknown dtype
+    assert L.medusa_heads(p, None, p, None, p, 16385, 64, 10, 1, 1, None) == -2   # more rows than a call takes
+    assert L.tree_linear(p, p, None, p, 129, 128, 64, 64, 0, 0, 1, None, 0, None) == -2        # 16512 rows
     assert L.tree_attention(p, p, p, p, p, p, t.handle, p, 1, 4, 3, 128, 64, 1.0, 1, p, 1 << 30, None) == -1
     assert L.tree_attention(p, p, p, p, p, p, t.handle, p, 1, 4, 4, 96, 64, 1.0, 1, p, 1 << 30, None) == -2
     assert L.tree_attention(None, p, p, p, p, p, t.handle, p, 1, 4, 4, 128, 64, 1.0, 1, p, 1 << 30, None) == -1

@@ -399,3 +399,11 @@ def _random_swiglu_shapes():
 @pytest.mark.parametrize("B,T,d_in,d_out,x_heads,y_heads", _random_swiglu_shapes())
 def test_linear_swiglu_bf16_random_shapes(B, T, d_in, d_out, x_heads, y_heads):
     swiglu_case(B, T, d_in, d_out, x_heads, y_heads)
+
+
+def test_linear_bf16_more_than_4096_rows():
+    """64 trees of 65 tokens (4160 rows) and beyond: plain, gated with head-major output, and the fused gate/up projection."""
+    linear_case("bf16", 64, 65, 512, 768, 0, 0, False, 460)
+    linear_case("bf16", 64, 65, 256, 1024, 2, 8, True, 461)
+    linear_case("bf16", 128, 65, 128, 256, 0, 0, False, 462)         # 8320 rows
+    swiglu_case(64, 65, 256, 512, 0, 0)

@@ -129,3 +129,9 @@ def _random_head_shapes():
 @pytest.mark.parametrize("M_rows,d,V,K,with_w1,seed", _random_head_shapes())
 def test_bf16_random_shapes(M_rows, d, V, K, with_w1, seed):
     run_case("bf16", M_rows, d, V, K, with_w1, seed)
+
+
+@pytest.mark.parametrize("M_rows,d,V,K,with_w1", [(4160, 256, 1000, 1, False), (5000, 128, 300, 2, True), (8200, 64, 520, 1, False)])
+def test_bf16_more_than_4096_rows(M_rows, d, V, K, with_w1):
+    """A batch of 64 trees of 65 tokens is 4160 rows: the row limit of a call is 16384."""
+    run_case("bf16", M_rows, d, V, K, with_w1, 400 + M_rows % 100)
