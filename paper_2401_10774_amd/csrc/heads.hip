@@ -877,12 +877,19 @@ GemmPlan plan_gemm(int M, int N, int d, int K, bool have_ws, bool wide_offsets) 
         if (tiles < 120) continue;
         // rounds: the busiest die decides (column tiles go round-robin over 8 dies of 32 CUs: 20 column
         // tiles x 12 row tiles are 240 tiles, yet 36 of them land on each of four dies)
-        // (a last round of only a few workgroups runs faster than a full one: 0.6 + 0.4 x its fill)
+        // (a last round of only a few workgroups runs a little faster than a full one: 0.8 + 0.2 x its fill; N = 5120,
+        // M = 2048 on 192-row tiles puts 33 tiles on four of the dies and takes 1.9 rounds, M = 4160 with 66 takes 2.8)
         const long on_die = (long)ceil_div(ceil_div(N, 256), 8) * ceil_div(M, r) * K;
-        const double die_rounds = on_die <= 32 ? 1.0 : (double)(on_die / 32) + (on_die % 32 ? 0.6 + 0.4 * (on_die % 32) / 32.0 : 0.0);
+        const double die_rounds = on_die <= 32 ? 1.0 : (double)(on_die / 32) + (on_die % 32 ? 0.8 + 0.2 * (on_die % 32) / 32.0 : 0.0);
         const double rounds = die_rounds > (double)((tiles + 255) / 256) ? die_rounds : (double)((tiles + 255) / 256);
-        const double t = (r == 128 ? 68.0 : 88.0) * scale * rounds + 0.6 * w_us;
-        if (t < best) { best = t; pick = GemmPlan::BIG; tall = r == 192; }
+        // (rounds of 128-row tiles get dearer the more of them there are -- 70 us per round at two, 77 at three, 84 at
+        // six, measured at N = 12288 -- while 192-row tiles hold 89-97: M = 4096, N = 12288 ran 507 us on 128-row tiles)
+        const double per_round = r == 128 ? 68.0 + 3.0 * ((rounds < 7.0 ? rounds : 7.0) - 1.0) : 88.0;
+        const double t = per_round * scale * rounds + 0.6 * w_us;
+        // (from five rounds on the 128 x 128 price is the less certain one -- M = 2080, N = 11008 ran 301 us there
+        // against 244 on 192-row tiles, priced 252 and 256 -- so it has to win by a twentieth)
+        const double margin = pick == GemmPlan::SQUARE && sq_tiles > 4 * 256 ? 1.0 / 0.95 : 1.0;
+        if (t < best * margin) { best = t; pick = GemmPlan::BIG; tall = r == 192; }
       }
       // A long reduction into few large tiles (the down projection of a batch of trees: M = 1040,
       // 11008 -> 4096 is 96 tiles of 192 x 256) can be split over 2 or 4 workgroups per tile when there
